@@ -1,0 +1,84 @@
+"""Seeded tensor generators.
+
+Every tensor comes from `numpy.random.default_rng(cfg.seed)` split into
+independent child streams in a fixed order, so a given configuration always
+yields the same bits no matter which consumer asks or in which order:
+
+    child 0..m-1 : full-precision weight matrices, in `cfg.matrices()` order
+    child m      : router first layer
+    child m+1    : router second layer
+    child m+2    : activations
+
+Activations are stored at the library boundary as bfloat16.  The only
+arithmetic here is the storage conversion fp32 -> bf16 bits (round to
+nearest even) and back, which defines the input values themselves.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+
+from .configs import WorkloadConfig
+
+_N_STREAMS = 8
+
+
+def _streams(cfg: WorkloadConfig):
+    return np.random.default_rng(cfg.seed).spawn(_N_STREAMS)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 array -> uint16 bfloat16 bit patterns, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """uint16 bfloat16 bit patterns -> the fp32 values they denote (exact)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def make_fp_weights(cfg: WorkloadConfig) -> Dict[str, np.ndarray]:
+    """The shared full-precision weights, fp32 [out, in] ~ N(0, w_std)."""
+    ss = _streams(cfg)
+    out = {}
+    for i, (name, (n, k)) in enumerate(cfg.matrices().items()):
+        w = ss[i].standard_normal((n, k), dtype=np.float32)
+        w *= np.float32(cfg.w_std)
+        out[name] = w
+    return out
+
+
+def make_router(cfg: WorkloadConfig) -> Dict[str, Optional[np.ndarray]]:
+    """Router weights, fp32.  hidden == 0: only w2 [K, D].  Biases are zero except cfg.router_bias."""
+    ss = _streams(cfg)
+    m = len(cfg.matrices())
+    K, D, Hd = cfg.K, cfg.D, cfg.router_hidden
+    r: Dict[str, Optional[np.ndarray]] = {"w1": None, "b1": None}
+    if Hd:
+        r["w1"] = (ss[m].standard_normal((Hd, D), dtype=np.float32) * np.float32(cfg.router_w_std))
+        r["b1"] = np.zeros(Hd, dtype=np.float32)
+        w2 = ss[m + 1].standard_normal((K, Hd), dtype=np.float32) * np.float32(cfg.router_w_std)
+        # The hidden units are non-negative after the ReLU, so a row's sum would act as a large
+        # per-expert constant and one expert would take most samples.  Rows are drawn zero-sum to
+        # keep the routing of a random router roughly uniform, as the workloads call for.
+        w2 -= w2.mean(axis=1, keepdims=True, dtype=np.float32)
+        r["w2"] = w2
+    else:
+        r["w2"] = (ss[m + 1].standard_normal((K, D), dtype=np.float32) * np.float32(cfg.router_w_std))
+    b2 = np.zeros(K, dtype=np.float32)
+    if cfg.router_bias:
+        b2[:] = np.asarray(cfg.router_bias, dtype=np.float32)
+    r["b2"] = b2
+    return r
+
+
+def make_activations(cfg: WorkloadConfig, S: Optional[int] = None) -> np.ndarray:
+    """Activations ~ N(0,1) as bfloat16 bit patterns, uint16 [S, T, D] (conv: [S, H, W, C] flattened to T=H*W)."""
+    ss = _streams(cfg)
+    m = len(cfg.matrices())
+    S = cfg.S if S is None else S
+    x = ss[m + 2].standard_normal((S, cfg.T, cfg.D), dtype=np.float32)
+    return f32_to_bf16_bits(x)

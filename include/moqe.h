@@ -1,0 +1,223 @@
+/*
+ * moqe.h - C ABI of the MI355X (gfx950) library for the routed forward pass through
+ * K quantization experts (MoQE, arXiv 2508.09204).
+ *
+ * The operation.  MoQE keeps several quantized variants ("quantization experts") of one
+ * full-precision model.  A router model scores each data sample (a sequence, an image),
+ * ONE expert is selected per sample, and that expert alone performs the inference on it
+ * (Section 3.1, Figure 1; the system's prediction is f_{r(x)}(x), appendix on router
+ * convergence; every input activates exactly one expert, appendix on the number of
+ * experts).  This library runs that pattern for a BATCH of samples with all experts
+ * resident: score and select (moqe_route), group samples by expert (moqe_bucket; its
+ * counts are the n_i of Eq. 2), run each group through its expert's low-bit weights
+ * (moqe_grouped_qgemm) and put results back in the caller's order; moqe_forward chains
+ * these for one block.  The per-sample result is the same as serving samples one by one.
+ *
+ * Conventions (all entry points).
+ *  - Return value: 0 on success, a negative MOQE_E_* code on failure.  On failure nothing
+ *    has been enqueued.  moqe_last_error_string() gives a thread-local description.
+ *  - Pointers named in "device" comments are DEVICE pointers owned by the caller; the
+ *    library never allocates, frees or retains device memory.  Descriptor structs
+ *    (moqe_qmat, moqe_router, moqe_block, moqe_aux) and arrays of them are HOST memory,
+ *    read during the call only.  Scratch memory is a caller-provided device workspace
+ *    whose size comes from the matching *_workspace_bytes query; it must be 256-byte
+ *    aligned and may be reused between calls on the same stream.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work on it and never synchronise the host.
+ *  - Activations are bfloat16 (raw 16-bit patterns), row-major.  A "sample" owns T
+ *    consecutive rows; M = S*T.  Weight matrices are [n, k] = [out, in], groups run
+ *    along k.
+ *  - Shapes accepted by the packed layout: n % 16 == 0, k % 128 == 0.
+ */
+#ifndef MOQE_H
+#define MOQE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOQE_OK             0
+#define MOQE_E_NULL        (-1)  /* a required pointer is NULL */
+#define MOQE_E_SHAPE       (-2)  /* bad size, alignment or inconsistent shapes */
+#define MOQE_E_FORMAT      (-3)  /* unsupported bits / group / symmetry / layout / act_mode */
+#define MOQE_E_WORKSPACE   (-4)  /* workspace missing, misaligned or too small */
+#define MOQE_E_HIP         (-5)  /* the HIP runtime reported an error */
+
+#define MOQE_MAX_EXPERTS   16
+
+#define MOQE_LAYOUT_CANONICAL 0  /* one code per byte, row-major [n, k] */
+#define MOQE_LAYOUT_PACKED    1  /* the device layout written by moqe_pack_qmat */
+
+#define MOQE_KIND_LINEAR    0
+#define MOQE_KIND_SILU_MLP  1
+#define MOQE_KIND_CONV3X3   2
+
+/* One quantized weight matrix of one expert.  The real weight is scale * (code - zero).
+ *
+ * Supported formats (the paper names Int8 and Int4 experts, Sections 4.1-4.3; the formats
+ * themselves are round-to-nearest ones):
+ *   symmetric per output channel, bits 8 / 6 / 4: group = 0, zero = NULL, codes signed in
+ *     [-(2^(bits-1)-1), 2^(bits-1)-1];
+ *   asymmetric group-wise, bits 4 / 3: group = 64 or 128 along k, codes in [0, 2^bits-1],
+ *     zero in the same range.
+ * Canonical layout: qdata is int8 (symmetric) or uint8 (asymmetric), [n, k] row-major;
+ *   scale is float [n] (group 0) or [n, k/group]; zero is uint8 with the shape of scale.
+ * Packed layout: qdata is the blob written by moqe_pack_qmat (codes, scales and
+ *   zero-points inside); scale and zero are ignored and may be NULL.
+ * act_mode 1 (int8 per-channel symmetric only): activations are quantized per row to
+ *   int8 with a dynamic scale and the product runs on integer matrix cores (W8A8). */
+typedef struct moqe_qmat {
+  const void*    qdata;      /* device */
+  const float*   scale;      /* device */
+  const uint8_t* zero;       /* device, NULL when symmetric */
+  int32_t n, k;
+  int32_t bits;              /* 8, 6, 4, 3 */
+  int32_t group;             /* 0, 64, 128 */
+  int32_t symmetric;         /* 0 / 1 */
+  int32_t act_mode;          /* 0: bf16 activations, 1: per-row dynamic int8 activations */
+  int32_t layout;            /* MOQE_LAYOUT_* */
+} moqe_qmat;
+
+/* Router: mean-pool the sample's rows, then [Linear(d->h), ReLU,] Linear(->K) giving one
+ * logit per expert (the router ends in an MLP that maps features to routing logits,
+ * Section 3.2).  h == 0: single linear layer, w1/b1 unused.  Weights fp32 row-major
+ * [out, in]; biases may be NULL. */
+typedef struct moqe_router {
+  const float* w1; const float* b1;   /* device, [h, d], [h] */
+  const float* w2; const float* b2;   /* device, [K, h or d], [K] */
+  int32_t d, h, n_experts;
+} moqe_router;
+
+/* One routed block.  w0/w1/w2 are host arrays of n_experts PACKED matrices.
+ *   LINEAR   : y = x W0^T.                         x [S*T, d], y [S*T, n]
+ *   SILU_MLP : h = bf16(silu(x Wg^T) * (x Wu^T)), y = h Wd^T with w0 = gate, w1 = up,
+ *              w2 = down; gate and up of an expert share one format.
+ *   CONV3X3  : per image, 3x3 convolution, stride 1, zero padding 1, no bias.  x is NHWC
+ *              [S, img_h, img_w, cin] (T = img_h*img_w), w0[e] is [cout, cin*9] with
+ *              k = c*9 + kh*3 + kw; y is NHWC fp32. */
+typedef struct moqe_block {
+  int32_t kind;
+  moqe_router router;
+  const moqe_qmat* w0;
+  const moqe_qmat* w1;
+  const moqe_qmat* w2;
+  int32_t n_experts;
+  int32_t img_h, img_w, cin;          /* CONV3X3 only */
+} moqe_block;
+
+/* Optional extra outputs of moqe_forward (any member may be NULL; all device). */
+typedef struct moqe_aux {
+  int32_t* expert_idx;   /* [S]    selected expert per sample */
+  float*   logits;       /* [S, K] router logits */
+  int32_t* counts;       /* [K]    samples per expert (n_i of Eq. 2) */
+  int32_t* offsets;      /* [K+1]  exclusive prefix sum of counts */
+  int32_t* perm;         /* [S]    bucket slot -> sample */
+  int32_t* inv_perm;     /* [S]    sample -> bucket slot */
+  void*    h;            /* SILU_MLP: the bf16 intermediate [S*T, F] in bucket order */
+} moqe_aux;
+
+const char* moqe_version(void);
+const char* moqe_last_error_string(void);
+
+/* When on, entry points validate their arguments and return without touching the GPU. */
+void moqe_set_dry_run(int32_t on);
+
+/* ---- routing ------------------------------------------------------------------------ */
+
+/* Scores each sample and takes the top-1 expert (Section 3.1: the router decides which
+ * expert is activated).  x: device bf16 [S*T, r->d].  expert_idx: device int32 [S];
+ * among equal maxima the lowest index wins.  logits: device float [S, K] or NULL.
+ * Pooling and both layers accumulate in fp32. */
+size_t  moqe_route_workspace_bytes(int32_t S, int32_t T, const moqe_router* r);
+int32_t moqe_route(const void* x, int32_t S, int32_t T, const moqe_router* r,
+                   int32_t* expert_idx, float* logits,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Groups samples by expert with a stable counting sort (the per-expert dispatch counts
+ * n_i of Eq. 2 and the permutation that makes each expert's samples contiguous).
+ *   counts[k] = #{s : e[s] = k};  offsets = exclusive prefix sum, offsets[K] = S;
+ *   inv_perm[s] = offsets[e[s]] + #{s' < s : e[s'] = e[s]};  perm[inv_perm[s]] = s.
+ * expert_idx values must lie in [0, K); K <= MOQE_MAX_EXPERTS.  All arrays device int32;
+ * counts, perm or inv_perm may be NULL.  Results are deterministic. */
+int32_t moqe_bucket(const int32_t* expert_idx, int32_t S, int32_t K,
+                    int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                    void* stream);
+
+/* ---- expert weights ----------------------------------------------------------------- */
+
+/* Round-to-nearest quantization of a device fp32 matrix w [n, k] into the canonical layout
+ * (how the workloads derive their experts from one full-precision model, Section 3.1).
+ * fp32 IEEE arithmetic, ties to even:
+ *   symmetric : s = max|w_row| / qmax (1 if 0), q = clamp(rint(w / s), -qmax, qmax)
+ *   asymmetric: lo = clip*min(min,0), hi = clip*max(max,0), s = (hi-lo)/(2^bits-1) (1 if 0),
+ *               z = clamp(rint(-lo/s)), q = clamp(rint(w/s) + z)
+ * out->qdata/scale/zero must point to device buffers of the canonical sizes; the other
+ * fields of `out` give the format. */
+int32_t moqe_quantize_rtn(const float* w, float clip, const moqe_qmat* out, void* stream);
+
+/* Size of the packed blob for a format; 0 if the format or shape is not supported. */
+size_t  moqe_packed_bytes(int32_t n, int32_t k, int32_t bits, int32_t group,
+                          int32_t symmetric, int32_t act_mode);
+
+/* canonical -> packed.  packed_out: device, `bytes` >= moqe_packed_bytes(...), 256-byte aligned. */
+int32_t moqe_pack_qmat(const moqe_qmat* canonical, void* packed_out, size_t bytes, void* stream);
+
+/* packed -> the integer weights code - zero as device int16 [n, k] (for exact checks), and
+ * optionally the scales in canonical shape (scale_out device float, may be NULL). */
+int32_t moqe_unpack_qmat(const moqe_qmat* packed, int16_t* q_minus_z, float* scale_out, void* stream);
+
+/* ---- grouped dequantize-GEMM -------------------------------------------------------- */
+
+/* For every expert e and every row r of its bucket: y_row = a_row * W_e^T, where the
+ * bucket of expert e is the samples perm[offsets[e] .. offsets[e+1]) and each sample brings
+ * its T rows (each sample is processed by its selected expert only, Section 3.1).
+ *   a       device bf16 [S*T, k], rows in the caller's order when perm != NULL (gathered on
+ *           load), or already in bucket order when perm == NULL.
+ *   offsets device int32 [K+1] in samples;  perm device int32 [S] or NULL.
+ *   experts host array of K packed matrices with equal n and k.
+ *   y       device float [S*T, n]; scatter = 1 writes each row at its caller-order position
+ *           (needs perm), scatter = 0 writes bucket order.
+ * The integer codes enter bf16 matrix cores exactly and the fp32 scale is applied to fp32
+ * partial sums per group, so no weight is rounded.  act_mode 1 experts quantize their rows
+ * to int8 first (workspace). */
+size_t  moqe_grouped_qgemm_workspace_bytes(const moqe_qmat* experts, int32_t K, int32_t S, int32_t T);
+int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t* perm,
+                           int32_t S, int32_t T, const moqe_qmat* experts, int32_t K,
+                           void* y, int32_t scatter,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- the whole block ---------------------------------------------------------------- */
+
+/* y_s = f_{r(x_s)}(x_s) for all samples of the batch: route, bucket, grouped qGEMM(s) with
+ * the fused SiLU gate, scatter back.  x: device bf16 [S*T, d]; y: device float [S*T, n_out]
+ * in the caller's order.  aux may be NULL. */
+size_t  moqe_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T);
+int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y,
+                     const moqe_aux* aux, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- timing ------------------------------------------------------------------------- */
+
+/* Per-kernel timing with HIP events recorded on the stream the kernels are launched on.
+ * moqe_profile_enable(1) starts recording (one event pair per launch, at most
+ * MOQE_PROFILE_MAX_LAUNCHES launches are kept); moqe_profile_read synchronises the recorded
+ * events and returns, for the kernel kind `kind` (MOQE_PK_*), the number of launches seen
+ * and their summed duration in milliseconds; moqe_profile_enable(0) stops and discards. */
+#define MOQE_PK_ROUTE      0
+#define MOQE_PK_BUCKET     1
+#define MOQE_PK_GEMM_GATEUP 2
+#define MOQE_PK_GEMM_PLAIN 3
+#define MOQE_PK_ACTQUANT   4
+#define MOQE_PK_IM2COL     5
+#define MOQE_PK_OTHER      6
+#define MOQE_PK_COUNT      7
+#define MOQE_PROFILE_MAX_LAUNCHES 65536
+int32_t moqe_profile_enable(int32_t on);
+int32_t moqe_profile_read(int32_t kind, int32_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOQE_H */

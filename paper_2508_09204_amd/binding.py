@@ -1,0 +1,292 @@
+"""ctypes binding of libmoqe.so: the functions of include/moqe.h under the same names.
+
+Argument marshalling only: every step of the routed forward pass runs inside the HIP
+library.  PyTorch appears here for device memory (tensors own the buffers) and for the
+current stream handle.  If the shared library is missing, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoqe.so")
+
+MOQE_MAX_EXPERTS = 16
+LAYOUT_CANONICAL, LAYOUT_PACKED = 0, 1
+KIND_LINEAR, KIND_SILU_MLP, KIND_CONV3X3 = 0, 1, 2
+PK_ROUTE, PK_BUCKET, PK_GEMM_GATEUP, PK_GEMM_PLAIN, PK_ACTQUANT, PK_IM2COL, PK_OTHER = range(7)
+
+
+class MoqeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"moqe error {code}: {msg}")
+        self.code = code
+
+
+class _QMat(C.Structure):
+    _fields_ = [("qdata", C.c_void_p), ("scale", C.c_void_p), ("zero", C.c_void_p),
+                ("n", C.c_int32), ("k", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
+                ("symmetric", C.c_int32), ("act_mode", C.c_int32), ("layout", C.c_int32)]
+
+
+class _Router(C.Structure):
+    _fields_ = [("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p),
+                ("d", C.c_int32), ("h", C.c_int32), ("n_experts", C.c_int32)]
+
+
+class _Block(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("router", _Router),
+                ("w0", C.POINTER(_QMat)), ("w1", C.POINTER(_QMat)), ("w2", C.POINTER(_QMat)),
+                ("n_experts", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32), ("cin", C.c_int32)]
+
+
+class _Aux(C.Structure):
+    _fields_ = [("expert_idx", C.c_void_p), ("logits", C.c_void_p), ("counts", C.c_void_p),
+                ("offsets", C.c_void_p), ("perm", C.c_void_p), ("inv_perm", C.c_void_p), ("h", C.c_void_p)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2508_09204_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    sig = {
+        "moqe_version": (C.c_char_p, []),
+        "moqe_last_error_string": (C.c_char_p, []),
+        "moqe_set_dry_run": (None, [i32]),
+        "moqe_route_workspace_bytes": (sz, [i32, i32, C.POINTER(_Router)]),
+        "moqe_route": (i32, [vp, i32, i32, C.POINTER(_Router), vp, vp, vp, sz, vp]),
+        "moqe_bucket": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
+        "moqe_quantize_rtn": (i32, [vp, C.c_float, C.POINTER(_QMat), vp]),
+        "moqe_packed_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
+        "moqe_pack_qmat": (i32, [C.POINTER(_QMat), vp, sz, vp]),
+        "moqe_unpack_qmat": (i32, [C.POINTER(_QMat), vp, vp, vp]),
+        "moqe_grouped_qgemm_workspace_bytes": (sz, [C.POINTER(_QMat), i32, i32, i32]),
+        "moqe_grouped_qgemm": (i32, [vp, vp, vp, i32, i32, C.POINTER(_QMat), i32, vp, i32, vp, sz, vp]),
+        "moqe_workspace_bytes": (sz, [C.POINTER(_Block), i32, i32]),
+        "moqe_forward": (i32, [C.POINTER(_Block), vp, i32, i32, vp, C.POINTER(_Aux), vp, sz, vp]),
+        "moqe_profile_enable": (i32, [i32]),
+        "moqe_profile_read": (i32, [i32, C.POINTER(i32), C.POINTER(C.c_double)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+lib = _load()
+EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
+            "moqe_route", "moqe_bucket", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
+            "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
+            "moqe_workspace_bytes", "moqe_forward", "moqe_profile_enable", "moqe_profile_read"]
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise MoqeError(rc, lib.moqe_last_error_string().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+
+
+# --------------------------------------------------------------------------------------
+# Descriptors that keep their tensors alive
+# --------------------------------------------------------------------------------------
+@dataclass
+class QMat:
+    """A quantized matrix on the device.  Canonical: qdata int8/uint8 [n,k], scale, zero.
+    Packed: qdata is the uint8 blob from moqe_pack_qmat."""
+    qdata: torch.Tensor
+    scale: Optional[torch.Tensor]
+    zero: Optional[torch.Tensor]
+    n: int
+    k: int
+    bits: int
+    group: int
+    symmetric: bool
+    act_mode: int = 0
+    layout: int = LAYOUT_CANONICAL
+
+    def c(self) -> _QMat:
+        return _QMat(_ptr(self.qdata), _ptr(self.scale), _ptr(self.zero), self.n, self.k, self.bits, self.group,
+                     int(self.symmetric), self.act_mode, self.layout)
+
+
+@dataclass
+class Router:
+    w1: Optional[torch.Tensor]
+    b1: Optional[torch.Tensor]
+    w2: torch.Tensor
+    b2: Optional[torch.Tensor]
+    d: int
+    h: int
+    n_experts: int
+
+    def c(self) -> _Router:
+        return _Router(_ptr(self.w1), _ptr(self.b1), _ptr(self.w2), _ptr(self.b2), self.d, self.h, self.n_experts)
+
+
+@dataclass
+class Block:
+    kind: int
+    router: Router
+    w0: List[QMat]
+    w1: Optional[List[QMat]] = None
+    w2: Optional[List[QMat]] = None
+    img_h: int = 0
+    img_w: int = 0
+    cin: int = 0
+    _keep: list = field(default_factory=list, repr=False)
+
+    def c(self) -> _Block:
+        def arr(ms):
+            if ms is None:
+                return None
+            a = (_QMat * len(ms))(*[m.c() for m in ms])
+            self._keep.append(a)
+            return a
+        self._keep.clear()
+        return _Block(self.kind, self.router.c(), arr(self.w0), arr(self.w1), arr(self.w2), len(self.w0),
+                      self.img_h, self.img_w, self.cin)
+
+
+@dataclass
+class Aux:
+    expert_idx: Optional[torch.Tensor] = None
+    logits: Optional[torch.Tensor] = None
+    counts: Optional[torch.Tensor] = None
+    offsets: Optional[torch.Tensor] = None
+    perm: Optional[torch.Tensor] = None
+    inv_perm: Optional[torch.Tensor] = None
+    h: Optional[torch.Tensor] = None
+
+    def c(self) -> _Aux:
+        return _Aux(_ptr(self.expert_idx), _ptr(self.logits), _ptr(self.counts), _ptr(self.offsets),
+                    _ptr(self.perm), _ptr(self.inv_perm), _ptr(self.h))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# --------------------------------------------------------------------------------------
+# The entry points (same names as the C ABI)
+# --------------------------------------------------------------------------------------
+def moqe_version() -> str:
+    return lib.moqe_version().decode()
+
+
+def moqe_set_dry_run(on: bool) -> None:
+    lib.moqe_set_dry_run(int(on))
+
+
+def moqe_route_workspace_bytes(S: int, T: int, router: Router) -> int:
+    r = router.c()
+    return lib.moqe_route_workspace_bytes(S, T, C.byref(r))
+
+
+def moqe_route(x: torch.Tensor, S: int, T: int, router: Router, expert_idx: torch.Tensor,
+               logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    r = router.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_route_workspace_bytes(S, T, C.byref(r)), x.device)
+    _check(lib.moqe_route(_ptr(x), S, T, C.byref(r), _ptr(expert_idx), _ptr(logits), _ptr(workspace),
+                          workspace.numel(), _stream()))
+
+
+def moqe_bucket(expert_idx: torch.Tensor, S: int, K: int, counts: Optional[torch.Tensor], offsets: torch.Tensor,
+                perm: Optional[torch.Tensor], inv_perm: Optional[torch.Tensor]) -> None:
+    _check(lib.moqe_bucket(_ptr(expert_idx), S, K, _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _stream()))
+
+
+def moqe_quantize_rtn(w: torch.Tensor, clip: float, out: QMat) -> None:
+    o = out.c()
+    _check(lib.moqe_quantize_rtn(_ptr(w), float(clip), C.byref(o), _stream()))
+
+
+def moqe_packed_bytes(n: int, k: int, bits: int, group: int, symmetric: bool, act_mode: int = 0) -> int:
+    return lib.moqe_packed_bytes(n, k, bits, group, int(symmetric), act_mode)
+
+
+def moqe_pack_qmat(canonical: QMat, packed_out: torch.Tensor) -> None:
+    c = canonical.c()
+    _check(lib.moqe_pack_qmat(C.byref(c), _ptr(packed_out), packed_out.numel(), _stream()))
+
+
+def moqe_unpack_qmat(packed: QMat, q_minus_z: torch.Tensor, scale_out: Optional[torch.Tensor] = None) -> None:
+    p = packed.c()
+    _check(lib.moqe_unpack_qmat(C.byref(p), _ptr(q_minus_z), _ptr(scale_out), _stream()))
+
+
+def moqe_grouped_qgemm_workspace_bytes(experts: Sequence[QMat], S: int, T: int) -> int:
+    arr = (_QMat * len(experts))(*[m.c() for m in experts])
+    return lib.moqe_grouped_qgemm_workspace_bytes(arr, len(experts), S, T)
+
+
+def moqe_grouped_qgemm(a: torch.Tensor, offsets: torch.Tensor, perm: Optional[torch.Tensor], S: int, T: int,
+                       experts: Sequence[QMat], y: torch.Tensor, scatter: bool,
+                       workspace: Optional[torch.Tensor] = None) -> None:
+    arr = (_QMat * len(experts))(*[m.c() for m in experts])
+    if workspace is None:
+        workspace = _workspace(lib.moqe_grouped_qgemm_workspace_bytes(arr, len(experts), S, T), a.device)
+    _check(lib.moqe_grouped_qgemm(_ptr(a), _ptr(offsets), _ptr(perm), S, T, arr, len(experts), _ptr(y),
+                                  int(scatter), _ptr(workspace), workspace.numel(), _stream()))
+
+
+def moqe_workspace_bytes(blk: Block, S: int, T: int) -> int:
+    b = blk.c()
+    return lib.moqe_workspace_bytes(C.byref(b), S, T)
+
+
+def moqe_forward(blk: Block, x: torch.Tensor, S: int, T: int, y: torch.Tensor, aux: Optional[Aux] = None,
+                 workspace: Optional[torch.Tensor] = None) -> None:
+    b = blk.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_workspace_bytes(C.byref(b), S, T), x.device)
+    a = aux.c() if aux is not None else None
+    _check(lib.moqe_forward(C.byref(b), _ptr(x), S, T, _ptr(y), C.byref(a) if a is not None else None,
+                            _ptr(workspace), workspace.numel(), _stream()))
+
+
+def moqe_profile_enable(on: bool) -> None:
+    _check(lib.moqe_profile_enable(int(on)))
+
+
+def moqe_profile_read(kind: int):
+    n = C.c_int32(0)
+    ms = C.c_double(0.0)
+    _check(lib.moqe_profile_read(kind, C.byref(n), C.byref(ms)))
+    return n.value, ms.value
+
+
+class ForwardCall:
+    """moqe_forward with its arguments marshalled once; calling it only enqueues the work."""
+
+    def __init__(self, blk: Block, x: torch.Tensor, S: int, T: int, y: torch.Tensor, aux: Optional[Aux] = None,
+                 workspace: Optional[torch.Tensor] = None):
+        self._blk_c = blk.c()
+        self._keep = (blk, x, y, aux)
+        if workspace is None:
+            workspace = _workspace(lib.moqe_workspace_bytes(C.byref(self._blk_c), S, T), x.device)
+        self.workspace = workspace
+        self._aux_c = aux.c() if aux is not None else None
+        self._args = (C.byref(self._blk_c), _ptr(x), S, T, _ptr(y),
+                      C.byref(self._aux_c) if self._aux_c is not None else None,
+                      _ptr(workspace), workspace.numel())
+
+    def __call__(self, stream: Optional[int] = None) -> None:
+        rc = lib.moqe_forward(*self._args, _stream() if stream is None else stream)
+        if rc != 0:
+            _check(rc)

@@ -1,0 +1,448 @@
+// C-ABI entry points: argument validation on the host, workspace carving, kernel sequencing.
+// Nothing here allocates device memory or synchronises the host (moqe_profile_read aside).
+#include "moqe_internal.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <atomic>
+#include <mutex>
+#include <vector>
+
+namespace moqe {
+
+static thread_local char g_err[512] = "";
+static std::atomic<int> g_dry{0};
+
+int32_t set_error(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool dry_run() { return g_dry.load() != 0; }
+
+int32_t check_launch(const char* what) {
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return set_error(MOQE_E_HIP, "%s: launch failed: %s", what, hipGetErrorString(err));
+  return MOQE_OK;
+}
+
+// ---- profiling ---------------------------------------------------------------------------
+struct ProfRec { hipEvent_t a, b; int kind; };
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof;
+
+ProfileScope::ProfileScope(int kind, hipStream_t s) : slot(-1), stream(s) {
+  if (!g_prof_on) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (!g_prof_on || g_prof.size() >= MOQE_PROFILE_MAX_LAUNCHES) return;
+  ProfRec r;
+  r.kind = kind;
+  if (hipEventCreate(&r.a) != hipSuccess) return;
+  if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
+  (void)hipEventRecord(r.a, s);
+  g_prof.push_back(r);
+  slot = int(g_prof.size()) - 1;
+}
+
+ProfileScope::~ProfileScope() {
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (slot < int(g_prof.size())) (void)hipEventRecord(g_prof[slot].b, stream);
+}
+
+static void prof_clear_locked() {
+  for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_prof.clear();
+}
+
+// ---- validation helpers --------------------------------------------------------------------
+static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+static int32_t check_qmat_format(const moqe_qmat& m, PackedInfo* pi, const char* who) {
+  if (!packed_info(m.n, m.k, m.bits, m.group, m.symmetric, m.act_mode, pi)) {
+    if (m.n <= 0 || m.k <= 0 || m.n % 16 || m.k % 128)
+      return set_error(MOQE_E_SHAPE, "%s: matrix %d x %d needs n %% 16 == 0 and k %% 128 == 0", who, m.n, m.k);
+    return set_error(MOQE_E_FORMAT, "%s: unsupported format bits=%d group=%d symmetric=%d act_mode=%d", who, m.bits,
+                     m.group, m.symmetric, m.act_mode);
+  }
+  return MOQE_OK;
+}
+
+static int32_t check_packed(const moqe_qmat& m, PackedInfo* pi, const char* who) {
+  int32_t rc = check_qmat_format(m, pi, who);
+  if (rc) return rc;
+  if (m.layout != MOQE_LAYOUT_PACKED) return set_error(MOQE_E_FORMAT, "%s: matrix must be in the packed layout", who);
+  if (!m.qdata) return set_error(MOQE_E_NULL, "%s: qdata is NULL", who);
+  if (!aligned(m.qdata, 256)) return set_error(MOQE_E_SHAPE, "%s: packed blob must be 256-byte aligned", who);
+  return MOQE_OK;
+}
+
+static int32_t check_router(const moqe_router* r, const char* who) {
+  if (!r) return set_error(MOQE_E_NULL, "%s: router is NULL", who);
+  if (r->n_experts < 1 || r->n_experts > MOQE_MAX_EXPERTS)
+    return set_error(MOQE_E_SHAPE, "%s: n_experts %d outside [1, %d]", who, r->n_experts, MOQE_MAX_EXPERTS);
+  if (r->d <= 0 || r->d % 8) return set_error(MOQE_E_SHAPE, "%s: router input dim %d must be a positive multiple of 8", who, r->d);
+  if (r->h < 0 || r->h % 4) return set_error(MOQE_E_SHAPE, "%s: router hidden dim %d must be a multiple of 4", who, r->h);
+  if (!r->w2) return set_error(MOQE_E_NULL, "%s: router w2 is NULL", who);
+  if (r->h > 0 && !r->w1) return set_error(MOQE_E_NULL, "%s: router w1 is NULL", who);
+  return MOQE_OK;
+}
+
+static void fill_expert(const moqe_qmat& m0, const moqe_qmat* m1, const PackedInfo& pi, ExpertDev* ex) {
+  ex->w[0] = static_cast<const uint8_t*>(m0.qdata);
+  ex->w[1] = m1 ? static_cast<const uint8_t*>(m1->qdata) : nullptr;
+  ex->fmt = pi.fmt; ex->gm = pi.gm; ex->zc = pi.zc; ex->asym = pi.asym;
+  ex->tile_bytes = pi.tile_bytes;
+  ex->scale_off = uint32_t(pi.scale_off);
+  ex->zero_off = uint32_t(pi.zero_off);
+}
+
+// Heaviest experts first, so the long tasks start early.
+static void order_experts(GemmArgs* ga) {
+  int idx[MOQE_MAX_EXPERTS];
+  for (int i = 0; i < ga->n_experts; ++i) idx[i] = i;
+  std::stable_sort(idx, idx + ga->n_experts,
+                   [&](int a, int b) { return ga->ex[a].tile_bytes > ga->ex[b].tile_bytes; });
+  for (int i = 0; i < ga->n_experts; ++i) ga->order[i] = idx[i];
+}
+
+static int choose_ksplit(int k, int ntasks, int n_experts) {
+  const int KT = k / 128;
+  // enough independent waves to keep every CU streaming; long rows are split across the waves of a group
+  const long waves = long(ntasks) * n_experts;
+  if (KT >= 64 && waves < 256L * 16) return 4;
+  if (KT >= 16 && waves < 256L * 16) return 2;
+  return 1;
+}
+
+// Workspace for the int8 copies of activation rows needed by act_mode-1 experts.
+static size_t a8_bytes(bool any_a8, int M, int kmax) {
+  if (!any_a8) return 0;
+  return align256(size_t(M) * kmax) + align256(size_t(M) * 4);
+}
+
+struct GroupedPlan {
+  PackedInfo pi[MOQE_MAX_EXPERTS];
+  bool any_a8;
+};
+
+static int32_t plan_experts(const moqe_qmat* experts, int K, const moqe_qmat* second, GroupedPlan* gp, const char* who) {
+  gp->any_a8 = false;
+  for (int e = 0; e < K; ++e) {
+    int32_t rc = check_packed(experts[e], &gp->pi[e], who);
+    if (rc) return rc;
+    if (experts[e].n != experts[0].n || experts[e].k != experts[0].k)
+      return set_error(MOQE_E_SHAPE, "%s: expert %d is %d x %d, expert 0 is %d x %d", who, e, experts[e].n, experts[e].k,
+                       experts[0].n, experts[0].k);
+    if (second) {
+      PackedInfo p2;
+      rc = check_packed(second[e], &p2, who);
+      if (rc) return rc;
+      if (second[e].n != experts[e].n || second[e].k != experts[e].k || p2.fmt != gp->pi[e].fmt || p2.gm != gp->pi[e].gm)
+        return set_error(MOQE_E_FORMAT, "%s: gate and up of expert %d must share shape and format", who, e);
+    }
+    if (gp->pi[e].fmt == FMT_I8A8) gp->any_a8 = true;
+  }
+  return MOQE_OK;
+}
+
+// Enqueues one grouped GEMM (plus the int8 row quantization its act_mode-1 experts need).
+static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t* a_perm, const int32_t* y_perm, int S, int T,
+                           const moqe_qmat* experts, const moqe_qmat* second, int K, const GroupedPlan& gp, void* y,
+                           uint8_t* a8_ws, hipStream_t st) {
+  GemmArgs ga;
+  memset(&ga, 0, sizeof(ga));
+  ga.n_experts = K;
+  ga.n = experts[0].n; ga.k = experts[0].k;
+  ga.S = S; ga.T = T;
+  ga.a = a; ga.offsets = offsets; ga.a_perm = a_perm; ga.y_perm = y_perm; ga.y = y;
+  for (int e = 0; e < K; ++e) fill_expert(experts[e], second ? &second[e] : nullptr, gp.pi[e], &ga.ex[e]);
+  order_experts(&ga);
+  const int M = S * T;
+  if (gp.any_a8) {
+    int8_t* aq = reinterpret_cast<int8_t*>(a8_ws);
+    float* as = reinterpret_cast<float*>(a8_ws + align256(size_t(M) * ga.k));
+    ga.a_q = aq; ga.a_scale = as;
+    for (int e = 0; e < K; ++e) {
+      if (gp.pi[e].fmt != FMT_I8A8) continue;
+      int32_t rc = launch_act_quant(a, ga.k, T, offsets, a_perm, e, M, aq, as, st);
+      if (rc) return rc;
+    }
+  }
+  const int NT = ga.n / 16;
+  const int ntasks = second ? NT : (NT + 1) / 2;
+  ga.ksplit = choose_ksplit(ga.k, ntasks, K);
+  return launch_qgemm_stream(ga, second != nullptr, st);
+}
+
+}  // namespace moqe
+
+using namespace moqe;
+
+extern "C" {
+
+const char* moqe_version(void) { return "moqe-gfx950 0.1"; }
+const char* moqe_last_error_string(void) { return g_err; }
+void moqe_set_dry_run(int32_t on) { g_dry.store(on ? 1 : 0); }
+
+// ---- routing -------------------------------------------------------------------------------
+size_t moqe_route_workspace_bytes(int32_t S, int32_t T, const moqe_router* r) {
+  if (!r || S < 0 || T <= 0 || r->d <= 0) return 0;
+  return route_ws_bytes(S, T, *r);
+}
+
+int32_t moqe_route(const void* x, int32_t S, int32_t T, const moqe_router* r, int32_t* expert_idx, float* logits,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t rc = check_router(r, "moqe_route");
+  if (rc) return rc;
+  if (S < 0 || T <= 0) return set_error(MOQE_E_SHAPE, "moqe_route: S=%d T=%d", S, T);
+  if (S == 0) return MOQE_OK;
+  if (!x || !expert_idx) return set_error(MOQE_E_NULL, "moqe_route: x or expert_idx is NULL");
+  if (!aligned(x, 16)) return set_error(MOQE_E_SHAPE, "moqe_route: x must be 16-byte aligned");
+  const size_t need = route_ws_bytes(S, T, *r);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < need)
+    return set_error(MOQE_E_WORKSPACE, "moqe_route: workspace needs %zu bytes, 256-byte aligned", need);
+  if (dry_run()) return MOQE_OK;
+  return launch_route(x, S, T, *r, expert_idx, logits, workspace, static_cast<hipStream_t>(stream));
+}
+
+int32_t moqe_bucket(const int32_t* expert_idx, int32_t S, int32_t K, int32_t* counts, int32_t* offsets, int32_t* perm,
+                    int32_t* inv_perm, void* stream) {
+  if (K < 1 || K > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "moqe_bucket: K=%d outside [1, %d]", K, MOQE_MAX_EXPERTS);
+  if (S < 0) return set_error(MOQE_E_SHAPE, "moqe_bucket: S=%d", S);
+  if (!offsets) return set_error(MOQE_E_NULL, "moqe_bucket: offsets is NULL");
+  if (S > 0 && !expert_idx) return set_error(MOQE_E_NULL, "moqe_bucket: expert_idx is NULL");
+  if (dry_run()) return MOQE_OK;
+  return launch_bucket(expert_idx, S, K, counts, offsets, perm, inv_perm, static_cast<hipStream_t>(stream));
+}
+
+// ---- expert weights ------------------------------------------------------------------------
+int32_t moqe_quantize_rtn(const float* w, float clip, const moqe_qmat* out, void* stream) {
+  if (!w || !out) return set_error(MOQE_E_NULL, "moqe_quantize_rtn: w or out is NULL");
+  PackedInfo pi;
+  moqe_qmat m = *out;
+  m.act_mode = 0;
+  int32_t rc = check_qmat_format(m, &pi, "moqe_quantize_rtn");
+  if (rc) return rc;
+  if (out->layout != MOQE_LAYOUT_CANONICAL) return set_error(MOQE_E_FORMAT, "moqe_quantize_rtn: output must be canonical");
+  if (!out->qdata || !out->scale || (!out->symmetric && !out->zero))
+    return set_error(MOQE_E_NULL, "moqe_quantize_rtn: output buffers missing");
+  if (!(clip > 0.f) || clip > 1.f) return set_error(MOQE_E_SHAPE, "moqe_quantize_rtn: clip %g outside (0, 1]", double(clip));
+  if (dry_run()) return MOQE_OK;
+  return launch_quantize(w, clip, *out, static_cast<hipStream_t>(stream));
+}
+
+size_t moqe_packed_bytes(int32_t n, int32_t k, int32_t bits, int32_t group, int32_t symmetric, int32_t act_mode) {
+  PackedInfo pi;
+  if (!packed_info(n, k, bits, group, symmetric, act_mode, &pi)) return 0;
+  return pi.total;
+}
+
+int32_t moqe_pack_qmat(const moqe_qmat* c, void* packed_out, size_t bytes, void* stream) {
+  if (!c || !packed_out) return set_error(MOQE_E_NULL, "moqe_pack_qmat: NULL argument");
+  PackedInfo pi;
+  int32_t rc = check_qmat_format(*c, &pi, "moqe_pack_qmat");
+  if (rc) return rc;
+  if (c->layout != MOQE_LAYOUT_CANONICAL) return set_error(MOQE_E_FORMAT, "moqe_pack_qmat: input must be canonical");
+  if (!c->qdata || !c->scale || (!c->symmetric && !c->zero)) return set_error(MOQE_E_NULL, "moqe_pack_qmat: input buffers missing");
+  if (bytes < pi.total || !aligned(packed_out, 256))
+    return set_error(MOQE_E_SHAPE, "moqe_pack_qmat: output needs %zu bytes, 256-byte aligned", pi.total);
+  if (dry_run()) return MOQE_OK;
+  return launch_pack(*c, pi, static_cast<uint8_t*>(packed_out), static_cast<hipStream_t>(stream));
+}
+
+int32_t moqe_unpack_qmat(const moqe_qmat* p, int16_t* q_minus_z, float* scale_out, void* stream) {
+  if (!p || !q_minus_z) return set_error(MOQE_E_NULL, "moqe_unpack_qmat: NULL argument");
+  PackedInfo pi;
+  int32_t rc = check_packed(*p, &pi, "moqe_unpack_qmat");
+  if (rc) return rc;
+  if (dry_run()) return MOQE_OK;
+  return launch_unpack(*p, pi, q_minus_z, scale_out, static_cast<hipStream_t>(stream));
+}
+
+// ---- grouped GEMM --------------------------------------------------------------------------
+size_t moqe_grouped_qgemm_workspace_bytes(const moqe_qmat* experts, int32_t K, int32_t S, int32_t T) {
+  if (!experts || K < 1 || K > MOQE_MAX_EXPERTS || S < 0 || T <= 0) return 0;
+  bool any = false;
+  for (int e = 0; e < K; ++e) any = any || experts[e].act_mode == 1;
+  return a8_bytes(any, S * T, experts[0].k);
+}
+
+int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t* perm, int32_t S, int32_t T,
+                           const moqe_qmat* experts, int32_t K, void* y, int32_t scatter, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  if (!experts) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: experts is NULL");
+  if (K < 1 || K > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: K=%d outside [1, %d]", K, MOQE_MAX_EXPERTS);
+  if (S < 0 || T <= 0 || (long long)S * T > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: S=%d T=%d", S, T);
+  GroupedPlan gp;
+  int32_t rc = plan_experts(experts, K, nullptr, &gp, "moqe_grouped_qgemm");
+  if (rc) return rc;
+  if (S == 0) return MOQE_OK;
+  if (!a || !offsets || !y) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: a, offsets or y is NULL");
+  if (!aligned(a, 16) || !aligned(y, 16)) return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: a and y must be 16-byte aligned");
+  if (scatter && !perm) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: scatter needs perm");
+  const size_t need = a8_bytes(gp.any_a8, S * T, experts[0].k);
+  if (need && (!workspace || !aligned(workspace, 256) || workspace_bytes < need))
+    return set_error(MOQE_E_WORKSPACE, "moqe_grouped_qgemm: workspace needs %zu bytes, 256-byte aligned", need);
+  if (dry_run()) return MOQE_OK;
+  return run_grouped(a, offsets, perm, scatter ? perm : nullptr, S, T, experts, nullptr, K, gp, y,
+                     static_cast<uint8_t*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+// ---- the whole block -----------------------------------------------------------------------
+namespace {
+struct FwdLayout {
+  size_t route, idx, logits, counts, offsets, perm, inv_perm, h, a8, col, total;
+};
+
+int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedPlan* gp0, GroupedPlan* gp2) {
+  if (!b) return set_error(MOQE_E_NULL, "moqe_forward: block is NULL");
+  int32_t rc = check_router(&b->router, "moqe_forward");
+  if (rc) return rc;
+  const int K = b->n_experts;
+  if (K != b->router.n_experts) return set_error(MOQE_E_SHAPE, "moqe_forward: block has %d experts, router %d", K, b->router.n_experts);
+  if (S < 0 || T <= 0 || (long long)S * T > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_forward: S=%d T=%d", S, T);
+  if (!b->w0) return set_error(MOQE_E_NULL, "moqe_forward: w0 is NULL");
+  if (b->kind == MOQE_KIND_SILU_MLP) {
+    if (!b->w1 || !b->w2) return set_error(MOQE_E_NULL, "moqe_forward: SILU_MLP needs w1 and w2");
+    rc = plan_experts(b->w0, K, b->w1, gp0, "moqe_forward(gate/up)");
+    if (rc) return rc;
+    rc = plan_experts(b->w2, K, nullptr, gp2, "moqe_forward(down)");
+    if (rc) return rc;
+    if (b->w0[0].k != b->router.d || b->w2[0].k != b->w0[0].n || b->w2[0].n != b->w0[0].k)
+      return set_error(MOQE_E_SHAPE, "moqe_forward: MLP shapes do not chain (d=%d, gate %dx%d, down %dx%d)", b->router.d,
+                       b->w0[0].n, b->w0[0].k, b->w2[0].n, b->w2[0].k);
+  } else if (b->kind == MOQE_KIND_LINEAR) {
+    rc = plan_experts(b->w0, K, nullptr, gp0, "moqe_forward(linear)");
+    if (rc) return rc;
+    if (b->w0[0].k != b->router.d) return set_error(MOQE_E_SHAPE, "moqe_forward: linear k=%d but router d=%d", b->w0[0].k, b->router.d);
+  } else if (b->kind == MOQE_KIND_CONV3X3) {
+    rc = plan_experts(b->w0, K, nullptr, gp0, "moqe_forward(conv)");
+    if (rc) return rc;
+    if (b->img_h <= 0 || b->img_w <= 0 || b->cin <= 0 || b->img_h * b->img_w != T || b->cin != b->router.d ||
+        b->w0[0].k != b->cin * 9)
+      return set_error(MOQE_E_SHAPE, "moqe_forward: conv needs T = img_h*img_w, cin = router d, k = 9*cin");
+  } else {
+    return set_error(MOQE_E_FORMAT, "moqe_forward: unknown block kind %d", b->kind);
+  }
+  const size_t M = size_t(S) * T;
+  size_t o = 0;
+  L->route = o;    o += align256(route_ws_bytes(S, T, b->router));
+  L->idx = o;      o += align256(size_t(S) * 4);
+  L->logits = o;   o += align256(size_t(S) * K * 4);
+  L->counts = o;   o += align256(size_t(K) * 4);
+  L->offsets = o;  o += align256(size_t(K + 1) * 4);
+  L->perm = o;     o += align256(size_t(S) * 4);
+  L->inv_perm = o; o += align256(size_t(S) * 4);
+  L->h = o;
+  if (b->kind == MOQE_KIND_SILU_MLP) o += align256(M * size_t(b->w0[0].n) * 2);
+  L->a8 = o;
+  {
+    bool any = gp0->any_a8 || (b->kind == MOQE_KIND_SILU_MLP && gp2->any_a8);
+    int kmax = b->w0[0].k;
+    if (b->kind == MOQE_KIND_SILU_MLP) kmax = std::max(kmax, b->w2[0].k);
+    o += a8_bytes(any, int(M), kmax);
+  }
+  L->col = o;
+  if (b->kind == MOQE_KIND_CONV3X3) o += align256(M * size_t(b->cin) * 9 * 2);
+  L->total = o;
+  return MOQE_OK;
+}
+}  // namespace
+
+size_t moqe_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T) {
+  FwdLayout L;
+  GroupedPlan g0, g2;
+  if (forward_layout(blk, S, T, &L, &g0, &g2)) return 0;
+  return L.total;
+}
+
+int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  FwdLayout L;
+  GroupedPlan g0, g2;
+  int32_t rc = forward_layout(blk, S, T, &L, &g0, &g2);
+  if (rc) return rc;
+  if (S == 0) return MOQE_OK;
+  if (!x || !y) return set_error(MOQE_E_NULL, "moqe_forward: x or y is NULL");
+  if (!aligned(x, 16) || !aligned(y, 16)) return set_error(MOQE_E_SHAPE, "moqe_forward: x and y must be 16-byte aligned");
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total)
+    return set_error(MOQE_E_WORKSPACE, "moqe_forward: workspace needs %zu bytes, 256-byte aligned", L.total);
+  if (dry_run()) return MOQE_OK;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  const int K = blk->n_experts;
+  int32_t* idx = reinterpret_cast<int32_t*>(ws + L.idx);
+  float* logits = reinterpret_cast<float*>(ws + L.logits);
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + L.counts);
+  int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
+  int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
+  int32_t* inv_perm = reinterpret_cast<int32_t*>(ws + L.inv_perm);
+  if (aux) {   // write straight into the caller's buffers where given
+    if (aux->expert_idx) idx = aux->expert_idx;
+    if (aux->logits) logits = aux->logits;
+    if (aux->counts) counts = aux->counts;
+    if (aux->offsets) offsets = aux->offsets;
+    if (aux->perm) perm = aux->perm;
+    if (aux->inv_perm) inv_perm = aux->inv_perm;
+  }
+
+  rc = launch_route(x, S, T, blk->router, idx, (aux && aux->logits) ? logits : nullptr, ws + L.route, st);
+  if (rc) return rc;
+  rc = launch_bucket(idx, S, K, counts, offsets, perm, (aux && aux->inv_perm) ? inv_perm : nullptr, st);
+  if (rc) return rc;
+
+  if (blk->kind == MOQE_KIND_LINEAR) {
+    return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st);
+  }
+  if (blk->kind == MOQE_KIND_SILU_MLP) {
+    void* h = (aux && aux->h) ? aux->h : static_cast<void*>(ws + L.h);
+    rc = run_grouped(x, offsets, perm, nullptr, S, T, blk->w0, blk->w1, K, g0, h, ws + L.a8, st);
+    if (rc) return rc;
+    return run_grouped(h, offsets, nullptr, perm, S, T, blk->w2, nullptr, K, g2, y, ws + L.a8, st);
+  }
+  // CONV3X3: materialise the 3x3 neighbourhoods in image order, then one grouped GEMM
+  void* col = ws + L.col;
+  rc = launch_im2col(x, S, blk->img_h, blk->img_w, blk->cin, col, st);
+  if (rc) return rc;
+  return run_grouped(col, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st);
+}
+
+// ---- timing --------------------------------------------------------------------------------
+int32_t moqe_profile_enable(int32_t on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  prof_clear_locked();
+  g_prof_on = on != 0;
+  return MOQE_OK;
+}
+
+int32_t moqe_profile_read(int32_t kind, int32_t* launches, double* total_ms) {
+  if (!launches || !total_ms) return set_error(MOQE_E_NULL, "moqe_profile_read: NULL argument");
+  if (kind < 0 || kind >= MOQE_PK_COUNT) return set_error(MOQE_E_SHAPE, "moqe_profile_read: kind %d", kind);
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  int n = 0;
+  double ms = 0.0;
+  for (auto& r : g_prof) {
+    if (r.kind != kind) continue;
+    hipError_t err = hipEventSynchronize(r.b);
+    if (err != hipSuccess) return set_error(MOQE_E_HIP, "moqe_profile_read: %s", hipGetErrorString(err));
+    float t = 0.f;
+    err = hipEventElapsedTime(&t, r.a, r.b);
+    if (err != hipSuccess) return set_error(MOQE_E_HIP, "moqe_profile_read: %s", hipGetErrorString(err));
+    ms += double(t);
+    ++n;
+  }
+  *launches = n;
+  *total_ms = ms;
+  return MOQE_OK;
+}
+
+}  // extern "C"

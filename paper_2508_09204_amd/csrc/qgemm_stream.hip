@@ -1,0 +1,479 @@
+// Grouped dequantize-GEMM, weight-streaming kernel.
+//
+// Each sample is processed by its selected expert only (MoQE Section 3.1), so for expert e the
+// rows of its bucket (a few rows in decode) meet the whole weight matrix of that expert: the
+// work is bound by reading packed weights once.  One wavefront owns two 16-row weight tiles
+// (gate and up tile of the same rows for the SiLU-gated pair, two neighbouring tiles
+// otherwise) and streams them along k with several tiles in flight; the lanes' packed codes
+// are already ordered as matrix-core operands, so a tile goes
+//     16-byte load -> a handful of bit operations -> bf16 MFMA
+// with no shuffles and no LDS.  Integer codes enter the matrix cores exactly (bf16 holds
+// every integer up to 256) with a constant offset; a second MFMA against an all-ones operand
+// gives the row sums of the activations over the same columns, which removes offset and
+// zero-point exactly: sum_k x (c + off) - (off + z) sum_k x.  The fp32 scale multiplies the
+// fp32 partial sum of each group, so no weight is ever rounded.
+#include "moqe_internal.h"
+
+namespace moqe {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NS = 2;        // weight tiles (streams) per wave
+constexpr int MT = 2;        // 16-row activation tiles per pass (32 bucket rows)
+constexpr uint32_t MAGIC = 0x43004300u;   // two bf16 values 128.0: OR-ing a code c < 128 gives 128 + c
+
+template <int FMT> struct Raw;
+template <> struct Raw<FMT_I8>   { static constexpr int N = 8; static constexpr int PF = 2; };
+template <> struct Raw<FMT_I8A8> { static constexpr int N = 8; static constexpr int PF = 2; };
+template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr int PF = 4; };
+template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 4; };
+template <> struct Raw<FMT_N6>   { static constexpr int N = 6; static constexpr int PF = 3; };
+
+template <int FMT>
+static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], const uint8_t* tile, int lane) {
+  if constexpr (FMT == FMT_I8 || FMT == FMT_I8A8) {
+    uint4 a = *reinterpret_cast<const uint4*>(tile + lane * 16);
+    uint4 b = *reinterpret_cast<const uint4*>(tile + 1024 + lane * 16);
+    r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w; r[4] = b.x; r[5] = b.y; r[6] = b.z; r[7] = b.w;
+  } else if constexpr (FMT == FMT_N4) {
+    uint4 a = *reinterpret_cast<const uint4*>(tile + lane * 16);
+    r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w;
+  } else if constexpr (FMT == FMT_N3) {
+    uint2 a = *reinterpret_cast<const uint2*>(tile + lane * 8);
+    r[0] = a.x; r[1] = a.y;
+    r[2] = *reinterpret_cast<const uint32_t*>(tile + 512 + lane * 4);
+  } else {
+    uint4 a = *reinterpret_cast<const uint4*>(tile + lane * 16);
+    uint2 b = *reinterpret_cast<const uint2*>(tile + 1024 + lane * 8);
+    r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w; r[4] = b.x; r[5] = b.y;
+  }
+}
+
+template <int SH> static __device__ __forceinline__ uint32_t shift_by(uint32_t v) {
+  if constexpr (SH >= 0) return v >> SH; else return v << (-SH);
+}
+
+// The matrix-core operand of step J (columns 32J + 8kq + 0..7 of the lane's row) as 8 bf16
+// values code + 128 (code itself for FMT_I8).
+template <int FMT, int J>
+static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N]) {
+  u32x4 d;
+  if constexpr (FMT == FMT_I8) {
+    const uint32_t u0 = r[(J / 2) * 4 + (J % 2) * 2], u1 = r[(J / 2) * 4 + (J % 2) * 2 + 1];
+    // integers up to 255 are exact in fp32 and their bf16 is the upper half of the fp32 pattern
+    const uint32_t f0 = __float_as_uint(float(u0 & 0xffu)), f1 = __float_as_uint(float((u0 >> 8) & 0xffu));
+    const uint32_t f2 = __float_as_uint(float((u0 >> 16) & 0xffu)), f3 = __float_as_uint(float(u0 >> 24));
+    const uint32_t f4 = __float_as_uint(float(u1 & 0xffu)), f5 = __float_as_uint(float((u1 >> 8) & 0xffu));
+    const uint32_t f6 = __float_as_uint(float((u1 >> 16) & 0xffu)), f7 = __float_as_uint(float(u1 >> 24));
+    d.x = __builtin_amdgcn_perm(f1, f0, 0x07060302u);
+    d.y = __builtin_amdgcn_perm(f3, f2, 0x07060302u);
+    d.z = __builtin_amdgcn_perm(f5, f4, 0x07060302u);
+    d.w = __builtin_amdgcn_perm(f7, f6, 0x07060302u);
+  } else if constexpr (FMT == FMT_N4) {
+    const uint32_t w = r[J];
+    d.x = (w & 0x000F000Fu) | MAGIC;
+    d.y = ((w >> 4) & 0x000F000Fu) | MAGIC;
+    d.z = ((w >> 8) & 0x000F000Fu) | MAGIC;
+    d.w = ((w >> 12) & 0x000F000Fu) | MAGIC;
+  } else if constexpr (FMT == FMT_N3) {
+    const uint32_t lo = r[J / 2], hi = r[2];
+    constexpr int P0 = 4 * (J % 2);       // first 2-bit field of this step inside `lo`
+    constexpr int Q0 = 4 * J;             // first 1-bit field of this step inside `hi`
+    d.x = ((lo >> (2 * (P0 + 0))) & 0x00030003u) | (shift_by<Q0 + 0 - 2>(hi) & 0x00040004u) | MAGIC;
+    d.y = ((lo >> (2 * (P0 + 1))) & 0x00030003u) | (shift_by<Q0 + 1 - 2>(hi) & 0x00040004u) | MAGIC;
+    d.z = ((lo >> (2 * (P0 + 2))) & 0x00030003u) | (shift_by<Q0 + 2 - 2>(hi) & 0x00040004u) | MAGIC;
+    d.w = ((lo >> (2 * (P0 + 3))) & 0x00030003u) | (shift_by<Q0 + 3 - 2>(hi) & 0x00040004u) | MAGIC;
+  } else {  // FMT_N6
+    const uint32_t w = r[J], hi = r[4 + J / 2];
+    constexpr int P0 = 4 * (J % 2);
+    d.x = (w & 0x000F000Fu) | (shift_by<2 * (P0 + 0) - 4>(hi) & 0x00300030u) | MAGIC;
+    d.y = ((w >> 4) & 0x000F000Fu) | (shift_by<2 * (P0 + 1) - 4>(hi) & 0x00300030u) | MAGIC;
+    d.z = ((w >> 8) & 0x000F000Fu) | (shift_by<2 * (P0 + 2) - 4>(hi) & 0x00300030u) | MAGIC;
+    d.w = ((w >> 12) & 0x000F000Fu) | (shift_by<2 * (P0 + 3) - 4>(hi) & 0x00300030u) | MAGIC;
+  }
+  return __builtin_bit_cast(bf16x8, d);
+}
+
+static __device__ __forceinline__ f32x4 mfma_bf16(const u32x4& a, const bf16x8& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), b, c, 0, 0, 0);
+}
+
+static __device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+static __device__ __forceinline__ float silu_mul(float g, float u) {
+  return (g / (1.0f + __expf(-g))) * u;
+}
+
+// One task: the wave's two weight tiles against the rows of one expert's bucket, over the
+// k-tiles [kt0, kt1).  `red` is this work-group's LDS reduction area.
+template <int FMT, int GM, bool GATEUP>
+static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int task,
+                                                   const int ks, const bool active_task, float* red) {
+  constexpr bool A8 = (FMT == FMT_I8A8);
+  constexpr int PF = Raw<FMT>::PF;
+  constexpr int NR = Raw<FMT>::N;
+  constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lr = lane & 15, lq = lane >> 4;
+  const int KT = ga.k >> 7, NT = ga.n >> 4;
+  const int T = ga.T;
+  const int off_e = ga.offsets[e];
+  const int M_e = (ga.offsets[e + 1] - off_e) * T;
+  if (M_e <= 0) return;                       // uniform over the work-group (one expert per work-group)
+
+  int nt[NS];
+  bool sv[NS];
+  const uint8_t* blob[NS];
+  if constexpr (GATEUP) {
+    nt[0] = nt[1] = task; sv[0] = sv[1] = active_task && task < NT;
+    blob[0] = ex.w[0]; blob[1] = ex.w[1];
+  } else {
+    nt[0] = 2 * task; nt[1] = 2 * task + 1;
+    sv[0] = active_task && nt[0] < NT; sv[1] = active_task && nt[1] < NT;
+    blob[0] = blob[1] = ex.w[0];
+  }
+  const int chunk = (KT + ga.ksplit - 1) / ga.ksplit;
+  const int kt0 = ks * chunk, kt1 = min(KT, kt0 + chunk);
+  const float cbase = (FMT == FMT_I8) ? 0.f : 128.f;
+  const float off_sym = cbase + float(ex.zc);
+
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
+
+  for (int pass0 = 0; pass0 < M_e; pass0 += 16 * MT) {
+    // ---- rows of this pass: operand rows (lane's row lr) and result rows (4*lq + r) ----
+    const uint8_t* arow[MT];
+    bool avalid[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = pass0 + mt * 16 + lr;
+      avalid[mt] = m < M_e;
+      const int mm = avalid[mt] ? m : 0;
+      if constexpr (A8) {
+        arow[mt] = reinterpret_cast<const uint8_t*>(ga.a_q) + (size_t(off_e) * T + mm) * size_t(ga.k);
+      } else {
+        size_t src;
+        if (ga.a_perm) src = size_t(ga.a_perm[off_e + mm / T]) * T + (mm % T);
+        else src = size_t(off_e) * T + mm;
+        arow[mt] = reinterpret_cast<const uint8_t*>(ga.a) + src * size_t(ga.k) * 2;
+      }
+    }
+
+    f32x4 tot[NS][MT];     // bf16 path: fp32 results; int8 path: int32 bit patterns
+    f32x4 xs_tot[MT];      // per-channel formats: running row sums of the activations
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      xs_tot[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < NS; ++s) tot[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    if (kt0 < kt1 && (sv[0] || sv[1])) {
+      uint32_t raw[PF][NS][NR];
+      float sc[PF][NS][GPT ? GPT : 1];
+      uint32_t zp[PF][NS];
+      u32x4 afr[2][4][MT];     // activation operands of the current and the next k-tile
+
+      auto issue_w = [&](int p, int kt) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          if (sv[s]) {
+            const size_t t = size_t(nt[s]) * KT + kt;
+            load_raw<FMT>(raw[p][s], blob[s] + t * ex.tile_bytes, lane);
+            if constexpr (GPT > 0) {
+              const float* sp = reinterpret_cast<const float*>(blob[s] + ex.scale_off) + (t * 16 + lr) * GPT;
+              const uint8_t* zq = blob[s] + ex.zero_off + (t * 16 + lr) * GPT;
+              if constexpr (GPT == 1) {
+                sc[p][s][0] = sp[0];
+                zp[p][s] = ex.asym ? uint32_t(zq[0]) : 0u;
+              } else {
+                float2 v = *reinterpret_cast<const float2*>(sp);
+                sc[p][s][0] = v.x; sc[p][s][1] = v.y;
+                zp[p][s] = ex.asym ? uint32_t(*reinterpret_cast<const uint16_t*>(zq)) : 0u;
+              }
+            }
+          }
+        }
+      };
+      auto issue_a = [&](int buf, int kt) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          if (pass0 + mt * 16 < M_e) {
+            if constexpr (A8) {
+#pragma unroll
+              for (int js = 0; js < 2; ++js) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (avalid[mt]) v = *reinterpret_cast<const u32x4*>(arow[mt] + size_t(kt) * 128 + js * 64 + lq * 16);
+                afr[buf][js][mt] = v;
+              }
+            } else {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (avalid[mt]) v = *reinterpret_cast<const u32x4*>(arow[mt] + (size_t(kt) * 128 + j * 32 + lq * 8) * 2);
+                afr[buf][j][mt] = v;
+              }
+            }
+          }
+        }
+      };
+
+#pragma unroll
+      for (int p = 0; p < PF; ++p)
+        if (kt0 + p < kt1) issue_w(p, kt0 + p);
+      issue_a(0, kt0);
+
+      for (int ktb = kt0; ktb < kt1; ktb += 2 * PF) {
+#pragma unroll
+        for (int pp = 0; pp < 2 * PF; ++pp) {
+          const int p = pp % PF, ab = pp & 1;
+          const int kt = ktb + pp;
+          if (kt < kt1) {
+            if (kt + 1 < kt1) issue_a(ab ^ 1, kt + 1);
+
+            if constexpr (A8) {
+#pragma unroll
+              for (int s = 0; s < NS; ++s) {
+                if (sv[s]) {
+#pragma unroll
+                  for (int mt = 0; mt < MT; ++mt) {
+                    if (pass0 + mt * 16 < M_e) {
+                      i32x4 acc = __builtin_bit_cast(i32x4, tot[s][mt]);
+#pragma unroll
+                      for (int js = 0; js < 2; ++js) {
+                        i32x4 b = {int(raw[p][s][js * 4 + 0]), int(raw[p][s][js * 4 + 1]), int(raw[p][s][js * 4 + 2]),
+                                   int(raw[p][s][js * 4 + 3])};
+                        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, afr[ab][js][mt]), b, acc, 0, 0, 0);
+                      }
+                      tot[s][mt] = __builtin_bit_cast(f32x4, acc);
+                    }
+                  }
+                }
+              }
+            } else {
+              // row sums of the activations over this tile's columns (per group)
+              f32x4 xs[MT][GPT ? GPT : 1];
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) {
+                if (pass0 + mt * 16 < M_e) {
+                  if constexpr (GM == GM_PC) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) xs_tot[mt] = mfma_bf16(afr[ab][j][mt], ones_b, xs_tot[mt]);
+                  } else if constexpr (GM == GM_G128) {
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v = mfma_bf16(afr[ab][j][mt], ones_b, v);
+                    xs[mt][0] = v;
+                  } else {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                      v = mfma_bf16(afr[ab][2 * h][mt], ones_b, v);
+                      v = mfma_bf16(afr[ab][2 * h + 1][mt], ones_b, v);
+                      xs[mt][h] = v;
+                    }
+                  }
+                }
+              }
+#pragma unroll
+              for (int s = 0; s < NS; ++s) {
+                if (sv[s]) {
+                  const bf16x8 b0 = frag<FMT, 0>(raw[p][s]);
+                  const bf16x8 b1 = frag<FMT, 1>(raw[p][s]);
+                  const bf16x8 b2 = frag<FMT, 2>(raw[p][s]);
+                  const bf16x8 b3 = frag<FMT, 3>(raw[p][s]);
+#pragma unroll
+                  for (int mt = 0; mt < MT; ++mt) {
+                    if (pass0 + mt * 16 < M_e) {
+                      if constexpr (GM == GM_PC) {
+                        f32x4 v = tot[s][mt];
+                        v = mfma_bf16(afr[ab][0][mt], b0, v);
+                        v = mfma_bf16(afr[ab][1][mt], b1, v);
+                        v = mfma_bf16(afr[ab][2][mt], b2, v);
+                        v = mfma_bf16(afr[ab][3][mt], b3, v);
+                        tot[s][mt] = v;
+                      } else if constexpr (GM == GM_G128) {
+                        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                        v = mfma_bf16(afr[ab][0][mt], b0, v);
+                        v = mfma_bf16(afr[ab][1][mt], b1, v);
+                        v = mfma_bf16(afr[ab][2][mt], b2, v);
+                        v = mfma_bf16(afr[ab][3][mt], b3, v);
+                        const float o = ex.asym ? 128.f + float(zp[p][s] & 0xffu) : off_sym;
+                        const float scv = sc[p][s][0];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
+                      } else {
+                        f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+                        v0 = mfma_bf16(afr[ab][0][mt], b0, v0);
+                        v0 = mfma_bf16(afr[ab][1][mt], b1, v0);
+                        v1 = mfma_bf16(afr[ab][2][mt], b2, v1);
+                        v1 = mfma_bf16(afr[ab][3][mt], b3, v1);
+                        const float o0 = ex.asym ? 128.f + float(zp[p][s] & 0xffu) : off_sym;
+                        const float o1 = ex.asym ? 128.f + float((zp[p][s] >> 8) & 0xffu) : off_sym;
+                        const float s0 = sc[p][s][0], s1 = sc[p][s][GPT == 2 ? 1 : 0];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                          tot[s][mt][r] += s0 * (v0[r] - o0 * xs[mt][0][r]);
+                          tot[s][mt][r] += s1 * (v1[r] - o1 * xs[mt][GPT == 2 ? 1 : 0][r]);
+                        }
+                      }
+                    }
+                  }
+                }
+              }
+            }
+            if (kt + PF < kt1) issue_w(p, kt + PF);
+          }
+        }
+      }
+    }
+
+    // ---- combine the k-slices of a task (fixed order), then the epilogue -------------------
+    if (ga.ksplit > 1) {
+      float* mine = red + size_t(wave) * (NS * MT * 4 * 64);
+      if (ks > 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[((s * MT + mt) * 4 + r) * 64 + lane] = tot[s][mt][r];
+      }
+      __syncthreads();
+      if (ks == 0) {
+        for (int o = 1; o < ga.ksplit; ++o) {
+          const float* other = red + size_t(wave + o) * (NS * MT * 4 * 64);
+#pragma unroll
+          for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const float v = other[((s * MT + mt) * 4 + r) * 64 + lane];
+                if constexpr (A8) {
+                  tot[s][mt][r] = __int_as_float(__float_as_int(tot[s][mt][r]) + __float_as_int(v));
+                } else {
+                  tot[s][mt][r] += v;
+                }
+              }
+        }
+      }
+      __syncthreads();
+    }
+    if constexpr (GM == GM_PC && !A8) {
+      if (ga.ksplit > 1) {
+        float* mine = red + size_t(wave) * (NS * MT * 4 * 64);
+        if (ks > 0) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[(mt * 4 + r) * 64 + lane] = xs_tot[mt][r];
+        }
+        __syncthreads();
+        if (ks == 0) {
+          for (int o = 1; o < ga.ksplit; ++o) {
+            const float* other = red + size_t(wave + o) * (NS * MT * 4 * 64);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) xs_tot[mt][r] += other[(mt * 4 + r) * 64 + lane];
+          }
+        }
+        __syncthreads();
+      }
+    }
+
+    if (ks == 0 && (sv[0] || sv[1])) {
+      float pcs[NS] = {1.f, 1.f};
+      if constexpr (GM == GM_PC) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+          if (sv[s]) pcs[s] = reinterpret_cast<const float*>(blob[s] + ex.scale_off)[nt[s] * 16 + lr];
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int m = pass0 + mt * 16 + lq * 4 + r;
+          if (m < M_e) {
+            float val[NS];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+              if constexpr (A8) {
+                const float sx = ga.a_scale[size_t(off_e) * T + m];
+                val[s] = float(__float_as_int(tot[s][mt][r])) * sx * pcs[s];
+              } else if constexpr (GM == GM_PC) {
+                val[s] = pcs[s] * (tot[s][mt][r] - off_sym * xs_tot[mt][r]);
+              } else {
+                val[s] = tot[s][mt][r];
+              }
+            }
+            const size_t brow = size_t(off_e) * T + m;
+            if constexpr (GATEUP) {
+              if (sv[0]) {
+                uint16_t* h = static_cast<uint16_t*>(ga.y);
+                h[brow * size_t(ga.n) + nt[0] * 16 + lr] = float_to_bf16_rne(silu_mul(val[0], val[1]));
+              }
+            } else {
+              size_t drow = brow;
+              if (ga.y_perm) drow = size_t(ga.y_perm[off_e + m / T]) * T + (m % T);
+              float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
+              if (sv[0]) y[nt[0] * 16 + lr] = val[0];
+              if (sv[1]) y[nt[1] * 16 + lr] = val[1];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+template <bool GATEUP>
+__global__ __launch_bounds__(256) void k_qgemm_stream(const GemmArgs ga) {
+  __shared__ float red[4 * NS * MT * 4 * 64];
+  const int wg = blockIdx.x;
+  const int eo = wg / ga.wg_per_expert;
+  const int e = ga.order[eo];
+  const int wgi = wg % ga.wg_per_expert;
+  const int wave = threadIdx.x >> 6;
+  const int wpt = 4 / ga.ksplit;
+  const int task = wgi * wpt + wave / ga.ksplit;
+  const int ks = wave % ga.ksplit;
+  const ExpertDev& ex = ga.ex[e];
+  const int NT = ga.n >> 4;
+  const int ntasks = GATEUP ? NT : (NT + 1) / 2;
+  const bool active = task < ntasks;
+  switch (ex.fmt * 4 + ex.gm) {
+    case FMT_I8 * 4 + GM_PC:     stream_task<FMT_I8, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_I8A8 * 4 + GM_PC:   stream_task<FMT_I8A8, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_N6 * 4 + GM_PC:     stream_task<FMT_N6, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_N4 * 4 + GM_PC:     stream_task<FMT_N4, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_N4 * 4 + GM_G128:   stream_task<FMT_N4, GM_G128, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_N4 * 4 + GM_G64:    stream_task<FMT_N4, GM_G64, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_N3 * 4 + GM_G128:   stream_task<FMT_N3, GM_G128, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_N3 * 4 + GM_G64:    stream_task<FMT_N3, GM_G64, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    default: break;
+  }
+}
+
+int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
+  const int NT = ga.n / 16;
+  const int ntasks = gateup ? NT : (NT + 1) / 2;
+  GemmArgs a = ga;
+  const int wpt = 4 / a.ksplit;
+  a.wg_per_expert = (ntasks + wpt - 1) / wpt;
+  const unsigned grid = unsigned(a.wg_per_expert) * unsigned(a.n_experts);
+  ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
+  if (gateup) hipLaunchKernelGGL(k_qgemm_stream<true>, dim3(grid), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(k_qgemm_stream<false>, dim3(grid), dim3(256), 0, st, a);
+  return check_launch("grouped_qgemm");
+}
+
+}  // namespace moqe

@@ -1,0 +1,179 @@
+"""The C ABI without a GPU: every symbol declared in include/moqe.h is exported, argument
+validation returns the documented error codes (dry-run mode: nothing is enqueued), and the packed
+layout's index functions form a bijection (checked through a host-compiled copy of the header)."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moqe.h")
+
+
+@pytest.fixture(scope="module")
+def mq():
+    from paper_2508_09204_amd import binding
+    binding.moqe_set_dry_run(True)
+    yield binding
+    binding.moqe_set_dry_run(False)
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(moqe_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(mq):
+    names = _declared_functions()
+    assert {"moqe_route", "moqe_bucket", "moqe_grouped_qgemm", "moqe_forward"} <= set(names)
+    for n in names:
+        assert hasattr(mq.lib, n), n
+    assert sorted(mq.EXPORTED) == names
+    assert mq.moqe_version().startswith("moqe-gfx950")
+
+
+FAKE = 0x10000   # a non-NULL, 256-byte aligned address; never dereferenced in dry-run mode
+
+
+def _qmat(mq, n=32, k=256, bits=4, group=128, sym=0, act=0, layout=1, ptr=FAKE):
+    return mq._QMat(ptr, ptr, ptr, n, k, bits, group, sym, act, layout)
+
+
+def test_bucket_argument_errors(mq):
+    lib = mq.lib
+    assert lib.moqe_bucket(FAKE, 8, 0, None, FAKE, None, None, None) == -2
+    assert lib.moqe_bucket(FAKE, 8, 17, None, FAKE, None, None, None) == -2
+    assert lib.moqe_bucket(FAKE, -1, 4, None, FAKE, None, None, None) == -2
+    assert lib.moqe_bucket(FAKE, 8, 4, None, None, None, None, None) == -1
+    assert lib.moqe_bucket(None, 8, 4, None, FAKE, None, None, None) == -1
+    assert b"expert_idx" in lib.moqe_last_error_string()
+    assert lib.moqe_bucket(FAKE, 8, 4, None, FAKE, None, None, None) == 0
+
+
+def test_packed_bytes_and_formats(mq):
+    pb = mq.moqe_packed_bytes
+    assert pb(256, 256, 8, 0, True) == 256 * 256 + 256 * 4
+    assert pb(256, 256, 4, 64, False) == 256 * 128 + 256 * 4 * 4 + 256 * 4
+    assert pb(256, 256, 3, 64, False) == 256 * 96 + 256 * 4 * 4 + 256 * 4
+    assert pb(4096, 11008, 4, 128, False) == 4096 * 5504 + 4096 * 86 * 5
+    assert pb(256, 2304, 6, 0, True) == 256 * 2304 * 6 // 8 + 256 * 4
+    for bad in [(250, 256, 4, 128, False, 0), (256, 200, 4, 128, False, 0), (256, 256, 5, 128, False, 0),
+                (256, 256, 4, 32, False, 0), (256, 256, 4, 128, True, 0), (256, 256, 4, 0, False, 0),
+                (256, 256, 4, 128, False, 1), (256, 256, 6, 0, True, 1)]:
+        assert pb(*bad) == 0, bad
+
+
+def test_grouped_qgemm_argument_errors(mq):
+    lib = mq.lib
+    ex = (mq._QMat * 2)(_qmat(mq), _qmat(mq))
+    call = lambda a, off, perm, S, T, e, K, y, sc, ws, wsb: lib.moqe_grouped_qgemm(a, off, perm, S, T, e, K, y, sc, ws, wsb, None)
+    assert call(FAKE, FAKE, FAKE, 4, 1, ex, 2, FAKE, 1, None, 0) == 0
+    assert call(None, FAKE, FAKE, 4, 1, ex, 2, FAKE, 1, None, 0) == -1
+    assert call(FAKE, FAKE, None, 4, 1, ex, 2, FAKE, 1, None, 0) == -1          # scatter without perm
+    assert call(FAKE, FAKE, FAKE, 4, 0, ex, 2, FAKE, 1, None, 0) == -2
+    assert call(FAKE, FAKE, FAKE, 4, 1, ex, 0, FAKE, 1, None, 0) == -2
+    assert call(FAKE + 2, FAKE, FAKE, 4, 1, ex, 2, FAKE, 1, None, 0) == -2      # misaligned activations
+    bad = (mq._QMat * 2)(_qmat(mq), _qmat(mq, n=48))
+    assert call(FAKE, FAKE, FAKE, 4, 1, bad, 2, FAKE, 1, None, 0) == -2          # experts of different shape
+    bad = (mq._QMat * 2)(_qmat(mq), _qmat(mq, bits=5))
+    assert call(FAKE, FAKE, FAKE, 4, 1, bad, 2, FAKE, 1, None, 0) == -3
+    bad = (mq._QMat * 2)(_qmat(mq), _qmat(mq, layout=0))
+    assert call(FAKE, FAKE, FAKE, 4, 1, bad, 2, FAKE, 1, None, 0) == -3          # canonical where packed is required
+    a8 = (mq._QMat * 1)(_qmat(mq, bits=8, group=0, sym=1, act=1))
+    need = lib.moqe_grouped_qgemm_workspace_bytes(a8, 1, 4, 1)
+    assert need >= 4 * 256 + 16
+    assert call(FAKE, FAKE, FAKE, 4, 1, a8, 1, FAKE, 1, None, 0) == -4
+    assert call(FAKE, FAKE, FAKE, 4, 1, a8, 1, FAKE, 1, FAKE, need - 1) == -4
+    assert call(FAKE, FAKE, FAKE, 4, 1, a8, 1, FAKE, 1, FAKE, need) == 0
+    assert call(FAKE, FAKE, FAKE, 0, 1, ex, 2, FAKE, 1, None, 0) == 0            # empty batch: nothing to do
+
+
+def test_route_and_forward_argument_errors(mq):
+    lib = mq.lib
+    r = mq._Router(FAKE, None, FAKE, None, 256, 32, 2)
+    need = lib.moqe_route_workspace_bytes(4, 3, C.byref(r))
+    assert need > 0
+    assert lib.moqe_route(FAKE, 4, 3, C.byref(r), FAKE, None, FAKE, need, None) == 0
+    assert lib.moqe_route(FAKE, 4, 3, C.byref(r), FAKE, None, FAKE, need - 1, None) == -4
+    assert lib.moqe_route(FAKE, 4, 3, C.byref(r), None, None, FAKE, need, None) == -1
+    assert lib.moqe_route(FAKE, 4, 3, None, FAKE, None, FAKE, need, None) == -1
+    rbad = mq._Router(FAKE, None, FAKE, None, 250, 32, 2)
+    assert lib.moqe_route(FAKE, 4, 3, C.byref(rbad), FAKE, None, FAKE, need, None) == -2
+    rbad = mq._Router(None, None, FAKE, None, 256, 32, 2)
+    assert lib.moqe_route(FAKE, 4, 3, C.byref(rbad), FAKE, None, FAKE, need, None) == -1
+
+    gate = (mq._QMat * 2)(_qmat(mq, n=512, k=256), _qmat(mq, n=512, k=256, bits=8, group=0, sym=1))
+    up = (mq._QMat * 2)(_qmat(mq, n=512, k=256), _qmat(mq, n=512, k=256, bits=8, group=0, sym=1))
+    down = (mq._QMat * 2)(_qmat(mq, n=256, k=512), _qmat(mq, n=256, k=512, bits=8, group=0, sym=1))
+    blk = mq._Block(1, r, gate, up, down, 2, 0, 0, 0)
+    need = lib.moqe_workspace_bytes(C.byref(blk), 4, 3)
+    assert need >= 4 * 3 * 512 * 2
+    assert lib.moqe_forward(C.byref(blk), FAKE, 4, 3, FAKE, None, FAKE, need, None) == 0
+    assert lib.moqe_forward(C.byref(blk), FAKE, 4, 3, FAKE, None, FAKE, need - 256, None) == -4
+    assert lib.moqe_forward(C.byref(blk), None, 4, 3, FAKE, None, FAKE, need, None) == -1
+    mixed = (mq._QMat * 2)(_qmat(mq, n=512, k=256, bits=3), _qmat(mq, n=512, k=256, bits=8, group=0, sym=1))
+    blk2 = mq._Block(1, r, gate, mixed, down, 2, 0, 0, 0)
+    assert lib.moqe_forward(C.byref(blk2), FAKE, 4, 3, FAKE, None, FAKE, need, None) == -3   # gate/up formats differ
+    blk3 = mq._Block(1, r, gate, up, gate, 2, 0, 0, 0)
+    assert lib.moqe_forward(C.byref(blk3), FAKE, 4, 3, FAKE, None, FAKE, need, None) == -2   # shapes do not chain
+    blk4 = mq._Block(7, r, gate, up, down, 2, 0, 0, 0)
+    assert lib.moqe_forward(C.byref(blk4), FAKE, 4, 3, FAKE, None, FAKE, need, None) == -3
+    assert lib.moqe_workspace_bytes(C.byref(blk4), 4, 3) == 0
+
+
+LAYOUT_PROBE = r'''
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+#define __host__
+#define __device__
+#include <cstdint>
+#include <cstddef>
+// only the layout math of the internal header is needed on the host
+#define MOQE_LAYOUT_ONLY
+%s
+int main(int argc, char** argv) {
+  int n = atoi(argv[1]), k = atoi(argv[2]), bits = atoi(argv[3]), group = atoi(argv[4]), sym = atoi(argv[5]), act = atoi(argv[6]);
+  moqe::PackedInfo pi;
+  if (!moqe::packed_info(n, k, bits, group, sym, act, &pi)) { printf("unsupported\n"); return 0; }
+  std::vector<uint8_t> used(pi.scale_off * 8, 0);
+  long clashes = 0, outside = 0;
+  for (int r = 0; r < n; ++r) for (int c = 0; c < k; ++c) {
+    moqe::CodePos p = moqe::code_pos(pi, r, c);
+    for (unsigned b = 0; b < p.bits0; ++b) { size_t bit = p.byte0 * 8 + p.shift0 + b; if (bit >= used.size()) ++outside; else if (used[bit]++) ++clashes; }
+    for (unsigned b = 0; b < p.bits1; ++b) { size_t bit = p.byte1 * 8 + p.shift1 + b; if (bit >= used.size()) ++outside; else if (used[bit]++) ++clashes; }
+  }
+  long unused = 0;
+  for (size_t i = 0; i < size_t(n) * k * bits; ++i) if (!used[i]) ++unused;   // dense: the first n*k*bits bits are all taken
+  printf("clashes=%%ld outside=%%ld unused=%%ld codebytes=%%zu\n", clashes, outside, unused, size_t(pi.nt) * pi.kt * pi.tile_bytes);
+  return 0;
+}
+'''
+
+
+def _layout_section():
+    src = open(os.path.join(ROOT, "paper_2508_09204_amd", "csrc", "moqe_internal.h")).read()
+    a = src.index("enum Fmt")
+    b = src.index("// Kernel-side description")
+    b = src.rindex("// ----", 0, b)
+    return "namespace moqe {\n" + src[a:b] + "\n}\n"
+
+
+@pytest.mark.parametrize("fmt", [(48, 384, 8, 0, 1, 0), (48, 384, 8, 0, 1, 1), (32, 256, 6, 0, 1, 0), (32, 256, 4, 0, 1, 0),
+                                 (32, 256, 4, 64, 0, 0), (32, 256, 4, 128, 0, 0), (32, 256, 3, 64, 0, 0),
+                                 (48, 384, 3, 128, 0, 0)])
+def test_packed_layout_is_a_dense_bijection(fmt, tmp_path):
+    """Every (row, col) gets its own bits, inside the code region, with no bit left unused: so the
+    packed blob holds exactly bits/8 bytes per weight."""
+    src = tmp_path / "probe.cpp"
+    src.write_text(LAYOUT_PROBE % _layout_section())
+    exe = tmp_path / "probe"
+    subprocess.run(["g++", "-O1", "-std=c++17", "-o", str(exe), str(src)], check=True)
+    out = subprocess.run([str(exe)] + [str(v) for v in fmt], check=True, capture_output=True, text=True).stdout
+    n, k, bits = fmt[0], fmt[1], fmt[2]
+    assert out.strip() == f"clashes=0 outside=0 unused=0 codebytes={n * k * bits // 8}", out

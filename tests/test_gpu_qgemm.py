@@ -1,0 +1,116 @@
+"""GPU parity: grouped dequantize-GEMM against the oracle, per format and for ragged buckets.
+
+Tolerance: |y - ref| <= 2e-3 * max(|ref|, rms(ref)) element-wise (bf16 inputs, fp32 accumulation).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import moqe_oracle as oc
+from tests import oracle_blocks as ob
+
+pytestmark = pytest.mark.gpu
+
+FORMATS = [(8, 0, True, 1.0, 0), (8, 0, True, 1.0, 1), (6, 0, True, 1.0, 0), (4, 0, True, 1.0, 0),
+           (4, 64, False, 1.0, 0), (4, 128, False, 0.9, 0), (3, 64, False, 1.0, 0), (3, 128, False, 1.0, 0)]
+
+
+def _run(a_bits, e_idx, qms, S, T, scatter=True, use_perm=True):
+    """Grouped GEMM on the GPU for routing e_idx; returns y (caller order) as numpy."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    K = len(qms)
+    counts, offsets, perm, inv = oc.bucket(e_idx, K)
+    n, k = qms[0].n, qms[0].k
+    a_host = a_bits.reshape(S, T, k)
+    if not use_perm:
+        a_host = a_host[perm]                         # hand the rows over already in bucket order
+    a = gb.bf16_dev(a_host.reshape(S * T, k))
+    y = torch.full((S * T, n), float("nan"), dtype=torch.float32, device=gb.DEV)
+    packed = [gb.packed_dev(q) for q in qms]
+    mq.moqe_grouped_qgemm(a, gb.to_dev(offsets), gb.to_dev(perm) if use_perm else None, S, T, packed, y,
+                          scatter and use_perm)
+    torch.cuda.synchronize()
+    out = y.cpu().numpy().reshape(S, T, n)
+    if not (scatter and use_perm):
+        out = out[inv]                                # bucket order -> caller order
+    return out
+
+
+def _ref(a_bits, e_idx, qms, S, T):
+    x = oc.bf16_bits_to_f64(a_bits).reshape(S, T, -1)
+    return np.stack([oc.qlinear(x[s], qms[int(e_idx[s])]) for s in range(S)])
+
+
+@pytest.mark.parametrize("bits,group,sym,clip,act", FORMATS)
+@pytest.mark.parametrize("S,T,n,k", [(5, 3, 48, 384), (37, 1, 32, 1024), (3, 50, 16, 128)])
+def test_single_format_single_expert(bits, group, sym, clip, act, S, T, n, k):
+    rng = np.random.default_rng(bits * 13 + group + S)
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    qm = oc.quantize(w, bits, group, sym, clip, act)
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((S * T, k)).astype(np.float32))
+    e = np.zeros(S, dtype=np.int32)
+    y = _run(a_bits, e, [qm], S, T)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, [qm], S, T))
+    assert ok, worst
+    assert worst < 0.05          # far inside the 2e-3 budget: nothing is rounded but the accumulation
+
+
+@pytest.mark.parametrize("scatter,use_perm", [(True, True), (False, True), (False, False)])
+def test_mixed_experts_ragged_buckets(scatter, use_perm):
+    rng = np.random.default_rng(21)
+    S, T, n, k = 45, 3, 80, 640
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    specs = [(4, 128, False, 1.0, 0), (3, 128, False, 1.0, 0), (8, 0, True, 1.0, 0), (8, 0, True, 1.0, 1),
+             (4, 64, False, 0.9, 0), (6, 0, True, 1.0, 0)]
+    qms = [oc.quantize(w, *s) for s in specs]
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((S * T, k)).astype(np.float32))
+    e = rng.integers(0, len(qms), S).astype(np.int32)
+    e[e == 4] = 0                                     # expert 4 stays empty
+    y = _run(a_bits, e, qms, S, T, scatter, use_perm)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, qms, S, T))
+    assert ok, worst
+
+
+@pytest.mark.parametrize("rows", [1, 15, 16, 17, 31, 32, 33, 64, 100])
+def test_bucket_sizes_around_tile_edges(rows):
+    rng = np.random.default_rng(rows)
+    n, k = 32, 256
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    qms = [oc.quantize(w, 4, 128, False), oc.quantize(w, 8, 0, True)]
+    S = rows + 3
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((S, k)).astype(np.float32))
+    e = np.zeros(S, dtype=np.int32)
+    e[[0, S // 2, S - 1]] = 1
+    y = _run(a_bits, e, qms, S, 1)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, qms, S, 1))
+    assert ok, worst
+
+
+def test_w8a8_integer_accumulators_are_exact():
+    """With unit scales the W8A8 output IS the int32 dot product: compare exactly."""
+    rng = np.random.default_rng(3)
+    S, n, k = 20, 32, 512
+    q = rng.integers(-127, 128, (n, k)).astype(np.int8)
+    qm = oc.QMat(q=q, scale=np.ones(n, dtype=np.float32), zero=None, bits=8, group=0, symmetric=True, act_mode=1)
+    xi = rng.integers(-127, 128, (S, k)).astype(np.float32)
+    xi[:, 0] = 127.0                                  # amax 127 -> activation scale exactly 1
+    a_bits = wl.f32_to_bf16_bits(xi)                  # integers up to 127 are exact in bf16
+    e = np.zeros(S, dtype=np.int32)
+    y = _run(a_bits, e, [qm], S, 1)
+    ref = xi.astype(np.int64) @ q.astype(np.int64).T
+    assert np.array_equal(y.reshape(S, n).astype(np.int64), ref)
+
+
+def test_decode_shape_llama_gate_matrix():
+    """One decode-shaped problem at full width: 64 rows over 4 experts of an 11008 x 4096 matrix."""
+    cfg = wl.get_config("llama7b_mlp_decode")
+    rng = np.random.default_rng(4)
+    w = (rng.standard_normal((cfg.F, cfg.D)) * 0.02).astype(np.float32)
+    qms = [oc.quantize(w, s.bits, s.group, s.symmetric, s.clip, s.act_mode) for s in cfg.experts]
+    a_bits = wl.make_activations(cfg).reshape(cfg.S, cfg.D)
+    e = rng.integers(0, 4, cfg.S).astype(np.int32)
+    y = _run(a_bits, e, qms, cfg.S, 1)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, qms, cfg.S, 1))
+    assert ok, worst

@@ -7,10 +7,10 @@
 // otherwise) and streams them along k with several tiles in flight; the lanes' packed codes
 // are already ordered as matrix-core operands, so a tile goes
 //     16-byte load -> a handful of bit operations -> bf16 MFMA
-// with no shuffles and no LDS.  Integer codes enter the matrix cores exactly (bf16 holds
-// every integer up to 256) with a constant offset; a second MFMA against an all-ones operand
+// with no shuffles and no LDS.  Integer codes enter the matrix cores exactly, as the bf16
+// value BASE + c/2 (or c for 8-bit codes), i.e. with a constant offset; a second MFMA against an all-ones operand
 // gives the row sums of the activations over the same columns, which removes offset and
-// zero-point exactly: sum_k x (c + off) - (off + z) sum_k x.  The fp32 scale multiplies the
+// zero-point exactly: sum_k x (off + c) - (off + z) sum_k x.  The fp32 scale multiplies the
 // fp32 partial sum of each group, so no weight is ever rounded.
 #include "moqe_internal.h"
 
@@ -23,7 +23,19 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NS = 2;        // weight tiles (streams) per wave
 constexpr int MT = 2;        // 16-row activation tiles per pass (32 bucket rows)
-constexpr uint32_t MAGIC = 0x43004300u;   // two bf16 values 128.0: OR-ing a code c < 128 gives 128 + c
+
+// How a stored code c appears to the matrix cores: the bf16 value BASE + CM * c.
+//   FMT_I8 : c itself (converted through fp32; integers up to 255 are exact in bf16).
+//   nibble / bit-plane formats: the code bits are OR-ed into the top mantissa bits of the bf16
+//   constant BASE = 2^e, whose mantissa step is BASE/128, so that the value is BASE + c/2.
+//   A small BASE keeps sum_k x (BASE + c/2) close in size to the wanted sum_k x (c - z), which
+//   limits the cancellation error of removing the offset afterwards.
+template <int FMT> struct CodeMap;
+template <> struct CodeMap<FMT_I8>   { static constexpr float BASE = 0.f,  CM = 1.f;  };
+template <> struct CodeMap<FMT_I8A8> { static constexpr float BASE = 0.f,  CM = 1.f;  };
+template <> struct CodeMap<FMT_N4>   { static constexpr float BASE = 8.f,  CM = 0.5f; };   // 0x4100 | c << 3
+template <> struct CodeMap<FMT_N3>   { static constexpr float BASE = 4.f,  CM = 0.5f; };   // 0x4080 | c << 4
+template <> struct CodeMap<FMT_N6>   { static constexpr float BASE = 32.f, CM = 0.5f; };   // 0x4200 | c << 1
 
 template <int FMT> struct Raw;
 template <> struct Raw<FMT_I8>   { static constexpr int N = 8; static constexpr int PF = 2; };
@@ -57,7 +69,7 @@ template <int SH> static __device__ __forceinline__ uint32_t shift_by(uint32_t v
 }
 
 // The matrix-core operand of step J (columns 32J + 8kq + 0..7 of the lane's row) as 8 bf16
-// values code + 128 (code itself for FMT_I8).
+// values BASE + CM * code.
 template <int FMT, int J>
 static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N]) {
   u32x4 d;
@@ -74,25 +86,25 @@ static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N]) 
     d.w = __builtin_amdgcn_perm(f7, f6, 0x07060302u);
   } else if constexpr (FMT == FMT_N4) {
     const uint32_t w = r[J];
-    d.x = (w & 0x000F000Fu) | MAGIC;
-    d.y = ((w >> 4) & 0x000F000Fu) | MAGIC;
-    d.z = ((w >> 8) & 0x000F000Fu) | MAGIC;
-    d.w = ((w >> 12) & 0x000F000Fu) | MAGIC;
+    d.x = (shift_by<-3>(w) & 0x00780078u) | 0x41004100u;
+    d.y = (shift_by<1>(w) & 0x00780078u) | 0x41004100u;
+    d.z = (shift_by<5>(w) & 0x00780078u) | 0x41004100u;
+    d.w = (shift_by<9>(w) & 0x00780078u) | 0x41004100u;
   } else if constexpr (FMT == FMT_N3) {
     const uint32_t lo = r[J / 2], hi = r[2];
     constexpr int P0 = 4 * (J % 2);       // first 2-bit field of this step inside `lo`
     constexpr int Q0 = 4 * J;             // first 1-bit field of this step inside `hi`
-    d.x = ((lo >> (2 * (P0 + 0))) & 0x00030003u) | (shift_by<Q0 + 0 - 2>(hi) & 0x00040004u) | MAGIC;
-    d.y = ((lo >> (2 * (P0 + 1))) & 0x00030003u) | (shift_by<Q0 + 1 - 2>(hi) & 0x00040004u) | MAGIC;
-    d.z = ((lo >> (2 * (P0 + 2))) & 0x00030003u) | (shift_by<Q0 + 2 - 2>(hi) & 0x00040004u) | MAGIC;
-    d.w = ((lo >> (2 * (P0 + 3))) & 0x00030003u) | (shift_by<Q0 + 3 - 2>(hi) & 0x00040004u) | MAGIC;
+    d.x = (shift_by<2 * (P0 + 0) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 0 - 6>(hi) & 0x00400040u) | 0x40804080u;
+    d.y = (shift_by<2 * (P0 + 1) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 1 - 6>(hi) & 0x00400040u) | 0x40804080u;
+    d.z = (shift_by<2 * (P0 + 2) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 2 - 6>(hi) & 0x00400040u) | 0x40804080u;
+    d.w = (shift_by<2 * (P0 + 3) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 3 - 6>(hi) & 0x00400040u) | 0x40804080u;
   } else {  // FMT_N6
     const uint32_t w = r[J], hi = r[4 + J / 2];
     constexpr int P0 = 4 * (J % 2);
-    d.x = (w & 0x000F000Fu) | (shift_by<2 * (P0 + 0) - 4>(hi) & 0x00300030u) | MAGIC;
-    d.y = ((w >> 4) & 0x000F000Fu) | (shift_by<2 * (P0 + 1) - 4>(hi) & 0x00300030u) | MAGIC;
-    d.z = ((w >> 8) & 0x000F000Fu) | (shift_by<2 * (P0 + 2) - 4>(hi) & 0x00300030u) | MAGIC;
-    d.w = ((w >> 12) & 0x000F000Fu) | (shift_by<2 * (P0 + 3) - 4>(hi) & 0x00300030u) | MAGIC;
+    d.x = (shift_by<-1>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 0) - 5>(hi) & 0x00600060u) | 0x42004200u;
+    d.y = (shift_by<3>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 1) - 5>(hi) & 0x00600060u) | 0x42004200u;
+    d.z = (shift_by<7>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 2) - 5>(hi) & 0x00600060u) | 0x42004200u;
+    d.w = (shift_by<11>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 3) - 5>(hi) & 0x00600060u) | 0x42004200u;
   }
   return __builtin_bit_cast(bf16x8, d);
 }
@@ -141,8 +153,9 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   }
   const int chunk = (KT + ga.ksplit - 1) / ga.ksplit;
   const int kt0 = ks * chunk, kt1 = min(KT, kt0 + chunk);
-  const float cbase = (FMT == FMT_I8) ? 0.f : 128.f;
-  const float off_sym = cbase + float(ex.zc);
+  // sum_k x (c - z) = (1/CM) * (sum_k x (BASE + CM c) - (BASE + CM z) sum_k x)
+  constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
+  const float off_sym = BASE + CM * float(ex.zc);
 
   const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
@@ -305,8 +318,8 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
                         v = mfma_bf16(afr[ab][1][mt], b1, v);
                         v = mfma_bf16(afr[ab][2][mt], b2, v);
                         v = mfma_bf16(afr[ab][3][mt], b3, v);
-                        const float o = ex.asym ? 128.f + float(zp[p][s] & 0xffu) : off_sym;
-                        const float scv = sc[p][s][0];
+                        const float o = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
+                        const float scv = sc[p][s][0] * INV_CM;
 #pragma unroll
                         for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
                       } else {
@@ -315,9 +328,9 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
                         v0 = mfma_bf16(afr[ab][1][mt], b1, v0);
                         v1 = mfma_bf16(afr[ab][2][mt], b2, v1);
                         v1 = mfma_bf16(afr[ab][3][mt], b3, v1);
-                        const float o0 = ex.asym ? 128.f + float(zp[p][s] & 0xffu) : off_sym;
-                        const float o1 = ex.asym ? 128.f + float((zp[p][s] >> 8) & 0xffu) : off_sym;
-                        const float s0 = sc[p][s][0], s1 = sc[p][s][GPT == 2 ? 1 : 0];
+                        const float o0 = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
+                        const float o1 = ex.asym ? BASE + CM * float((zp[p][s] >> 8) & 0xffu) : off_sym;
+                        const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                           tot[s][mt][r] += s0 * (v0[r] - o0 * xs[mt][0][r]);
@@ -410,7 +423,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
                 const float sx = ga.a_scale[size_t(off_e) * T + m];
                 val[s] = float(__float_as_int(tot[s][mt][r])) * sx * pcs[s];
               } else if constexpr (GM == GM_PC) {
-                val[s] = pcs[s] * (tot[s][mt][r] - off_sym * xs_tot[mt][r]);
+                val[s] = (pcs[s] * INV_CM) * (tot[s][mt][r] - off_sym * xs_tot[mt][r]);
               } else {
                 val[s] = tot[s][mt][r];
               }

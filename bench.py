@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed forward pass through quantization experts on one MI355X.
+
+A step is one moqe_forward over one batch of the workload: route -> bucket -> grouped
+dequantize-GEMM gate/up with the fused SiLU gate -> grouped dequantize-GEMM down -> scatter.
+Default workload: the LLaMA-7B-shaped MLP block in decode (64 sequences x 1 token, 4 experts),
+synthetic seeded tensors.  Inputs are resident in HBM before the timed region.  Prints ONE JSON
+line with the throughput, the roofline of the dominant kernel (measured with HIP events on the
+launch stream during the timed steps) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def algorithmic_weight_bytes(n, k, spec):
+    """Bytes the format defines for one matrix: packed code bits + fp32 scales + u8 zero-points."""
+    code = n * k * spec.bits // 8
+    if spec.group:
+        meta = n * (k // spec.group) * (4 + (0 if spec.symmetric else 1))
+    else:
+        meta = n * 4
+    return code + meta
+
+
+def build_device_block(cfg, n_copies):
+    """Quantizes and packs the experts ON THE GPU through the library; returns `n_copies` blocks that
+    share the router but own separate copies of the packed weights (rotated between steps so that a
+    step never finds its weights in the last-level cache from the step before)."""
+    import torch
+    import workloads as wl
+    from paper_2508_09204_amd import binding as mq, experts as ex
+
+    dev = "cuda:0"
+    fpw = wl.make_fp_weights(cfg)
+    r = wl.make_router(cfg)
+    td = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    router = mq.Router(td(r["w1"]), td(r["b1"]), td(r["w2"]), td(r["b2"]), cfg.D, cfg.router_hidden, cfg.K)
+    packed = {}
+    for name, w in fpw.items():
+        wd = torch.from_numpy(w).to(dev)
+        packed[name] = [ex.quantize_and_pack(wd, e.bits, e.group, e.symmetric, e.clip, e.act_mode) for e in cfg.experts]
+        del wd
+    torch.cuda.synchronize()
+
+    def clone(qm):
+        return mq.QMat(qm.qdata.clone(), None, None, qm.n, qm.k, qm.bits, qm.group, qm.symmetric, qm.act_mode, qm.layout)
+
+    blocks = []
+    for c in range(n_copies):
+        pk = packed if c == 0 else {n: [clone(q) for q in v] for n, v in packed.items()}
+        if cfg.kind == wl.configs.KIND_SILU_MLP:
+            blocks.append(mq.Block(cfg.kind, router, pk["gate"], pk["up"], pk["down"]))
+        else:
+            blocks.append(mq.Block(cfg.kind, router, pk["w0"], img_h=cfg.img_h, img_w=cfg.img_w,
+                                   cin=cfg.D if cfg.kind == wl.configs.KIND_CONV3X3 else 0))
+    return blocks
+
+
+def cpu_baseline(cfg, max_seconds_hint=30.0):
+    """The oracle as it stands, timed on the host: the whole forward for the decode workload,
+    a bounded number of sequences for larger ones."""
+    import numpy as np
+    import workloads as wl
+    from oracle import moqe_oracle as oc
+    from tests import oracle_blocks as ob
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    blk = ob.make_block(cfg)                      # quantization is offline work: not timed
+    bits = wl.make_activations(cfg)
+    x64 = oc.bf16_bits_to_f64(bits)
+    if cfg.M <= 256:
+        n_s, rows, sample = cfg.S, None, f"all {cfg.S} samples x {cfg.T} rows"
+    elif cfg.kind == wl.configs.KIND_CONV3X3:
+        n_s, rows = min(cfg.S, 32), None
+        sample = f"first {n_s} images, whole images"
+    else:
+        n_s, rows = min(cfg.S, 16), [0, cfg.T // 2, cfg.T - 1]
+        sample = f"first {n_s} samples, 3 rows each (all columns)"
+    t0 = time.perf_counter()
+    y, idx, _ = oc.forward(blk, x64[:n_s], rows=rows)
+    dt = time.perf_counter() - t0
+    units = y.shape[0] * y.shape[1] if cfg.unit == "tokens" else y.shape[0]
+    return {"value": units / dt, "unit": f"{cfg.unit}/s", "cores": int(cores), "kind": "oracle",
+            "sample": sample + f"; {dt:.1f} s wall, dequantization of the routed experts included"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama7b_mlp_decode")
+    ap.add_argument("--copies", type=int, default=0, help="rotating weight copies (0 = pick so that they exceed 1 GiB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (samples would shard across GPUs with no collective); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2508_09204_amd import binding as mq
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    cfg = wl.get_config(args.workload)
+    is_mlp = cfg.kind == wl.configs.KIND_SILU_MLP
+    mats = cfg.matrices()
+    per_expert_bytes = [sum(algorithmic_weight_bytes(n, k, e) for (n, k) in mats.values()) for e in cfg.experts]
+    n_copies = args.copies or max(2, min(8, -(-(1 << 30) // sum(per_expert_bytes))))
+    blocks = build_device_block(cfg, n_copies)
+
+    dev = "cuda:0"
+    bits = wl.make_activations(cfg)
+    x = torch.from_numpy(bits.view("int16").reshape(cfg.M, cfg.D)).to(dev).view(torch.bfloat16)
+    n_out = cfg.D if is_mlp else cfg.F
+    y = torch.empty((cfg.M, n_out), dtype=torch.float32, device=dev)
+    counts = torch.zeros(cfg.K, dtype=torch.int32, device=dev)
+    aux = mq.Aux(counts=counts)
+    calls = [mq.ForwardCall(b, x, cfg.S, cfg.T, y, aux) for b in blocks]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    dominant = mq.PK_GEMM_GATEUP if is_mlp else mq.PK_GEMM_PLAIN
+    mq.moqe_profile_enable(1 << dominant)          # warm the event pool before the timed region
+    for i in range(args.warmup):
+        calls[i % n_copies](stream)
+    torch.cuda.synchronize()
+    mq.moqe_profile_enable(1 << dominant)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        calls[i % n_copies](stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    launches, kern_ms = mq.moqe_profile_read(dominant)
+    mq.moqe_profile_enable(0)
+
+    hist = counts.cpu().tolist()
+    ms_per_step = dt * 1e3 / args.steps
+    units = cfg.M if cfg.unit == "tokens" else cfg.S
+    value = units / (dt / args.steps)
+    kern_us = kern_ms * 1e3 / max(launches, 1)
+
+    # algorithmic bytes / flops of the dominant kernel per launch: each non-empty expert's matrices once
+    if is_mlp:
+        dom_mats = [mats["gate"], mats["up"]]
+    else:
+        dom_mats = list(mats.values())
+    dom_bytes = sum(sum(algorithmic_weight_bytes(n, k, e) for (n, k) in dom_mats)
+                    for e, c in zip(cfg.experts, hist) if c > 0)
+    dom_flops = sum(2.0 * c * cfg.T * sum(n * k for (n, k) in dom_mats) for c in hist)
+    hbm_bound = cfg.M <= 1024
+    if hbm_bound:
+        achieved = dom_bytes / (kern_us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+    else:
+        achieved = dom_flops / (kern_us * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    roof["kernel"] = "k_qgemm_stream<gate/up + SiLU>" if is_mlp else "k_qgemm_stream<plain>"
+    roof["kernel_us"] = kern_us
+    roof["launches_timed"] = launches
+    roof["algorithmic_bytes_per_launch"] = dom_bytes
+    roof["algorithmic_flops_per_launch"] = dom_flops
+
+    out = {
+        "metric": "routed qGEMM throughput (whole routed block: route + bucket + grouped qGEMMs + scatter)",
+        "value": value, "unit": f"{cfg.unit}/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic (seeded N(0,1) activations, N(0,0.02) weights quantized by round-to-nearest on the GPU)",
+        "config": {"workload": cfg.name, "samples": cfg.S, "rows_per_sample": cfg.T, "d": cfg.D, "f": cfg.F,
+                   "experts": [e.label() for e in cfg.experts], "routing_histogram": hist,
+                   "arithmetic": "bf16 activations x exact integer weight codes on bf16 MFMA, fp32 accumulate and scales",
+                   "rotating_weight_copies": n_copies},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -201,10 +201,11 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
 /* ---- timing ------------------------------------------------------------------------- */
 
 /* Per-kernel timing with HIP events recorded on the stream the kernels are launched on.
- * moqe_profile_enable(1) starts recording (one event pair per launch, at most
- * MOQE_PROFILE_MAX_LAUNCHES launches are kept); moqe_profile_read synchronises the recorded
- * events and returns, for the kernel kind `kind` (MOQE_PK_*), the number of launches seen
- * and their summed duration in milliseconds; moqe_profile_enable(0) stops and discards. */
+ * moqe_profile_enable(mask) discards earlier records and starts recording every launch whose
+ * kernel kind k has bit (1 << k) set in mask (MOQE_PK_*; at most MOQE_PROFILE_MAX_LAUNCHES
+ * launches are kept; mask 0 stops).  moqe_profile_read synchronises the recorded events of one
+ * kind and returns the number of launches seen and their summed duration in milliseconds.
+ * Not thread-safe against concurrent forward calls on other streams' events being reused. */
 #define MOQE_PK_ROUTE      0
 #define MOQE_PK_BUCKET     1
 #define MOQE_PK_GEMM_GATEUP 2
@@ -214,7 +215,7 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
 #define MOQE_PK_OTHER      6
 #define MOQE_PK_COUNT      7
 #define MOQE_PROFILE_MAX_LAUNCHES 65536
-int32_t moqe_profile_enable(int32_t on);
+int32_t moqe_profile_enable(int32_t kind_mask);
 int32_t moqe_profile_read(int32_t kind, int32_t* launches, double* total_ms);
 
 #ifdef __cplusplus

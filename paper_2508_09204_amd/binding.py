@@ -260,8 +260,8 @@ def moqe_forward(blk: Block, x: torch.Tensor, S: int, T: int, y: torch.Tensor, a
                             _ptr(workspace), workspace.numel(), _stream()))
 
 
-def moqe_profile_enable(on: bool) -> None:
-    _check(lib.moqe_profile_enable(int(on)))
+def moqe_profile_enable(kind_mask: int) -> None:
+    _check(lib.moqe_profile_enable(int(kind_mask)))
 
 
 def moqe_profile_read(kind: int):

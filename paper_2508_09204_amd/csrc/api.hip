@@ -33,33 +33,33 @@ int32_t check_launch(const char* what) {
 }
 
 // ---- profiling ---------------------------------------------------------------------------
-struct ProfRec { hipEvent_t a, b; int kind; };
+// Event pairs come from a pool that only grows, so that recording inside a timed region costs two
+// hipEventRecord calls per launch and no event creation once the pool is warm.
+struct ProfRec { int ev; int kind; };
 static std::mutex g_prof_mu;
-static bool g_prof_on = false;
+static uint32_t g_prof_mask = 0;
 static std::vector<ProfRec> g_prof;
+static std::vector<hipEvent_t> g_pool;     // events 2i, 2i+1 form pair i
 
 ProfileScope::ProfileScope(int kind, hipStream_t s) : slot(-1), stream(s) {
-  if (!g_prof_on) return;
+  if (!((g_prof_mask >> kind) & 1u)) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  if (!g_prof_on || g_prof.size() >= MOQE_PROFILE_MAX_LAUNCHES) return;
-  ProfRec r;
-  r.kind = kind;
-  if (hipEventCreate(&r.a) != hipSuccess) return;
-  if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return; }
-  (void)hipEventRecord(r.a, s);
-  g_prof.push_back(r);
-  slot = int(g_prof.size()) - 1;
+  if (!((g_prof_mask >> kind) & 1u) || g_prof.size() >= MOQE_PROFILE_MAX_LAUNCHES) return;
+  const size_t pair = g_prof.size();
+  while (g_pool.size() < 2 * (pair + 1)) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    g_pool.push_back(e);
+  }
+  (void)hipEventRecord(g_pool[2 * pair], s);
+  g_prof.push_back(ProfRec{int(pair), kind});
+  slot = int(pair);
 }
 
 ProfileScope::~ProfileScope() {
   if (slot < 0) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  if (slot < int(g_prof.size())) (void)hipEventRecord(g_prof[slot].b, stream);
-}
-
-static void prof_clear_locked() {
-  for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-  g_prof.clear();
+  if (size_t(2 * slot + 1) < g_pool.size()) (void)hipEventRecord(g_pool[2 * slot + 1], stream);
 }
 
 // ---- validation helpers --------------------------------------------------------------------
@@ -417,10 +417,10 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
 }
 
 // ---- timing --------------------------------------------------------------------------------
-int32_t moqe_profile_enable(int32_t on) {
+int32_t moqe_profile_enable(int32_t kind_mask) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  prof_clear_locked();
-  g_prof_on = on != 0;
+  g_prof.clear();
+  g_prof_mask = uint32_t(kind_mask) & ((1u << MOQE_PK_COUNT) - 1u);
   return MOQE_OK;
 }
 
@@ -432,10 +432,11 @@ int32_t moqe_profile_read(int32_t kind, int32_t* launches, double* total_ms) {
   double ms = 0.0;
   for (auto& r : g_prof) {
     if (r.kind != kind) continue;
-    hipError_t err = hipEventSynchronize(r.b);
+    hipEvent_t a = g_pool[2 * r.ev], b = g_pool[2 * r.ev + 1];
+    hipError_t err = hipEventSynchronize(b);
     if (err != hipSuccess) return set_error(MOQE_E_HIP, "moqe_profile_read: %s", hipGetErrorString(err));
     float t = 0.f;
-    err = hipEventElapsedTime(&t, r.a, r.b);
+    err = hipEventElapsedTime(&t, a, b);
     if (err != hipSuccess) return set_error(MOQE_E_HIP, "moqe_profile_read: %s", hipGetErrorString(err));
     ms += double(t);
     ++n;

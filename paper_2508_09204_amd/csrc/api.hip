@@ -113,15 +113,6 @@ static void order_experts(GemmArgs* ga) {
   for (int i = 0; i < ga->n_experts; ++i) ga->order[i] = idx[i];
 }
 
-static int choose_ksplit(int k, int ntasks, int n_experts) {
-  const int KT = k / 128;
-  // enough independent waves to keep every CU streaming; long rows are split across the waves of a group
-  const long waves = long(ntasks) * n_experts;
-  if (KT >= 64 && waves < 256L * 16) return 4;
-  if (KT >= 16 && waves < 256L * 16) return 2;
-  return 1;
-}
-
 // Workspace for the int8 copies of activation rows needed by act_mode-1 experts.
 static size_t a8_bytes(bool any_a8, int M, int kmax) {
   if (!any_a8) return 0;
@@ -157,6 +148,8 @@ static int32_t plan_experts(const moqe_qmat* experts, int K, const moqe_qmat* se
 static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t* a_perm, const int32_t* y_perm, int S, int T,
                            const moqe_qmat* experts, const moqe_qmat* second, int K, const GroupedPlan& gp, void* y,
                            uint8_t* a8_ws, hipStream_t st) {
+  if (size_t(S) * size_t(T) * size_t(experts[0].k) * 2 >= (size_t(1) << 32))
+    return set_error(MOQE_E_SHAPE, "grouped_qgemm: activation matrix of %d x %d exceeds 4 GiB", S * T, experts[0].k);
   GemmArgs ga;
   memset(&ga, 0, sizeof(ga));
   ga.n_experts = K;
@@ -176,9 +169,6 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
       if (rc) return rc;
     }
   }
-  const int NT = ga.n / 16;
-  const int ntasks = second ? NT : (NT + 1) / 2;
-  ga.ksplit = choose_ksplit(ga.k, ntasks, K);
   return launch_qgemm_stream(ga, second != nullptr, st);
 }
 

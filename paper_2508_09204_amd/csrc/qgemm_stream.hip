@@ -42,7 +42,7 @@ template <> struct Raw<FMT_I8>   { static constexpr int N = 8; static constexpr 
 template <> struct Raw<FMT_I8A8> { static constexpr int N = 8; static constexpr int PF = 2; };
 template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr int PF = 4; };
 template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 4; };
-template <> struct Raw<FMT_N6>   { static constexpr int N = 6; static constexpr int PF = 3; };
+template <> struct Raw<FMT_N6>   { static constexpr int N = 6; static constexpr int PF = 2; };
 
 template <int FMT>
 static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], const uint8_t* tile, int lane) {
@@ -123,61 +123,123 @@ static __device__ __forceinline__ float silu_mul(float g, float u) {
   return (g / (1.0f + __expf(-g))) * u;
 }
 
-// One task: the wave's two weight tiles against the rows of one expert's bucket, over the
-// k-tiles [kt0, kt1).  `red` is this work-group's LDS reduction area.
+// Work-group geometry (runtime, uniform): W waves = WN tasks x WK k-slices.  A task is a pair
+// of weight tiles; slice ks of a task covers the k-tiles [ks*ceil(KT/WK), ...).  The activation
+// rows of the pass (at most 32) are staged in LDS once per work-group and chunk of TPC k-tiles
+// per slice, double-buffered, and shared by all waves, so activations cross the L2 once per
+// work-group instead of once per wave.
+struct Geom {
+  int wn, wk, tpc;      // tasks per work-group, k-slices, k-tiles per chunk (wk * tpc == 4)
+};
+
+constexpr int ROWS = 16 * MT;                 // bucket rows per pass
+constexpr int KCHUNK_TOTAL = 512;             // columns staged per chunk over all slices
+constexpr int WAVES = 8;                      // waves per work-group
+constexpr int AU_MAX = 4;                     // 16-byte units a thread stages per chunk, at most
+
+template <bool A8> __host__ __device__ constexpr int a_row_stride(int kc) { return kc * (A8 ? 1 : 2) + 16; }
+
+// LDS bytes: two activation buffers (bf16 worst case); the k-slice reduction reuses them.
+static constexpr int LDS_BYTES = 2 * 4 * ROWS * (128 * 2 + 16) > 2 * ROWS * (512 * 2 + 16)
+                                     ? 2 * 4 * ROWS * (128 * 2 + 16) : 2 * ROWS * (512 * 2 + 16);
+
 template <int FMT, int GM, bool GATEUP>
-static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int task,
-                                                   const int ks, const bool active_task, float* red) {
+static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int wgi,
+                                                   uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
   constexpr int PF = Raw<FMT>::PF;
+  static_assert(4 % PF == 0, "the tile loop is unrolled by four and indexes the prefetch ring statically");
   constexpr int NR = Raw<FMT>::N;
   constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int EB = A8 ? 1 : 2;              // bytes per activation element
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lq = lane >> 4;
   const int KT = ga.k >> 7, NT = ga.n >> 4;
   const int T = ga.T;
+  const int wk = ga.wk, tpc = ga.tpc;
   const int off_e = ga.offsets[e];
   const int M_e = (ga.offsets[e + 1] - off_e) * T;
   if (M_e <= 0) return;                       // uniform over the work-group (one expert per work-group)
+
+  const int ks = wave % wk;
+  const int task = wgi * ga.wn + wave / wk;
+  const int ntasks = GATEUP ? NT : (NT + 1) / 2;
+  const bool active_task = task < ntasks;
 
   int nt[NS];
   bool sv[NS];
   const uint8_t* blob[NS];
   if constexpr (GATEUP) {
-    nt[0] = nt[1] = task; sv[0] = sv[1] = active_task && task < NT;
+    nt[0] = nt[1] = task; sv[0] = sv[1] = active_task;
     blob[0] = ex.w[0]; blob[1] = ex.w[1];
   } else {
     nt[0] = 2 * task; nt[1] = 2 * task + 1;
     sv[0] = active_task && nt[0] < NT; sv[1] = active_task && nt[1] < NT;
     blob[0] = blob[1] = ex.w[0];
   }
-  const int chunk = (KT + ga.ksplit - 1) / ga.ksplit;
-  const int kt0 = ks * chunk, kt1 = min(KT, kt0 + chunk);
+  const int slice_tiles = (KT + wk - 1) / wk;              // k-tiles per slice (last slice may be shorter)
+  const int kt0 = ks * slice_tiles, kt1 = min(KT, kt0 + slice_tiles);
+  const int n_chunks = (slice_tiles + tpc - 1) / tpc;
+  const int KC = 128 * tpc;                                // columns per slice and chunk
+  const int rstride = a_row_stride<A8>(KC);
+  const int buf_bytes = wk * ROWS * rstride;
+
   // sum_k x (c - z) = (1/CM) * (sum_k x (BASE + CM c) - (BASE + CM z) sum_k x)
   constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
   const float off_sym = BASE + CM * float(ex.zc);
-
   const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
 
-  for (int pass0 = 0; pass0 < M_e; pass0 += 16 * MT) {
-    // ---- rows of this pass: operand rows (lane's row lr) and result rows (4*lq + r) ----
-    const uint8_t* arow[MT];
-    bool avalid[MT];
+  // ---- staging plan: which 16-byte units of a chunk this thread copies -----------------------
+  const int upr = KC * EB / 16;                            // units per row
+  const int n_units = wk * ROWS * upr;
+
+  for (int pass0 = 0; pass0 < M_e; pass0 += ROWS) {
+    const int rows_here = min(ROWS, M_e - pass0);
+    // Per staged unit: byte offset of its chunk-0 source from the activation base, and how many
+    // bytes of the row remain inside the slice from there (0: the unit is zero-filled).
+    const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
+    uint32_t uoff[AU_MAX];
+    int ukend[AU_MAX];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = pass0 + mt * 16 + lr;
-      avalid[mt] = m < M_e;
-      const int mm = avalid[mt] ? m : 0;
-      if constexpr (A8) {
-        arow[mt] = reinterpret_cast<const uint8_t*>(ga.a_q) + (size_t(off_e) * T + mm) * size_t(ga.k);
-      } else {
-        size_t src;
-        if (ga.a_perm) src = size_t(ga.a_perm[off_e + mm / T]) * T + (mm % T);
-        else src = size_t(off_e) * T + mm;
-        arow[mt] = reinterpret_cast<const uint8_t*>(ga.a) + src * size_t(ga.k) * 2;
+    for (int i = 0; i < AU_MAX; ++i) {
+      const int u = tid + i * nthreads;
+      uoff[i] = 0u; ukend[i] = 0;
+      if (u < n_units) {
+        const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
+        const int sk0 = sl * slice_tiles, sk1 = min(KT, sk0 + slice_tiles);
+        if (row < rows_here && sk0 < sk1) {
+          const int m = pass0 + row;
+          size_t src;
+          if constexpr (A8) src = size_t(off_e) * T + m;
+          else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
+          else src = size_t(off_e) * T + m;
+          uoff[i] = uint32_t((src * size_t(ga.k) + size_t(sk0) * 128) * EB + cu * 16);
+          ukend[i] = (sk1 - sk0) * 128 * EB - cu * 16;
+        }
       }
     }
+    u32x4 areg[AU_MAX];
+    auto a_fetch = [&](int c) {       // global -> registers, chunk c
+      const int koff = c * KC * EB;
+#pragma unroll
+      for (int i = 0; i < AU_MAX; ++i) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (koff < ukend[i]) v = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + koff);
+        areg[i] = v;
+      }
+    };
+    auto a_store = [&](int buf) {     // registers -> LDS buffer
+#pragma unroll
+      for (int i = 0; i < AU_MAX; ++i) {
+        const int u = tid + i * nthreads;
+        if (u < n_units) {
+          const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
+          *reinterpret_cast<u32x4*>(lds + buf * buf_bytes + (sl * ROWS + row) * rstride + cu * 16) = areg[i];
+        }
+      }
+    };
 
     f32x4 tot[NS][MT];     // bf16 path: fp32 results; int8 path: int32 bit patterns
     f32x4 xs_tot[MT];      // per-channel formats: running row sums of the activations
@@ -188,169 +250,170 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
       for (int s = 0; s < NS; ++s) tot[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    if (kt0 < kt1 && (sv[0] || sv[1])) {
-      uint32_t raw[PF][NS][NR];
-      float sc[PF][NS][GPT ? GPT : 1];
-      uint32_t zp[PF][NS];
-      u32x4 afr[2][4][MT];     // activation operands of the current and the next k-tile
+    uint32_t raw[PF][NS][NR];
+    float sc[PF][NS][GPT ? GPT : 1];
+    uint32_t zp[PF][NS];
+    const bool wave_has_work = (sv[0] || sv[1]) && kt0 < kt1;
 
-      auto issue_w = [&](int p, int kt) {
+    auto issue_w = [&](int p, int kt) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        if (sv[s]) {
+          const size_t t = size_t(nt[s]) * KT + kt;
+          load_raw<FMT>(raw[p][s], blob[s] + t * ex.tile_bytes, lane);
+          if constexpr (GPT > 0) {
+            const float* sp = reinterpret_cast<const float*>(blob[s] + ex.scale_off) + (t * 16 + lr) * GPT;
+            const uint8_t* zq = blob[s] + ex.zero_off + (t * 16 + lr) * GPT;
+            if constexpr (GPT == 1) {
+              sc[p][s][0] = sp[0];
+              zp[p][s] = ex.asym ? uint32_t(zq[0]) : 0u;
+            } else {
+              float2 v = *reinterpret_cast<const float2*>(sp);
+              sc[p][s][0] = v.x; sc[p][s][1] = v.y;
+              zp[p][s] = ex.asym ? uint32_t(*reinterpret_cast<const uint16_t*>(zq)) : 0u;
+            }
+          }
+        }
+      }
+    };
+
+    // One k-tile: activation operands come from LDS (tile `tl` of the current chunk buffer).
+    auto consume = [&](int p, const uint8_t* abuf, int tl) {
+      const uint8_t* arow0 = abuf + (ks * ROWS + lr) * rstride + tl * 128 * EB;
+      if constexpr (A8) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          if (mt * 16 < rows_here) {
+            i32x4 a0 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * rstride + lq * 16);
+            i32x4 a1 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * rstride + 64 + lq * 16);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+              if (sv[s]) {
+                i32x4 acc = __builtin_bit_cast(i32x4, tot[s][mt]);
+                i32x4 b0 = {int(raw[p][s][0]), int(raw[p][s][1]), int(raw[p][s][2]), int(raw[p][s][3])};
+                i32x4 b1 = {int(raw[p][s][4]), int(raw[p][s][5]), int(raw[p][s][6]), int(raw[p][s][7])};
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, acc, 0, 0, 0);
+                tot[s][mt] = __builtin_bit_cast(f32x4, acc);
+              }
+            }
+          }
+        }
+      } else {
+        u32x4 af[MT][4];
+        f32x4 xs[MT][GPT ? GPT : 1];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          if (mt * 16 < rows_here) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              af[mt][j] = *reinterpret_cast<const u32x4*>(arow0 + mt * 16 * rstride + (j * 32 + lq * 8) * 2);
+            if constexpr (GM == GM_PC) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) xs_tot[mt] = mfma_bf16(af[mt][j], ones_b, xs_tot[mt]);
+            } else if constexpr (GM == GM_G128) {
+              f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+              for (int j = 0; j < 4; ++j) v = mfma_bf16(af[mt][j], ones_b, v);
+              xs[mt][0] = v;
+            } else {
+#pragma unroll
+              for (int h = 0; h < 2; ++h) {
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                v = mfma_bf16(af[mt][2 * h], ones_b, v);
+                v = mfma_bf16(af[mt][2 * h + 1], ones_b, v);
+                xs[mt][h] = v;
+              }
+            }
+          }
+        }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
           if (sv[s]) {
-            const size_t t = size_t(nt[s]) * KT + kt;
-            load_raw<FMT>(raw[p][s], blob[s] + t * ex.tile_bytes, lane);
-            if constexpr (GPT > 0) {
-              const float* sp = reinterpret_cast<const float*>(blob[s] + ex.scale_off) + (t * 16 + lr) * GPT;
-              const uint8_t* zq = blob[s] + ex.zero_off + (t * 16 + lr) * GPT;
-              if constexpr (GPT == 1) {
-                sc[p][s][0] = sp[0];
-                zp[p][s] = ex.asym ? uint32_t(zq[0]) : 0u;
-              } else {
-                float2 v = *reinterpret_cast<const float2*>(sp);
-                sc[p][s][0] = v.x; sc[p][s][1] = v.y;
-                zp[p][s] = ex.asym ? uint32_t(*reinterpret_cast<const uint16_t*>(zq)) : 0u;
+            const bf16x8 b0 = frag<FMT, 0>(raw[p][s]);
+            const bf16x8 b1 = frag<FMT, 1>(raw[p][s]);
+            const bf16x8 b2 = frag<FMT, 2>(raw[p][s]);
+            const bf16x8 b3 = frag<FMT, 3>(raw[p][s]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              if (mt * 16 < rows_here) {
+                if constexpr (GM == GM_PC) {
+                  f32x4 v = tot[s][mt];
+                  v = mfma_bf16(af[mt][0], b0, v);
+                  v = mfma_bf16(af[mt][1], b1, v);
+                  v = mfma_bf16(af[mt][2], b2, v);
+                  v = mfma_bf16(af[mt][3], b3, v);
+                  tot[s][mt] = v;
+                } else if constexpr (GM == GM_G128) {
+                  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                  v = mfma_bf16(af[mt][0], b0, v);
+                  v = mfma_bf16(af[mt][1], b1, v);
+                  v = mfma_bf16(af[mt][2], b2, v);
+                  v = mfma_bf16(af[mt][3], b3, v);
+                  const float o = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
+                  const float scv = sc[p][s][0] * INV_CM;
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
+                } else {
+                  f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+                  v0 = mfma_bf16(af[mt][0], b0, v0);
+                  v0 = mfma_bf16(af[mt][1], b1, v0);
+                  v1 = mfma_bf16(af[mt][2], b2, v1);
+                  v1 = mfma_bf16(af[mt][3], b3, v1);
+                  const float o0 = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
+                  const float o1 = ex.asym ? BASE + CM * float((zp[p][s] >> 8) & 0xffu) : off_sym;
+                  const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) {
+                    tot[s][mt][r] += s0 * (v0[r] - o0 * xs[mt][0][r]);
+                    tot[s][mt][r] += s1 * (v1[r] - o1 * xs[mt][GPT == 2 ? 1 : 0][r]);
+                  }
+                }
               }
             }
           }
         }
-      };
-      auto issue_a = [&](int buf, int kt) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          if (pass0 + mt * 16 < M_e) {
-            if constexpr (A8) {
-#pragma unroll
-              for (int js = 0; js < 2; ++js) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (avalid[mt]) v = *reinterpret_cast<const u32x4*>(arow[mt] + size_t(kt) * 128 + js * 64 + lq * 16);
-                afr[buf][js][mt] = v;
-              }
-            } else {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (avalid[mt]) v = *reinterpret_cast<const u32x4*>(arow[mt] + (size_t(kt) * 128 + j * 32 + lq * 8) * 2);
-                afr[buf][j][mt] = v;
-              }
-            }
-          }
-        }
-      };
+      }
+    };
 
+    // ---- prologue: first weight tiles in flight, chunk 0 of the activations into LDS --------
+    if (wave_has_work) {
 #pragma unroll
       for (int p = 0; p < PF; ++p)
         if (kt0 + p < kt1) issue_w(p, kt0 + p);
-      issue_a(0, kt0);
+    }
+    a_fetch(0);
+    a_store(0);
+    __syncthreads();
 
-      for (int ktb = kt0; ktb < kt1; ktb += 2 * PF) {
+    // ---- main loop over the slice's k-tiles, four per iteration (PF divides 4) --------------
+    const int tiles_padded = n_chunks * tpc;
+    for (int tb = 0; tb < tiles_padded; tb += 4) {
 #pragma unroll
-        for (int pp = 0; pp < 2 * PF; ++pp) {
-          const int p = pp % PF, ab = pp & 1;
-          const int kt = ktb + pp;
-          if (kt < kt1) {
-            if (kt + 1 < kt1) issue_a(ab ^ 1, kt + 1);
-
-            if constexpr (A8) {
-#pragma unroll
-              for (int s = 0; s < NS; ++s) {
-                if (sv[s]) {
-#pragma unroll
-                  for (int mt = 0; mt < MT; ++mt) {
-                    if (pass0 + mt * 16 < M_e) {
-                      i32x4 acc = __builtin_bit_cast(i32x4, tot[s][mt]);
-#pragma unroll
-                      for (int js = 0; js < 2; ++js) {
-                        i32x4 b = {int(raw[p][s][js * 4 + 0]), int(raw[p][s][js * 4 + 1]), int(raw[p][s][js * 4 + 2]),
-                                   int(raw[p][s][js * 4 + 3])};
-                        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, afr[ab][js][mt]), b, acc, 0, 0, 0);
-                      }
-                      tot[s][mt] = __builtin_bit_cast(f32x4, acc);
-                    }
-                  }
-                }
-              }
-            } else {
-              // row sums of the activations over this tile's columns (per group)
-              f32x4 xs[MT][GPT ? GPT : 1];
-#pragma unroll
-              for (int mt = 0; mt < MT; ++mt) {
-                if (pass0 + mt * 16 < M_e) {
-                  if constexpr (GM == GM_PC) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) xs_tot[mt] = mfma_bf16(afr[ab][j][mt], ones_b, xs_tot[mt]);
-                  } else if constexpr (GM == GM_G128) {
-                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) v = mfma_bf16(afr[ab][j][mt], ones_b, v);
-                    xs[mt][0] = v;
-                  } else {
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                      v = mfma_bf16(afr[ab][2 * h][mt], ones_b, v);
-                      v = mfma_bf16(afr[ab][2 * h + 1][mt], ones_b, v);
-                      xs[mt][h] = v;
-                    }
-                  }
-                }
-              }
-#pragma unroll
-              for (int s = 0; s < NS; ++s) {
-                if (sv[s]) {
-                  const bf16x8 b0 = frag<FMT, 0>(raw[p][s]);
-                  const bf16x8 b1 = frag<FMT, 1>(raw[p][s]);
-                  const bf16x8 b2 = frag<FMT, 2>(raw[p][s]);
-                  const bf16x8 b3 = frag<FMT, 3>(raw[p][s]);
-#pragma unroll
-                  for (int mt = 0; mt < MT; ++mt) {
-                    if (pass0 + mt * 16 < M_e) {
-                      if constexpr (GM == GM_PC) {
-                        f32x4 v = tot[s][mt];
-                        v = mfma_bf16(afr[ab][0][mt], b0, v);
-                        v = mfma_bf16(afr[ab][1][mt], b1, v);
-                        v = mfma_bf16(afr[ab][2][mt], b2, v);
-                        v = mfma_bf16(afr[ab][3][mt], b3, v);
-                        tot[s][mt] = v;
-                      } else if constexpr (GM == GM_G128) {
-                        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                        v = mfma_bf16(afr[ab][0][mt], b0, v);
-                        v = mfma_bf16(afr[ab][1][mt], b1, v);
-                        v = mfma_bf16(afr[ab][2][mt], b2, v);
-                        v = mfma_bf16(afr[ab][3][mt], b3, v);
-                        const float o = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
-                        const float scv = sc[p][s][0] * INV_CM;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
-                      } else {
-                        f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
-                        v0 = mfma_bf16(afr[ab][0][mt], b0, v0);
-                        v0 = mfma_bf16(afr[ab][1][mt], b1, v0);
-                        v1 = mfma_bf16(afr[ab][2][mt], b2, v1);
-                        v1 = mfma_bf16(afr[ab][3][mt], b3, v1);
-                        const float o0 = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
-                        const float o1 = ex.asym ? BASE + CM * float((zp[p][s] >> 8) & 0xffu) : off_sym;
-                        const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                          tot[s][mt][r] += s0 * (v0[r] - o0 * xs[mt][0][r]);
-                          tot[s][mt][r] += s1 * (v1[r] - o1 * xs[mt][GPT == 2 ? 1 : 0][r]);
-                        }
-                      }
-                    }
-                  }
-                }
-              }
-            }
-            if (kt + PF < kt1) issue_w(p, kt + PF);
+      for (int q = 0; q < 4; ++q) {
+        const int ti = tb + q;                   // tile index inside the slice
+        if (ti < tiles_padded) {                 // uniform over the work-group
+          const int c = ti / tpc, tl = ti % tpc;
+          if (tl == 0 && c + 1 < n_chunks) a_fetch(c + 1);
+          const int kt = kt0 + ti;
+          if (wave_has_work && kt < kt1) {
+            consume(q % PF, lds + (c & 1) * buf_bytes, tl);
+            if (kt + PF < kt1) issue_w(q % PF, kt + PF);
+          }
+          if (tl == tpc - 1 && c + 1 < n_chunks) {
+            a_store((c + 1) & 1);
+            __syncthreads();
           }
         }
       }
     }
 
     // ---- combine the k-slices of a task (fixed order), then the epilogue -------------------
-    if (ga.ksplit > 1) {
-      float* mine = red + size_t(wave) * (NS * MT * 4 * 64);
+    if (wk > 1) {
+      __syncthreads();                           // everyone is done with the activation buffers
+      float* red = reinterpret_cast<float*>(lds);
+      constexpr int SLOT = (NS * MT + MT) * 4 * 64;
+      float* mine = red + size_t(wave) * SLOT;
       if (ks > 0) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
@@ -358,11 +421,15 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
           for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 4; ++r) mine[((s * MT + mt) * 4 + r) * 64 + lane] = tot[s][mt][r];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) mine[((NS * MT + mt) * 4 + r) * 64 + lane] = xs_tot[mt][r];
       }
       __syncthreads();
       if (ks == 0) {
-        for (int o = 1; o < ga.ksplit; ++o) {
-          const float* other = red + size_t(wave + o) * (NS * MT * 4 * 64);
+        for (int o = 1; o < wk; ++o) {
+          const float* other = red + size_t(wave + o) * SLOT;
 #pragma unroll
           for (int s = 0; s < NS; ++s)
 #pragma unroll
@@ -370,36 +437,14 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
                 const float v = other[((s * MT + mt) * 4 + r) * 64 + lane];
-                if constexpr (A8) {
-                  tot[s][mt][r] = __int_as_float(__float_as_int(tot[s][mt][r]) + __float_as_int(v));
-                } else {
-                  tot[s][mt][r] += v;
-                }
+                if constexpr (A8) tot[s][mt][r] = __int_as_float(__float_as_int(tot[s][mt][r]) + __float_as_int(v));
+                else tot[s][mt][r] += v;
               }
-        }
-      }
-      __syncthreads();
-    }
-    if constexpr (GM == GM_PC && !A8) {
-      if (ga.ksplit > 1) {
-        float* mine = red + size_t(wave) * (NS * MT * 4 * 64);
-        if (ks > 0) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) mine[(mt * 4 + r) * 64 + lane] = xs_tot[mt][r];
+            for (int r = 0; r < 4; ++r) xs_tot[mt][r] += other[((NS * MT + mt) * 4 + r) * 64 + lane];
         }
-        __syncthreads();
-        if (ks == 0) {
-          for (int o = 1; o < ga.ksplit; ++o) {
-            const float* other = red + size_t(wave + o) * (NS * MT * 4 * 64);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-              for (int r = 0; r < 4; ++r) xs_tot[mt][r] += other[(mt * 4 + r) * 64 + lane];
-          }
-        }
-        __syncthreads();
       }
     }
 
@@ -445,47 +490,59 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
         }
       }
     }
+    __syncthreads();                             // LDS is reused by the next pass
   }
 }
 
 template <bool GATEUP>
-__global__ __launch_bounds__(256) void k_qgemm_stream(const GemmArgs ga) {
-  __shared__ float red[4 * NS * MT * 4 * 64];
+__global__ __launch_bounds__(512) void k_qgemm_stream(const GemmArgs ga) {
+  extern __shared__ __align__(16) uint8_t lds[];
   const int wg = blockIdx.x;
-  const int eo = wg / ga.wg_per_expert;
-  const int e = ga.order[eo];
+  const int e = ga.order[wg / ga.wg_per_expert];
   const int wgi = wg % ga.wg_per_expert;
-  const int wave = threadIdx.x >> 6;
-  const int wpt = 4 / ga.ksplit;
-  const int task = wgi * wpt + wave / ga.ksplit;
-  const int ks = wave % ga.ksplit;
   const ExpertDev& ex = ga.ex[e];
-  const int NT = ga.n >> 4;
-  const int ntasks = GATEUP ? NT : (NT + 1) / 2;
-  const bool active = task < ntasks;
   switch (ex.fmt * 4 + ex.gm) {
-    case FMT_I8 * 4 + GM_PC:     stream_task<FMT_I8, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
-    case FMT_I8A8 * 4 + GM_PC:   stream_task<FMT_I8A8, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
-    case FMT_N6 * 4 + GM_PC:     stream_task<FMT_N6, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
-    case FMT_N4 * 4 + GM_PC:     stream_task<FMT_N4, GM_PC, GATEUP>(ga, ex, e, task, ks, active, red); break;
-    case FMT_N4 * 4 + GM_G128:   stream_task<FMT_N4, GM_G128, GATEUP>(ga, ex, e, task, ks, active, red); break;
-    case FMT_N4 * 4 + GM_G64:    stream_task<FMT_N4, GM_G64, GATEUP>(ga, ex, e, task, ks, active, red); break;
-    case FMT_N3 * 4 + GM_G128:   stream_task<FMT_N3, GM_G128, GATEUP>(ga, ex, e, task, ks, active, red); break;
-    case FMT_N3 * 4 + GM_G64:    stream_task<FMT_N3, GM_G64, GATEUP>(ga, ex, e, task, ks, active, red); break;
+    case FMT_I8 * 4 + GM_PC:     stream_task<FMT_I8, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_I8A8 * 4 + GM_PC:   stream_task<FMT_I8A8, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_N6 * 4 + GM_PC:     stream_task<FMT_N6, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_PC:     stream_task<FMT_N4, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_G128:   stream_task<FMT_N4, GM_G128, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_G64:    stream_task<FMT_N4, GM_G64, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_N3 * 4 + GM_G128:   stream_task<FMT_N3, GM_G128, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_N3 * 4 + GM_G64:    stream_task<FMT_N3, GM_G64, GATEUP>(ga, ex, e, wgi, lds); break;
     default: break;
   }
 }
 
 int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
-  const int NT = ga.n / 16;
+  const int NT = ga.n / 16, KT = ga.k / 128;
   const int ntasks = gateup ? NT : (NT + 1) / 2;
   GemmArgs a = ga;
-  const int wpt = 4 / a.ksplit;
-  a.wg_per_expert = (ntasks + wpt - 1) / wpt;
+  // Geometry: enough work-groups to fill 256 CUs twice over; long rows are cut into k-slices.
+  const int waves = WAVES;
+  int wk = 1;
+  auto total = [&](int k) { return long((ntasks + (waves / k) - 1) / (waves / k)) * a.n_experts; };
+  while (wk < 4 && total(wk) < 512 && KT / (2 * wk) >= 2) wk *= 2;
+  a.wk = wk;
+  a.tpc = 4 / wk;
+  a.wn = waves / wk;
+  a.wg_per_expert = (ntasks + a.wn - 1) / a.wn;
   const unsigned grid = unsigned(a.wg_per_expert) * unsigned(a.n_experts);
+  const int slot_bytes = (NS * MT + MT) * 4 * 64 * 4;
+  int lds_bytes = LDS_BYTES;
+  if (waves * slot_bytes > lds_bytes) lds_bytes = waves * slot_bytes;
+  // more than 64 KiB of dynamic LDS has to be requested once per kernel
+  static bool lds_ok[2] = {false, false};
+  if (!lds_ok[gateup ? 1 : 0]) {
+    const void* fn = gateup ? reinterpret_cast<const void*>(&k_qgemm_stream<true>)
+                            : reinterpret_cast<const void*>(&k_qgemm_stream<false>);
+    hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: cannot reserve LDS: %s", hipGetErrorString(err));
+    lds_ok[gateup ? 1 : 0] = true;
+  }
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL(k_qgemm_stream<true>, dim3(grid), dim3(256), 0, st, a);
-  else hipLaunchKernelGGL(k_qgemm_stream<false>, dim3(grid), dim3(256), 0, st, a);
+  if (gateup) hipLaunchKernelGGL(k_qgemm_stream<true>, dim3(grid), dim3(waves * 64), lds_bytes, st, a);
+  else hipLaunchKernelGGL(k_qgemm_stream<false>, dim3(grid), dim3(waves * 64), lds_bytes, st, a);
   return check_launch("grouped_qgemm");
 }
 

@@ -160,7 +160,7 @@ struct GemmArgs {
   const int32_t* a_perm;     // bucket slot -> sample for reading a; NULL: a is in bucket order
   const int32_t* y_perm;     // bucket slot -> sample for writing y; NULL: bucket order
   void*     y;               // float [M, n] (plain) or bf16 [M, n] (gate/up, bucket order)
-  int32_t   wn, wk, tpc;     // work-group geometry: tasks, k-slices, k-tiles per staged chunk (wk*tpc == 4)
+  int32_t   wn, wk;          // work-group geometry: tasks per work-group, k-slices per task
   int32_t   wg_per_expert;
 };
 

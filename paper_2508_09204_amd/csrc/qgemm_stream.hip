@@ -40,8 +40,8 @@ template <> struct CodeMap<FMT_N6>   { static constexpr float BASE = 32.f, CM = 
 template <int FMT> struct Raw;
 template <> struct Raw<FMT_I8>   { static constexpr int N = 8; static constexpr int PF = 2; };
 template <> struct Raw<FMT_I8A8> { static constexpr int N = 8; static constexpr int PF = 2; };
-template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr int PF = 4; };
-template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 4; };
+template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr int PF = 2; };
+template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 2; };
 template <> struct Raw<FMT_N6>   { static constexpr int N = 6; static constexpr int PF = 2; };
 
 template <int FMT>
@@ -123,47 +123,45 @@ static __device__ __forceinline__ float silu_mul(float g, float u) {
   return (g / (1.0f + __expf(-g))) * u;
 }
 
-// Work-group geometry (runtime, uniform): W waves = WN tasks x WK k-slices.  A task is a pair
+// Work-group geometry: 8 waves = WN (2) tasks x WK (4) k-slices.  A task is a pair
 // of weight tiles; slice ks of a task covers the k-tiles [ks*ceil(KT/WK), ...).  The activation
-// rows of the pass (at most 32) are staged in LDS once per work-group and chunk of TPC k-tiles
-// per slice, double-buffered, and shared by all waves, so activations cross the L2 once per
-// work-group instead of once per wave.
-struct Geom {
-  int wn, wk, tpc;      // tasks per work-group, k-slices, k-tiles per chunk (wk * tpc == 4)
-};
-
+// rows of the pass (at most 32) are staged in LDS one k-tile per slice at a time, double-
+// buffered, and shared by all waves, so activations cross the L2 once per work-group instead of
+// once per wave.  Inside the tile loop every global load is unconditional (addresses are
+// clamped, unused data is masked), which lets the compiler keep the whole prefetch ring in
+// flight instead of draining it at control-flow joins.
 constexpr int ROWS = 16 * MT;                 // bucket rows per pass
-constexpr int KCHUNK_TOTAL = 512;             // columns staged per chunk over all slices
 constexpr int WAVES = 8;                      // waves per work-group
-constexpr int AU_MAX = 4;                     // 16-byte units a thread stages per chunk, at most
+constexpr int WK = 4;                         // k-slices per task
+constexpr int WN = WAVES / WK;                // tasks per work-group
 
-template <bool A8> __host__ __device__ constexpr int a_row_stride(int kc) { return kc * (A8 ? 1 : 2) + 16; }
+template <bool A8> __host__ __device__ constexpr int a_row_stride() { return 128 * (A8 ? 1 : 2) + 16; }
 
 // LDS bytes: two activation buffers (bf16 worst case); the k-slice reduction reuses them.
-static constexpr int LDS_BYTES = 2 * 4 * ROWS * (128 * 2 + 16) > 2 * ROWS * (512 * 2 + 16)
-                                     ? 2 * 4 * ROWS * (128 * 2 + 16) : 2 * ROWS * (512 * 2 + 16);
+static constexpr int LDS_BYTES = 2 * WK * ROWS * a_row_stride<false>();
 
 template <int FMT, int GM, bool GATEUP>
 static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int wgi,
                                                    uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
   constexpr int PF = Raw<FMT>::PF;
-  static_assert(4 % PF == 0, "the tile loop is unrolled by four and indexes the prefetch ring statically");
+  static_assert(PF == 2, "the tile loop is unrolled by two and indexes the prefetch ring statically");
   constexpr int NR = Raw<FMT>::N;
   constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
   constexpr int EB = A8 ? 1 : 2;              // bytes per activation element
-  const int tid = threadIdx.x, nthreads = blockDim.x;
+  constexpr int nthreads = WAVES * 64;
+  const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lq = lane >> 4;
   const int KT = ga.k >> 7, NT = ga.n >> 4;
   const int T = ga.T;
-  const int wk = ga.wk, tpc = ga.tpc;
+  constexpr int wk = WK;
   const int off_e = ga.offsets[e];
   const int M_e = (ga.offsets[e + 1] - off_e) * T;
   if (M_e <= 0) return;                       // uniform over the work-group (one expert per work-group)
 
   const int ks = wave % wk;
-  const int task = wgi * ga.wn + wave / wk;
+  const int task = wgi * WN + wave / wk;
   const int ntasks = GATEUP ? NT : (NT + 1) / 2;
   const bool active_task = task < ntasks;
 
@@ -180,10 +178,13 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   }
   const int slice_tiles = (KT + wk - 1) / wk;              // k-tiles per slice (last slice may be shorter)
   const int kt0 = ks * slice_tiles, kt1 = min(KT, kt0 + slice_tiles);
-  const int n_chunks = (slice_tiles + tpc - 1) / tpc;
-  const int KC = 128 * tpc;                                // columns per slice and chunk
-  const int rstride = a_row_stride<A8>(KC);
-  const int buf_bytes = wk * ROWS * rstride;
+  constexpr int KC = 128;                                  // columns staged per slice and step
+  constexpr int rstride = a_row_stride<A8>();
+  constexpr int buf_bytes = wk * ROWS * rstride;
+  // streams without a tile of their own (odd tile count, padding tasks) and waves whose slice is
+  // empty still run the loop on clamped addresses; their results are never stored
+  const int nt_ld[NS] = {sv[0] ? nt[0] : 0, sv[1] ? nt[1] : 0};
+  const int kt_last = max(kt0, kt1 - 1) < KT ? max(kt0, kt1 - 1) : KT - 1;
 
   // sum_k x (c - z) = (1/CM) * (sum_k x (BASE + CM c) - (BASE + CM z) sum_k x)
   constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
@@ -192,8 +193,10 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
 
   // ---- staging plan: which 16-byte units of a chunk this thread copies -----------------------
-  const int upr = KC * EB / 16;                            // units per row
-  const int n_units = wk * ROWS * upr;
+  constexpr int upr = KC * EB / 16;                        // units per row
+  constexpr int n_units = wk * ROWS * upr;
+  constexpr int AU_MAX = n_units / nthreads;               // 16-byte units per thread and step
+  static_assert(n_units % nthreads == 0, "every thread stages the same number of units");
 
   for (int pass0 = 0; pass0 < M_e; pass0 += ROWS) {
     const int rows_here = min(ROWS, M_e - pass0);
@@ -206,7 +209,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
     for (int i = 0; i < AU_MAX; ++i) {
       const int u = tid + i * nthreads;
       uoff[i] = 0u; ukend[i] = 0;
-      if (u < n_units) {
+      {
         const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
         const int sk0 = sl * slice_tiles, sk1 = min(KT, sk0 + slice_tiles);
         if (row < rows_here && sk0 < sk1) {
@@ -221,23 +224,22 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
       }
     }
     u32x4 areg[AU_MAX];
-    auto a_fetch = [&](int c) {       // global -> registers, chunk c
+    auto a_fetch = [&](int c) {       // global -> registers, k-tile c of every slice
       const int koff = c * KC * EB;
 #pragma unroll
       for (int i = 0; i < AU_MAX; ++i) {
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (koff < ukend[i]) v = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + koff);
-        areg[i] = v;
+        const bool in = koff < ukend[i];
+        const u32x4 v = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + (in ? koff : 0));
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        areg[i] = in ? v : z;
       }
     };
     auto a_store = [&](int buf) {     // registers -> LDS buffer
 #pragma unroll
       for (int i = 0; i < AU_MAX; ++i) {
         const int u = tid + i * nthreads;
-        if (u < n_units) {
-          const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
-          *reinterpret_cast<u32x4*>(lds + buf * buf_bytes + (sl * ROWS + row) * rstride + cu * 16) = areg[i];
-        }
+        const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
+        *reinterpret_cast<u32x4*>(lds + buf * buf_bytes + (sl * ROWS + row) * rstride + cu * 16) = areg[i];
       }
     };
 
@@ -253,33 +255,31 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
     uint32_t raw[PF][NS][NR];
     float sc[PF][NS][GPT ? GPT : 1];
     uint32_t zp[PF][NS];
-    const bool wave_has_work = (sv[0] || sv[1]) && kt0 < kt1;
 
-    auto issue_w = [&](int p, int kt) {
+    auto issue_w = [&](int p, int kt_want) {
+      const int kt = min(kt_want, kt_last);
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        if (sv[s]) {
-          const size_t t = size_t(nt[s]) * KT + kt;
-          load_raw<FMT>(raw[p][s], blob[s] + t * ex.tile_bytes, lane);
-          if constexpr (GPT > 0) {
-            const float* sp = reinterpret_cast<const float*>(blob[s] + ex.scale_off) + (t * 16 + lr) * GPT;
-            const uint8_t* zq = blob[s] + ex.zero_off + (t * 16 + lr) * GPT;
-            if constexpr (GPT == 1) {
-              sc[p][s][0] = sp[0];
-              zp[p][s] = ex.asym ? uint32_t(zq[0]) : 0u;
-            } else {
-              float2 v = *reinterpret_cast<const float2*>(sp);
-              sc[p][s][0] = v.x; sc[p][s][1] = v.y;
-              zp[p][s] = ex.asym ? uint32_t(*reinterpret_cast<const uint16_t*>(zq)) : 0u;
-            }
+        const size_t t = size_t(nt_ld[s]) * KT + kt;
+        load_raw<FMT>(raw[p][s], blob[s] + t * ex.tile_bytes, lane);
+        if constexpr (GPT > 0) {          // group formats are asymmetric: scale and zero-point per group
+          const float* sp = reinterpret_cast<const float*>(blob[s] + ex.scale_off) + (t * 16 + lr) * GPT;
+          const uint8_t* zq = blob[s] + ex.zero_off + (t * 16 + lr) * GPT;
+          if constexpr (GPT == 1) {
+            sc[p][s][0] = sp[0];
+            zp[p][s] = uint32_t(zq[0]);
+          } else {
+            float2 v = *reinterpret_cast<const float2*>(sp);
+            sc[p][s][0] = v.x; sc[p][s][1] = v.y;
+            zp[p][s] = uint32_t(*reinterpret_cast<const uint16_t*>(zq));
           }
         }
       }
     };
 
     // One k-tile: activation operands come from LDS (tile `tl` of the current chunk buffer).
-    auto consume = [&](int p, const uint8_t* abuf, int tl) {
-      const uint8_t* arow0 = abuf + (ks * ROWS + lr) * rstride + tl * 128 * EB;
+    auto consume = [&](int p, const uint8_t* abuf) {
+      const uint8_t* arow0 = abuf + (ks * ROWS + lr) * rstride;
       if constexpr (A8) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -288,14 +288,12 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
             i32x4 a1 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * rstride + 64 + lq * 16);
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-              if (sv[s]) {
-                i32x4 acc = __builtin_bit_cast(i32x4, tot[s][mt]);
-                i32x4 b0 = {int(raw[p][s][0]), int(raw[p][s][1]), int(raw[p][s][2]), int(raw[p][s][3])};
-                i32x4 b1 = {int(raw[p][s][4]), int(raw[p][s][5]), int(raw[p][s][6]), int(raw[p][s][7])};
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, acc, 0, 0, 0);
-                tot[s][mt] = __builtin_bit_cast(f32x4, acc);
-              }
+              i32x4 acc = __builtin_bit_cast(i32x4, tot[s][mt]);
+              i32x4 b0 = {int(raw[p][s][0]), int(raw[p][s][1]), int(raw[p][s][2]), int(raw[p][s][3])};
+              i32x4 b1 = {int(raw[p][s][4]), int(raw[p][s][5]), int(raw[p][s][6]), int(raw[p][s][7])};
+              acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, acc, 0, 0, 0);
+              acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, acc, 0, 0, 0);
+              tot[s][mt] = __builtin_bit_cast(f32x4, acc);
             }
           }
         }
@@ -329,7 +327,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
         }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-          if (sv[s]) {
+          {
             const bf16x8 b0 = frag<FMT, 0>(raw[p][s]);
             const bf16x8 b1 = frag<FMT, 1>(raw[p][s]);
             const bf16x8 b2 = frag<FMT, 2>(raw[p][s]);
@@ -350,7 +348,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
                   v = mfma_bf16(af[mt][1], b1, v);
                   v = mfma_bf16(af[mt][2], b2, v);
                   v = mfma_bf16(af[mt][3], b3, v);
-                  const float o = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
+                  const float o = BASE + CM * float(zp[p][s] & 0xffu);
                   const float scv = sc[p][s][0] * INV_CM;
 #pragma unroll
                   for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
@@ -360,8 +358,8 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
                   v0 = mfma_bf16(af[mt][1], b1, v0);
                   v1 = mfma_bf16(af[mt][2], b2, v1);
                   v1 = mfma_bf16(af[mt][3], b3, v1);
-                  const float o0 = ex.asym ? BASE + CM * float(zp[p][s] & 0xffu) : off_sym;
-                  const float o1 = ex.asym ? BASE + CM * float((zp[p][s] >> 8) & 0xffu) : off_sym;
+                  const float o0 = BASE + CM * float(zp[p][s] & 0xffu);
+                  const float o1 = BASE + CM * float((zp[p][s] >> 8) & 0xffu);
                   const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
 #pragma unroll
                   for (int r = 0; r < 4; ++r) {
@@ -376,41 +374,34 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
       }
     };
 
-    // ---- prologue: first weight tiles in flight, chunk 0 of the activations into LDS --------
-    if (wave_has_work) {
+    // ---- prologue: first weight tiles in flight, k-tile 0 of the activations into LDS -------
 #pragma unroll
-      for (int p = 0; p < PF; ++p)
-        if (kt0 + p < kt1) issue_w(p, kt0 + p);
-    }
+    for (int p = 0; p < PF; ++p) issue_w(p, kt0 + p);
     a_fetch(0);
     a_store(0);
     __syncthreads();
 
-    // ---- main loop over the slice's k-tiles, four per iteration (PF divides 4) --------------
-    const int tiles_padded = n_chunks * tpc;
-    for (int tb = 0; tb < tiles_padded; tb += 4) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int ti = tb + q;                   // tile index inside the slice
-        if (ti < tiles_padded) {                 // uniform over the work-group
-          const int c = ti / tpc, tl = ti % tpc;
-          if (tl == 0 && c + 1 < n_chunks) a_fetch(c + 1);
-          const int kt = kt0 + ti;
-          if (wave_has_work && kt < kt1) {
-            consume(q % PF, lds + (c & 1) * buf_bytes, tl);
-            if (kt + PF < kt1) issue_w(q % PF, kt + PF);
-          }
-          if (tl == tpc - 1 && c + 1 < n_chunks) {
-            a_store((c + 1) & 1);
-            __syncthreads();
-          }
-        }
-      }
+    // ---- main loop over the slice's k-tiles: while tile ti is multiplied, the activations of
+    // tile ti+1 travel global -> registers -> the other LDS buffer, and weight tile ti+PF is
+    // requested.  Two tiles per iteration so that the ring index is static.
+    // Tiles past the end of a shorter slice see zero activations and contribute nothing.
+    auto step = [&](int ti, int p) {
+      a_fetch(ti + 1);
+      consume(p, lds + (ti & 1) * buf_bytes);
+      issue_w(p, kt0 + ti + PF);
+      a_store((ti + 1) & 1);
+      __syncthreads();
+    };
+    int tb = 0;
+#pragma unroll 1
+    for (; tb + 2 <= slice_tiles; tb += 2) {
+      step(tb, 0);
+      step(tb + 1, 1);
     }
+    if (tb < slice_tiles) step(tb, 0);                      // uniform over the work-group
 
     // ---- combine the k-slices of a task (fixed order), then the epilogue -------------------
     if (wk > 1) {
-      __syncthreads();                           // everyone is done with the activation buffers
       float* red = reinterpret_cast<float*>(lds);
       constexpr int SLOT = (NS * MT + MT) * 4 * 64;
       float* mine = red + size_t(wave) * SLOT;
@@ -515,18 +506,13 @@ __global__ __launch_bounds__(512) void k_qgemm_stream(const GemmArgs ga) {
 }
 
 int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
-  const int NT = ga.n / 16, KT = ga.k / 128;
+  const int NT = ga.n / 16;
   const int ntasks = gateup ? NT : (NT + 1) / 2;
   GemmArgs a = ga;
-  // Geometry: enough work-groups to fill 256 CUs twice over; long rows are cut into k-slices.
   const int waves = WAVES;
-  int wk = 1;
-  auto total = [&](int k) { return long((ntasks + (waves / k) - 1) / (waves / k)) * a.n_experts; };
-  while (wk < 4 && total(wk) < 512 && KT / (2 * wk) >= 2) wk *= 2;
-  a.wk = wk;
-  a.tpc = 4 / wk;
-  a.wn = waves / wk;
-  a.wg_per_expert = (ntasks + a.wn - 1) / a.wn;
+  a.wk = WK;
+  a.wn = WN;
+  a.wg_per_expert = (ntasks + WN - 1) / WN;
   const unsigned grid = unsigned(a.wg_per_expert) * unsigned(a.n_experts);
   const int slot_bytes = (NS * MT + MT) * 4 * 64 * 4;
   int lds_bytes = LDS_BYTES;

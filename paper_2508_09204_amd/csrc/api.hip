@@ -92,6 +92,8 @@ static int32_t check_router(const moqe_router* r, const char* who) {
   if (r->h < 0 || r->h % 4) return set_error(MOQE_E_SHAPE, "%s: router hidden dim %d must be a multiple of 4", who, r->h);
   if (!r->w2) return set_error(MOQE_E_NULL, "%s: router w2 is NULL", who);
   if (r->h > 0 && !r->w1) return set_error(MOQE_E_NULL, "%s: router w1 is NULL", who);
+  if (!aligned(r->w2, 16) || (r->w1 && !aligned(r->w1, 16)) || (r->b1 && !aligned(r->b1, 16)))
+    return set_error(MOQE_E_SHAPE, "%s: router weights must be 16-byte aligned", who);
   return MOQE_OK;
 }
 
@@ -385,9 +387,8 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
     if (aux->inv_perm) inv_perm = aux->inv_perm;
   }
 
-  rc = launch_route(x, S, T, blk->router, idx, (aux && aux->logits) ? logits : nullptr, ws + L.route, st);
-  if (rc) return rc;
-  rc = launch_bucket(idx, S, K, counts, offsets, perm, (aux && aux->inv_perm) ? inv_perm : nullptr, st);
+  rc = launch_route_bucket(x, S, T, blk->router, idx, (aux && aux->logits) ? logits : nullptr, counts, offsets, perm,
+                           (aux && aux->inv_perm) ? inv_perm : nullptr, ws + L.route, st);
   if (rc) return rc;
 
   if (blk->kind == MOQE_KIND_LINEAR) {

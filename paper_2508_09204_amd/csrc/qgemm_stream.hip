@@ -123,7 +123,7 @@ static __device__ __forceinline__ float silu_mul(float g, float u) {
   return (g / (1.0f + __expf(-g))) * u;
 }
 
-// Work-group geometry: 8 waves = WN (2) tasks x WK (4) k-slices.  A task is a pair
+// Work-group geometry: 8 waves = WN tasks x WK k-slices (WK = 2 or 4, chosen per launch).  A task is a pair
 // of weight tiles; slice ks of a task covers the k-tiles [ks*ceil(KT/WK), ...).  The activation
 // rows of the pass (at most 32) are staged in LDS one k-tile per slice at a time, double-
 // buffered, and shared by all waves, so activations cross the L2 once per work-group instead of
@@ -132,15 +132,14 @@ static __device__ __forceinline__ float silu_mul(float g, float u) {
 // flight instead of draining it at control-flow joins.
 constexpr int ROWS = 16 * MT;                 // bucket rows per pass
 constexpr int WAVES = 8;                      // waves per work-group
-constexpr int WK = 4;                         // k-slices per task
-constexpr int WN = WAVES / WK;                // tasks per work-group
+constexpr int WK_MAX = 4;                     // k-slices per task, at most
 
 template <bool A8> __host__ __device__ constexpr int a_row_stride() { return 128 * (A8 ? 1 : 2) + 16; }
 
 // LDS bytes: two activation buffers (bf16 worst case); the k-slice reduction reuses them.
-static constexpr int LDS_BYTES = 2 * WK * ROWS * a_row_stride<false>();
+static constexpr int LDS_BYTES = 2 * WK_MAX * ROWS * a_row_stride<false>();
 
-template <int FMT, int GM, bool GATEUP>
+template <int FMT, int GM, bool GATEUP, int WK>
 static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int wgi,
                                                    uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
@@ -156,6 +155,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   const int KT = ga.k >> 7, NT = ga.n >> 4;
   const int T = ga.T;
   constexpr int wk = WK;
+  constexpr int WN = WAVES / WK;                // tasks per work-group
   const int off_e = ga.offsets[e];
   const int M_e = (ga.offsets[e + 1] - off_e) * T;
   if (M_e <= 0) return;                       // uniform over the work-group (one expert per work-group)
@@ -195,8 +195,9 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   // ---- staging plan: which 16-byte units of a chunk this thread copies -----------------------
   constexpr int upr = KC * EB / 16;                        // units per row
   constexpr int n_units = wk * ROWS * upr;
-  constexpr int AU_MAX = n_units / nthreads;               // 16-byte units per thread and step
-  static_assert(n_units % nthreads == 0, "every thread stages the same number of units");
+  constexpr int AU_MAX = n_units >= nthreads ? n_units / nthreads : 1;   // 16-byte units per thread and step
+  static_assert(n_units % nthreads == 0 || n_units * 2 == nthreads, "whole units per thread, or half the threads idle");
+  constexpr bool ALL_STAGE = n_units >= nthreads;          // false: only the lower half of the threads stages
 
   for (int pass0 = 0; pass0 < M_e; pass0 += ROWS) {
     const int rows_here = min(ROWS, M_e - pass0);
@@ -209,7 +210,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
     for (int i = 0; i < AU_MAX; ++i) {
       const int u = tid + i * nthreads;
       uoff[i] = 0u; ukend[i] = 0;
-      {
+      if (ALL_STAGE || u < n_units) {
         const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
         const int sk0 = sl * slice_tiles, sk1 = min(KT, sk0 + slice_tiles);
         if (row < rows_here && sk0 < sk1) {
@@ -239,7 +240,8 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
       for (int i = 0; i < AU_MAX; ++i) {
         const int u = tid + i * nthreads;
         const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
-        *reinterpret_cast<u32x4*>(lds + buf * buf_bytes + (sl * ROWS + row) * rstride + cu * 16) = areg[i];
+        if (ALL_STAGE || u < n_units)
+          *reinterpret_cast<u32x4*>(lds + buf * buf_bytes + (sl * ROWS + row) * rstride + cu * 16) = areg[i];
       }
     };
 
@@ -485,50 +487,56 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   }
 }
 
-template <bool GATEUP>
-__global__ __launch_bounds__(512) void k_qgemm_stream(const GemmArgs ga) {
+template <bool GATEUP, int WK>
+__global__ __launch_bounds__(512, 2) void k_qgemm_stream(const GemmArgs ga) {
   extern __shared__ __align__(16) uint8_t lds[];
   const int wg = blockIdx.x;
   const int e = ga.order[wg / ga.wg_per_expert];
   const int wgi = wg % ga.wg_per_expert;
   const ExpertDev& ex = ga.ex[e];
   switch (ex.fmt * 4 + ex.gm) {
-    case FMT_I8 * 4 + GM_PC:     stream_task<FMT_I8, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
-    case FMT_I8A8 * 4 + GM_PC:   stream_task<FMT_I8A8, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
-    case FMT_N6 * 4 + GM_PC:     stream_task<FMT_N6, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_PC:     stream_task<FMT_N4, GM_PC, GATEUP>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_G128:   stream_task<FMT_N4, GM_G128, GATEUP>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_G64:    stream_task<FMT_N4, GM_G64, GATEUP>(ga, ex, e, wgi, lds); break;
-    case FMT_N3 * 4 + GM_G128:   stream_task<FMT_N3, GM_G128, GATEUP>(ga, ex, e, wgi, lds); break;
-    case FMT_N3 * 4 + GM_G64:    stream_task<FMT_N3, GM_G64, GATEUP>(ga, ex, e, wgi, lds); break;
+    case FMT_I8 * 4 + GM_PC:     stream_task<FMT_I8, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_I8A8 * 4 + GM_PC:   stream_task<FMT_I8A8, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_N6 * 4 + GM_PC:     stream_task<FMT_N6, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_PC:     stream_task<FMT_N4, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_G128:   stream_task<FMT_N4, GM_G128, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_G64:    stream_task<FMT_N4, GM_G64, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_N3 * 4 + GM_G128:   stream_task<FMT_N3, GM_G128, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_N3 * 4 + GM_G64:    stream_task<FMT_N3, GM_G64, GATEUP, WK>(ga, ex, e, wgi, lds); break;
     default: break;
   }
 }
 
+typedef void (*StreamKernel)(const GemmArgs);
+
 int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
-  const int NT = ga.n / 16;
+  const int NT = ga.n / 16, KT = ga.k / 128;
   const int ntasks = gateup ? NT : (NT + 1) / 2;
   GemmArgs a = ga;
-  const int waves = WAVES;
-  a.wk = WK;
-  a.wn = WN;
-  a.wg_per_expert = (ntasks + WN - 1) / WN;
+  // Long rows are cut into four k-slices per task, short ones into two: a wave should keep a
+  // dozen or more tiles to amortise its set-up, and there should be a few work-groups per CU.
+  const int wk = KT >= 64 ? 4 : 2;
+  const int wn = WAVES / wk;
+  a.wk = wk;
+  a.wn = wn;
+  a.wg_per_expert = (ntasks + wn - 1) / wn;
   const unsigned grid = unsigned(a.wg_per_expert) * unsigned(a.n_experts);
   const int slot_bytes = (NS * MT + MT) * 4 * 64 * 4;
   int lds_bytes = LDS_BYTES;
-  if (waves * slot_bytes > lds_bytes) lds_bytes = waves * slot_bytes;
+  if (WAVES * slot_bytes > lds_bytes) lds_bytes = WAVES * slot_bytes;
+  const int ki = (gateup ? 2 : 0) + (wk == 4 ? 1 : 0);
+  static const StreamKernel kernels[4] = {k_qgemm_stream<false, 2>, k_qgemm_stream<false, 4>, k_qgemm_stream<true, 2>,
+                                          k_qgemm_stream<true, 4>};
   // more than 64 KiB of dynamic LDS has to be requested once per kernel
-  static bool lds_ok[2] = {false, false};
-  if (!lds_ok[gateup ? 1 : 0]) {
-    const void* fn = gateup ? reinterpret_cast<const void*>(&k_qgemm_stream<true>)
-                            : reinterpret_cast<const void*>(&k_qgemm_stream<false>);
-    hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+  static bool lds_ok[4] = {false, false, false, false};
+  if (!lds_ok[ki]) {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[ki]),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
     if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: cannot reserve LDS: %s", hipGetErrorString(err));
-    lds_ok[gateup ? 1 : 0] = true;
+    lds_ok[ki] = true;
   }
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL(k_qgemm_stream<true>, dim3(grid), dim3(waves * 64), lds_bytes, st, a);
-  else hipLaunchKernelGGL(k_qgemm_stream<false>, dim3(grid), dim3(waves * 64), lds_bytes, st, a);
+  hipLaunchKernelGGL(kernels[ki], dim3(grid), dim3(WAVES * 64), lds_bytes, st, a);
   return check_launch("grouped_qgemm");
 }
 

@@ -64,6 +64,14 @@ static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], cons
   }
 }
 
+// (x & mask) | orv in one VALU operation (the mask travels in a scalar register, which the
+// three-operand encoding allows once per instruction).
+static __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t orv) {
+  uint32_t d;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(orv));
+  return d;
+}
+
 template <int SH> static __device__ __forceinline__ uint32_t shift_by(uint32_t v) {
   if constexpr (SH >= 0) return v >> SH; else return v << (-SH);
 }
@@ -86,25 +94,25 @@ static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N]) 
     d.w = __builtin_amdgcn_perm(f7, f6, 0x07060302u);
   } else if constexpr (FMT == FMT_N4) {
     const uint32_t w = r[J];
-    d.x = (shift_by<-3>(w) & 0x00780078u) | 0x41004100u;
-    d.y = (shift_by<1>(w) & 0x00780078u) | 0x41004100u;
-    d.z = (shift_by<5>(w) & 0x00780078u) | 0x41004100u;
-    d.w = (shift_by<9>(w) & 0x00780078u) | 0x41004100u;
+    d.x = and_or(shift_by<-3>(w), 0x00780078u, 0x41004100u);
+    d.y = and_or(shift_by<1>(w), 0x00780078u, 0x41004100u);
+    d.z = and_or(shift_by<5>(w), 0x00780078u, 0x41004100u);
+    d.w = and_or(shift_by<9>(w), 0x00780078u, 0x41004100u);
   } else if constexpr (FMT == FMT_N3) {
     const uint32_t lo = r[J / 2], hi = r[2];
     constexpr int P0 = 4 * (J % 2);       // first 2-bit field of this step inside `lo`
     constexpr int Q0 = 4 * J;             // first 1-bit field of this step inside `hi`
-    d.x = (shift_by<2 * (P0 + 0) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 0 - 6>(hi) & 0x00400040u) | 0x40804080u;
-    d.y = (shift_by<2 * (P0 + 1) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 1 - 6>(hi) & 0x00400040u) | 0x40804080u;
-    d.z = (shift_by<2 * (P0 + 2) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 2 - 6>(hi) & 0x00400040u) | 0x40804080u;
-    d.w = (shift_by<2 * (P0 + 3) - 4>(lo) & 0x00300030u) | (shift_by<Q0 + 3 - 6>(hi) & 0x00400040u) | 0x40804080u;
+    d.x = and_or(shift_by<2 * (P0 + 0) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 0 - 6>(hi), 0x00400040u, 0x40804080u));
+    d.y = and_or(shift_by<2 * (P0 + 1) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 1 - 6>(hi), 0x00400040u, 0x40804080u));
+    d.z = and_or(shift_by<2 * (P0 + 2) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 2 - 6>(hi), 0x00400040u, 0x40804080u));
+    d.w = and_or(shift_by<2 * (P0 + 3) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 3 - 6>(hi), 0x00400040u, 0x40804080u));
   } else {  // FMT_N6
     const uint32_t w = r[J], hi = r[4 + J / 2];
     constexpr int P0 = 4 * (J % 2);
-    d.x = (shift_by<-1>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 0) - 5>(hi) & 0x00600060u) | 0x42004200u;
-    d.y = (shift_by<3>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 1) - 5>(hi) & 0x00600060u) | 0x42004200u;
-    d.z = (shift_by<7>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 2) - 5>(hi) & 0x00600060u) | 0x42004200u;
-    d.w = (shift_by<11>(w) & 0x001E001Eu) | (shift_by<2 * (P0 + 3) - 5>(hi) & 0x00600060u) | 0x42004200u;
+    d.x = and_or(shift_by<-1>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 0) - 5>(hi), 0x00600060u, 0x42004200u));
+    d.y = and_or(shift_by<3>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 1) - 5>(hi), 0x00600060u, 0x42004200u));
+    d.z = and_or(shift_by<7>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 2) - 5>(hi), 0x00600060u, 0x42004200u));
+    d.w = and_or(shift_by<11>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 3) - 5>(hi), 0x00600060u, 0x42004200u));
   }
   return __builtin_bit_cast(bf16x8, d);
 }
@@ -201,8 +209,10 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
 
   for (int pass0 = 0; pass0 < M_e; pass0 += ROWS) {
     const int rows_here = min(ROWS, M_e - pass0);
-    // Per staged unit: byte offset of its chunk-0 source from the activation base, and how many
-    // bytes of the row remain inside the slice from there (0: the unit is zero-filled).
+    // Per staged unit: byte offset of its step-0 source from the activation base, and the largest
+    // step offset that stays inside the unit's slice.  Nothing is zero-filled: rows past the end of
+    // the bucket repeat its last row (their products land in result rows that are never stored), and
+    // steps past the end of a slice re-read its last tile and are not multiplied.
     const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
     uint32_t uoff[AU_MAX];
     int ukend[AU_MAX];
@@ -212,28 +222,22 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
       uoff[i] = 0u; ukend[i] = 0;
       if (ALL_STAGE || u < n_units) {
         const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
-        const int sk0 = sl * slice_tiles, sk1 = min(KT, sk0 + slice_tiles);
-        if (row < rows_here && sk0 < sk1) {
-          const int m = pass0 + row;
-          size_t src;
-          if constexpr (A8) src = size_t(off_e) * T + m;
-          else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
-          else src = size_t(off_e) * T + m;
-          uoff[i] = uint32_t((src * size_t(ga.k) + size_t(sk0) * 128) * EB + cu * 16);
-          ukend[i] = (sk1 - sk0) * 128 * EB - cu * 16;
-        }
+        const int sk0 = min(sl * slice_tiles, KT - 1), sk1 = min(KT, sl * slice_tiles + slice_tiles);
+        const int m = pass0 + min(row, rows_here - 1);
+        size_t src;
+        if constexpr (A8) src = size_t(off_e) * T + m;
+        else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
+        else src = size_t(off_e) * T + m;
+        uoff[i] = uint32_t((src * size_t(ga.k) + size_t(sk0) * 128) * EB + cu * 16);
+        ukend[i] = max(sk1 - sk0 - 1, 0) * 128 * EB;      // offset of the slice's last tile
       }
     }
     u32x4 areg[AU_MAX];
     auto a_fetch = [&](int c) {       // global -> registers, k-tile c of every slice
       const int koff = c * KC * EB;
 #pragma unroll
-      for (int i = 0; i < AU_MAX; ++i) {
-        const bool in = koff < ukend[i];
-        const u32x4 v = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + (in ? koff : 0));
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        areg[i] = in ? v : z;
-      }
+      for (int i = 0; i < AU_MAX; ++i)
+        areg[i] = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + min(koff, ukend[i]));
     };
     auto a_store = [&](int buf) {     // registers -> LDS buffer
 #pragma unroll
@@ -386,10 +390,10 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
     // ---- main loop over the slice's k-tiles: while tile ti is multiplied, the activations of
     // tile ti+1 travel global -> registers -> the other LDS buffer, and weight tile ti+PF is
     // requested.  Two tiles per iteration so that the ring index is static.
-    // Tiles past the end of a shorter slice see zero activations and contribute nothing.
+    // Tiles past the end of a shorter slice are skipped (uniform over the wave).
     auto step = [&](int ti, int p) {
       a_fetch(ti + 1);
-      consume(p, lds + (ti & 1) * buf_bytes);
+      if (kt0 + ti < kt1) consume(p, lds + (ti & 1) * buf_bytes);
       issue_w(p, kt0 + ti + PF);
       a_store((ti + 1) & 1);
       __syncthreads();

@@ -146,6 +146,8 @@ static int32_t plan_experts(const moqe_qmat* experts, int K, const moqe_qmat* se
   return MOQE_OK;
 }
 
+constexpr int TILE_MIN_ROWS_PER_EXPERT = 64;
+
 // Enqueues one grouped GEMM (plus the int8 row quantization its act_mode-1 experts need).
 static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t* a_perm, const int32_t* y_perm, int S, int T,
                            const moqe_qmat* experts, const moqe_qmat* second, int K, const GroupedPlan& gp, void* y,
@@ -171,6 +173,9 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
       if (rc) return rc;
     }
   }
+  // Buckets of a few rows stream the weights once per launch; buckets of many rows are a dense
+  // contraction and take the LDS-tiled kernel.
+  if (M > TILE_MIN_ROWS_PER_EXPERT * K) return launch_qgemm_tile(ga, second != nullptr, st);
   return launch_qgemm_stream(ga, second != nullptr, st);
 }
 

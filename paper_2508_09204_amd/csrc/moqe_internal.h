@@ -190,6 +190,7 @@ int32_t launch_quantize(const float* w, float clip, const moqe_qmat& out, hipStr
 int32_t launch_pack(const moqe_qmat& c, const PackedInfo& pi, uint8_t* out, hipStream_t st);
 int32_t launch_unpack(const moqe_qmat& p, const PackedInfo& pi, int16_t* out, float* scale_out, hipStream_t st);
 int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st);
+int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st);
 int32_t launch_act_quant(const void* x_bf16, int kdim, int T, const int32_t* offsets, const int32_t* perm,
                          int expert, int max_rows, int8_t* out, float* scales, hipStream_t st);
 int32_t launch_im2col(const void* x, int S, int H, int W, int C, void* out, hipStream_t st);

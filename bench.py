@@ -163,7 +163,10 @@ def main():
     dom_bytes = sum(sum(algorithmic_weight_bytes(n, k, e) for (n, k) in dom_mats)
                     for e, c in zip(cfg.experts, hist) if c > 0)
     dom_flops = sum(2.0 * c * cfg.T * sum(n * k for (n, k) in dom_mats) for c in hist)
-    hbm_bound = cfg.M <= 1024
+    # the library streams the weights for buckets of a few rows and tiles the contraction for larger
+    # ones (more than 64 rows per expert on average): the first is bound by HBM, the second by MFMA
+    tiled = cfg.M > 64 * cfg.K
+    hbm_bound = not tiled
     if hbm_bound:
         achieved = dom_bytes / (kern_us * 1e-6) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -172,7 +175,7 @@ def main():
         achieved = dom_flops / (kern_us * 1e-6) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
-    roof["kernel"] = "k_qgemm_stream<gate/up + SiLU>" if is_mlp else "k_qgemm_stream<plain>"
+    roof["kernel"] = ("k_qgemm_tile" if tiled else "k_qgemm_stream") + ("<gate/up + SiLU>" if is_mlp else "<plain>")
     roof["kernel_us"] = kern_us
     roof["launches_timed"] = launches
     roof["algorithmic_bytes_per_launch"] = dom_bytes

@@ -205,7 +205,7 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
  * kernel kind k has bit (1 << k) set in mask (MOQE_PK_*; at most MOQE_PROFILE_MAX_LAUNCHES
  * launches are kept; mask 0 stops).  moqe_profile_read synchronises the recorded events of one
  * kind and returns the number of launches seen and their summed duration in milliseconds.
- * Not thread-safe against concurrent forward calls on other streams' events being reused. */
+ * The record list is process-wide and unlocked: enable, run and read from one thread at a time. */
 #define MOQE_PK_ROUTE      0
 #define MOQE_PK_BUCKET     1
 #define MOQE_PK_GEMM_GATEUP 2

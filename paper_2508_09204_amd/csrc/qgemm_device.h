@@ -30,8 +30,8 @@ template <> struct CodeMap<FMT_N6>   { static constexpr float BASE = 32.f, CM = 
 template <int FMT> struct Raw;
 template <> struct Raw<FMT_I8>   { static constexpr int N = 8; static constexpr int PF = 2; };
 template <> struct Raw<FMT_I8A8> { static constexpr int N = 8; static constexpr int PF = 2; };
-template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr int PF = 2; };
-template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 2; };
+template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr int PF = 4; };
+template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 4; };
 template <> struct Raw<FMT_N6>   { static constexpr int N = 6; static constexpr int PF = 2; };
 
 template <int FMT>

@@ -21,32 +21,41 @@ constexpr int MT = 2;        // 16-row activation tiles per pass (32 bucket rows
 
 // Work-group geometry: 8 waves = WN tasks x WK k-slices (WK = 2 or 4, chosen per launch).  A task is a pair
 // of weight tiles; slice ks of a task covers the k-tiles [ks*ceil(KT/WK), ...).  The activation
-// rows of the pass (at most 32) are staged in LDS one k-tile per slice at a time, double-
-// buffered, and shared by all waves, so activations cross the L2 once per work-group instead of
-// once per wave.  Inside the tile loop every global load is unconditional (addresses are
-// clamped, unused data is masked), which lets the compiler keep the whole prefetch ring in
-// flight instead of draining it at control-flow joins.
+// rows of the pass (at most 32) are staged in LDS in chunks of CH = 8/WK k-tiles per slice,
+// double-buffered, and shared by all waves, so activations cross the L2 once per work-group
+// instead of once per wave and the work-group meets at a barrier once per chunk only: while a
+// chunk is multiplied, each step copies one k-tile of the next chunk into the other buffer.
+// Inside the tile loop every global load is unconditional (addresses are clamped, unused data is
+// masked), which lets the compiler keep the whole prefetch ring in flight instead of draining
+// it at control-flow joins.
 constexpr int ROWS = 16 * MT;                 // bucket rows per pass
 constexpr int WAVES = 8;                      // waves per work-group
-constexpr int WK_MAX = 4;                     // k-slices per task, at most
+constexpr int A_SLOT = 256;                   // LDS bytes per staged row and k-tile (int8 rows use half)
 
-template <bool A8> __host__ __device__ constexpr int a_row_stride() { return 128 * (A8 ? 1 : 2) + 16; }
+// A staged row is 16 units of 16 bytes; unit u of row r is stored at position u ^ (r & 15), which
+// keeps the 16-byte-per-lane operand reads (16 rows x 4 units per instruction) free of bank conflicts.
+static __device__ __forceinline__ int a_unit_pos(int row, int unit) { return (unit ^ (row & 15)) * 16; }
 
-// LDS bytes: two activation buffers (bf16 worst case); the k-slice reduction reuses them.
-static constexpr int LDS_BYTES = 2 * WK_MAX * ROWS * a_row_stride<false>();
+// LDS bytes: two buffers of (WK slices x CH k-tiles = 8) x ROWS rows; the k-slice reduction reuses them.
+static constexpr int LDS_BYTES = 2 * 8 * ROWS * A_SLOT;
 
 template <int FMT, int GM, bool GATEUP, int WK>
 static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int wgi,
                                                    uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
-  constexpr int PF = Raw<FMT>::PF;
-  static_assert(PF == 2, "the tile loop is unrolled by two and indexes the prefetch ring statically");
+  // tiles in flight per stream (a deeper ring was measured and bought nothing)
+  constexpr int PF = 2;
+  constexpr int CH = 8 / WK;                  // k-tiles per staged chunk and slice
+  constexpr int U = PF > CH ? PF : CH;        // steps per loop iteration: ring slot and chunk position are static
+  static_assert(U % PF == 0 && U % CH == 0, "the unrolled loop indexes the prefetch ring and the chunk statically");
   constexpr int NR = Raw<FMT>::N;
   constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
   constexpr int EB = A8 ? 1 : 2;              // bytes per activation element
   constexpr int nthreads = WAVES * 64;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  // the wave index is uniform over the wave: telling the compiler so keeps everything derived
+  // from it (task, k-slice, tile addresses) in scalar registers
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lq = lane >> 4;
   const int KT = ga.k >> 7, NT = ga.n >> 4;
   const int T = ga.T;
@@ -75,8 +84,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   const int slice_tiles = (KT + wk - 1) / wk;              // k-tiles per slice (last slice may be shorter)
   const int kt0 = ks * slice_tiles, kt1 = min(KT, kt0 + slice_tiles);
   constexpr int KC = 128;                                  // columns staged per slice and step
-  constexpr int rstride = a_row_stride<A8>();
-  constexpr int buf_bytes = wk * ROWS * rstride;
+  constexpr int buf_bytes = wk * CH * ROWS * A_SLOT;
   // streams without a tile of their own (odd tile count, padding tasks) and waves whose slice is
   // empty still run the loop on clamped addresses; their results are never stored
   const int nt_ld[NS] = {sv[0] ? nt[0] : 0, sv[1] ? nt[1] : 0};
@@ -127,13 +135,13 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
       for (int i = 0; i < AU_MAX; ++i)
         areg[i] = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + min(koff, ukend[i]));
     };
-    auto a_store = [&](int buf) {     // registers -> LDS buffer
+    auto a_store = [&](uint8_t* dst) {     // registers -> LDS; dst = buffer + k-tile position inside the chunk
 #pragma unroll
       for (int i = 0; i < AU_MAX; ++i) {
         const int u = tid + i * nthreads;
         const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
         if (ALL_STAGE || u < n_units)
-          *reinterpret_cast<u32x4*>(lds + buf * buf_bytes + (sl * ROWS + row) * rstride + cu * 16) = areg[i];
+          *reinterpret_cast<u32x4*>(dst + (sl * CH * ROWS + row) * A_SLOT + a_unit_pos(row, cu)) = areg[i];
       }
     };
 
@@ -173,13 +181,13 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
 
     // One k-tile: activation operands come from LDS (tile `tl` of the current chunk buffer).
     auto consume = [&](int p, const uint8_t* abuf) {
-      const uint8_t* arow0 = abuf + (ks * ROWS + lr) * rstride;
+      const uint8_t* arow0 = abuf + (ks * CH * ROWS + lr) * A_SLOT;      // row lr: unit u sits at (u ^ lr) * 16
       if constexpr (A8) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           if (mt * 16 < rows_here) {
-            i32x4 a0 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * rstride + lq * 16);
-            i32x4 a1 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * rstride + 64 + lq * 16);
+            i32x4 a0 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * A_SLOT + ((lq ^ lr) * 16));
+            i32x4 a1 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * A_SLOT + (((4 + lq) ^ lr) * 16));
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
               i32x4 acc = __builtin_bit_cast(i32x4, tot[s][mt]);
@@ -192,74 +200,66 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
           }
         }
       } else {
-        u32x4 af[MT][4];
+        // Operands of the activations are read from LDS where they are used (once per weight
+        // stream) instead of being held for the whole tile: LDS has bandwidth to spare, registers
+        // are what limits the depth of the weight prefetch.
+        auto a_op = [&](int mt, int j) {
+          return *reinterpret_cast<const u32x4*>(arow0 + mt * 16 * A_SLOT + (((j * 4 + lq) ^ lr) * 16));
+        };
         f32x4 xs[MT][GPT ? GPT : 1];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          if (mt * 16 < rows_here) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              af[mt][j] = *reinterpret_cast<const u32x4*>(arow0 + mt * 16 * rstride + (j * 32 + lq * 8) * 2);
-            if constexpr (GM == GM_PC) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) xs_tot[mt] = mfma_bf16(af[mt][j], ones_b, xs_tot[mt]);
-            } else if constexpr (GM == GM_G128) {
-              f32x4 v = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-              for (int j = 0; j < 4; ++j) v = mfma_bf16(af[mt][j], ones_b, v);
-              xs[mt][0] = v;
-            } else {
-#pragma unroll
-              for (int h = 0; h < 2; ++h) {
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                v = mfma_bf16(af[mt][2 * h], ones_b, v);
-                v = mfma_bf16(af[mt][2 * h + 1], ones_b, v);
-                xs[mt][h] = v;
-              }
-            }
-          }
-        }
-#pragma unroll
         for (int s = 0; s < NS; ++s) {
-          {
-            const bf16x8 b0 = frag<FMT, 0>(raw[p][s]);
-            const bf16x8 b1 = frag<FMT, 1>(raw[p][s]);
-            const bf16x8 b2 = frag<FMT, 2>(raw[p][s]);
-            const bf16x8 b3 = frag<FMT, 3>(raw[p][s]);
+          const bf16x8 b0 = frag<FMT, 0>(raw[p][s]);
+          const bf16x8 b1 = frag<FMT, 1>(raw[p][s]);
+          const bf16x8 b2 = frag<FMT, 2>(raw[p][s]);
+          const bf16x8 b3 = frag<FMT, 3>(raw[p][s]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              if (mt * 16 < rows_here) {
+          for (int mt = 0; mt < MT; ++mt) {
+            if (mt * 16 < rows_here) {
+              const u32x4 a0 = a_op(mt, 0), a1 = a_op(mt, 1), a2 = a_op(mt, 2), a3 = a_op(mt, 3);
+              const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+              if (s == 0) {                 // row sums of the activations over the tile's groups, once per tile
                 if constexpr (GM == GM_PC) {
-                  f32x4 v = tot[s][mt];
-                  v = mfma_bf16(af[mt][0], b0, v);
-                  v = mfma_bf16(af[mt][1], b1, v);
-                  v = mfma_bf16(af[mt][2], b2, v);
-                  v = mfma_bf16(af[mt][3], b3, v);
-                  tot[s][mt] = v;
+                  xs_tot[mt] = mfma_bf16(a0, ones_b, xs_tot[mt]);
+                  xs_tot[mt] = mfma_bf16(a1, ones_b, xs_tot[mt]);
+                  xs_tot[mt] = mfma_bf16(a2, ones_b, xs_tot[mt]);
+                  xs_tot[mt] = mfma_bf16(a3, ones_b, xs_tot[mt]);
                 } else if constexpr (GM == GM_G128) {
-                  f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                  v = mfma_bf16(af[mt][0], b0, v);
-                  v = mfma_bf16(af[mt][1], b1, v);
-                  v = mfma_bf16(af[mt][2], b2, v);
-                  v = mfma_bf16(af[mt][3], b3, v);
-                  const float o = BASE + CM * float(zp[p][s] & 0xffu);
-                  const float scv = sc[p][s][0] * INV_CM;
-#pragma unroll
-                  for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
+                  f32x4 v = mfma_bf16(a0, ones_b, zero);
+                  v = mfma_bf16(a1, ones_b, v);
+                  v = mfma_bf16(a2, ones_b, v);
+                  xs[mt][0] = mfma_bf16(a3, ones_b, v);
                 } else {
-                  f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
-                  v0 = mfma_bf16(af[mt][0], b0, v0);
-                  v0 = mfma_bf16(af[mt][1], b1, v0);
-                  v1 = mfma_bf16(af[mt][2], b2, v1);
-                  v1 = mfma_bf16(af[mt][3], b3, v1);
-                  const float o0 = BASE + CM * float(zp[p][s] & 0xffu);
-                  const float o1 = BASE + CM * float((zp[p][s] >> 8) & 0xffu);
-                  const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
+                  xs[mt][0] = mfma_bf16(a1, ones_b, mfma_bf16(a0, ones_b, zero));
+                  xs[mt][GPT == 2 ? 1 : 0] = mfma_bf16(a3, ones_b, mfma_bf16(a2, ones_b, zero));
+                }
+              }
+              if constexpr (GM == GM_PC) {
+                f32x4 v = tot[s][mt];
+                v = mfma_bf16(a0, b0, v);
+                v = mfma_bf16(a1, b1, v);
+                v = mfma_bf16(a2, b2, v);
+                v = mfma_bf16(a3, b3, v);
+                tot[s][mt] = v;
+              } else if constexpr (GM == GM_G128) {
+                f32x4 v = mfma_bf16(a0, b0, zero);
+                v = mfma_bf16(a1, b1, v);
+                v = mfma_bf16(a2, b2, v);
+                v = mfma_bf16(a3, b3, v);
+                const float o = BASE + CM * float(zp[p][s] & 0xffu);
+                const float scv = sc[p][s][0] * INV_CM;
 #pragma unroll
-                  for (int r = 0; r < 4; ++r) {
-                    tot[s][mt][r] += s0 * (v0[r] - o0 * xs[mt][0][r]);
-                    tot[s][mt][r] += s1 * (v1[r] - o1 * xs[mt][GPT == 2 ? 1 : 0][r]);
-                  }
+                for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
+              } else {
+                f32x4 v0 = mfma_bf16(a1, b1, mfma_bf16(a0, b0, zero));
+                f32x4 v1 = mfma_bf16(a3, b3, mfma_bf16(a2, b2, zero));
+                const float o0 = BASE + CM * float(zp[p][s] & 0xffu);
+                const float o1 = BASE + CM * float((zp[p][s] >> 8) & 0xffu);
+                const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                  tot[s][mt][r] += s0 * (v0[r] - o0 * xs[mt][0][r]);
+                  tot[s][mt][r] += s1 * (v1[r] - o1 * xs[mt][GPT == 2 ? 1 : 0][r]);
                 }
               }
             }
@@ -268,31 +268,42 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
       }
     };
 
-    // ---- prologue: first weight tiles in flight, k-tile 0 of the activations into LDS -------
+    // ---- prologue: first weight tiles in flight, the first chunk of the activations into LDS ----
 #pragma unroll
     for (int p = 0; p < PF; ++p) issue_w(p, kt0 + p);
-    a_fetch(0);
-    a_store(0);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      a_fetch(c);
+      a_store(lds + c * ROWS * A_SLOT);
+    }
     __syncthreads();
 
     // ---- main loop over the slice's k-tiles: while tile ti is multiplied, the activations of
-    // tile ti+1 travel global -> registers -> the other LDS buffer, and weight tile ti+PF is
-    // requested.  Two tiles per iteration so that the ring index is static.
+    // tile ti+CH (the same position in the next chunk) travel global -> registers -> the other
+    // LDS buffer, and weight tile ti+PF is requested.  U tiles per iteration so that the ring slot
+    // and the position inside the chunk are static; the work-group meets once per chunk.
     // Tiles past the end of a shorter slice are skipped (uniform over the wave).
-    auto step = [&](int ti, int p) {
-      a_fetch(ti + 1);
-      if (kt0 + ti < kt1) consume(p, lds + (ti & 1) * buf_bytes);
-      issue_w(p, kt0 + ti + PF);
-      a_store((ti + 1) & 1);
-      __syncthreads();
+    auto step = [&](int ti, int i) {                        // i = ti % U, known at compile time where it matters
+      const int cur = (ti / CH) & 1;
+      uint8_t* const rd = lds + cur * buf_bytes + (i % CH) * ROWS * A_SLOT;
+      uint8_t* const wr = lds + (cur ^ 1) * buf_bytes + (i % CH) * ROWS * A_SLOT;
+      a_fetch(ti + CH);
+      if (kt0 + ti < kt1) consume(i % PF, rd);
+      issue_w(i % PF, kt0 + ti + PF);
+      a_store(wr);
+      if ((i + 1) % CH == 0) __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);                    // keep the steps apart: their temporaries must not pile up
     };
     int tb = 0;
 #pragma unroll 1
-    for (; tb + 2 <= slice_tiles; tb += 2) {
-      step(tb, 0);
-      step(tb + 1, 1);
+    for (; tb + U <= slice_tiles; tb += U) {
+#pragma unroll
+      for (int i = 0; i < U; ++i) step(tb + i, i);
     }
-    if (tb < slice_tiles) step(tb, 0);                      // uniform over the work-group
+#pragma unroll
+    for (int i = 0; i < U - 1; ++i)
+      if (tb + i < slice_tiles) step(tb + i, i);            // uniform over the work-group
+    __syncthreads();                                        // all reads of the staged rows are done
 
     // ---- combine the k-slices of a task (fixed order), then the epilogue -------------------
     if (wk > 1) {
@@ -380,7 +391,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
 }
 
 template <bool GATEUP, int WK>
-__global__ __launch_bounds__(512, 2) void k_qgemm_stream(const GemmArgs ga) {
+__global__ __launch_bounds__(WAVES * 64, 2) void k_qgemm_stream(const GemmArgs ga) {
   extern __shared__ __align__(16) uint8_t lds[];
   const int wg = blockIdx.x;
   const int e = ga.order[wg / ga.wg_per_expert];
@@ -423,7 +434,7 @@ int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
   static bool lds_ok[4] = {false, false, false, false};
   if (!lds_ok[ki]) {
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[ki]),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: cannot reserve LDS: %s", hipGetErrorString(err));
     lds_ok[ki] = true;
   }

@@ -1,28 +1,36 @@
 // Grouped dequantize-GEMM, tile kernel for large buckets (prefill, images).
 //
 // Each sample is processed by its selected expert only (MoQE Section 3.1); when an expert's bucket
-// holds hundreds of rows the work is a dense contraction and belongs on the matrix cores with both
-// operands staged through LDS.  A work-group of 8 waves owns a 128 x 128 output tile of one
-// expert: 128 bucket rows (gathered through the permutation on load) times 128 weight rows (for
-// the SiLU-gated pair: 64 gate rows and the 64 up rows of the same features, so the gate meets its
-// up value in registers).  Per 128-column k-tile every wave fetches one packed 16-row weight tile
-// with the same coalesced 16-byte-per-lane load as the streaming kernel, unpacks it to exact bf16
-// operands (BASE + c/2) and stores them to LDS; the activation tile goes global -> registers ->
-// LDS; the next k-tile's loads are in flight while the current one is multiplied.  Offsets and
-// zero-points are removed with the activation row sums (an MFMA against ones) and the fp32 scale
-// multiplies each group's fp32 partial sum, exactly as in the streaming kernel: no weight is
-// rounded.
+// holds hundreds of rows the work is a dense contraction and belongs on the matrix cores.  A
+// work-group of 8 waves (2 along the rows x 4 along the weight rows) owns 128 bucket rows x 256
+// weight rows of one expert (for the SiLU-gated pair: 128 gate rows and the 128 up rows of the
+// same features, so the gate meets its up value in registers); a wave owns 64 x 64.
+//
+//  * Activations: the 128 x 128 tile of a k-step is gathered through the permutation into
+//    registers and written to LDS (rows of 256 bytes, 16-byte units XOR-swizzled by the row so
+//    that the 16-byte-per-lane operand reads are free of bank conflicts), double-buffered, one
+//    barrier per k-step.
+//  * Weights never touch LDS: the packed layout already is the matrix-core operand order, so each
+//    wave loads the four packed 16-row tiles of its 64 weight rows with one coalesced 16-byte-per-
+//    lane load each (two k-steps ahead) and unpacks them in registers to exact bf16 operands
+//    BASE + c/2.  LDS traffic is thus one 16-byte read per lane for every four matrix-core
+//    operations.
+//  * Offset and zero-point are removed with the row sums of the activations (an MFMA against
+//    ones), as in the streaming kernel.  Per-group scales use ONE accumulator: entering group g
+//    the accumulator is multiplied by s_{g-1}/s_g, so that it always holds the sum in units of the
+//    current group's scale, and the last scale multiplies the result.  No weight is rounded; the
+//    extra roundings are one fp32 multiply per group on the accumulator.
 #include "qgemm_device.h"
 
 namespace moqe {
 
 constexpr int TBM = 128;                 // bucket rows per work-group tile
-constexpr int TBN = 128;                 // weight rows per work-group tile
-constexpr int TWAVES = 8;
-constexpr int TMB = 2;                   // 16-row blocks per wave (rows)
-constexpr int TNB = 4;                   // 16-row blocks per wave (weight rows)
-
-template <bool A8> __host__ __device__ constexpr int tile_row_stride() { return 128 * (A8 ? 1 : 2) + 16; }
+constexpr int TWM = 2, TWN = 4;          // waves along rows / weight rows
+constexpr int TWAVES = TWM * TWN;
+constexpr int TMB = 4, TNB = 4;          // 16 x 16 blocks per wave: 64 rows x 64 weight rows
+constexpr int TBN = TWN * TNB * 16;      // 256 weight rows per work-group tile
+constexpr int T_SLOT = 256;              // LDS bytes per staged row and k-step (int8 rows use half)
+constexpr int T_LDS_BYTES = 2 * TBM * T_SLOT;
 
 template <int FMT, int GM, bool GATEUP>
 static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int m0,
@@ -31,48 +39,45 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
   constexpr int NR = Raw<FMT>::N;
   constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
   constexpr int EB = A8 ? 1 : 2;
-  constexpr int RS = tile_row_stride<A8>();
-  constexpr int A_CHUNKS = 128 * EB / 16;            // 16-byte chunks per activation row and k-tile
-  constexpr int A_ROWS_PER_IT = TWAVES * 64 / A_CHUNKS;
+  constexpr int A_UNITS = 128 * EB / 16;             // 16-byte units per activation row and k-step
+  constexpr int A_ROWS_PER_IT = TWAVES * 64 / A_UNITS;
   constexpr int A_ITERS = TBM / A_ROWS_PER_IT;
   constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
 
-  uint8_t* const lds_a = lds;
-  uint8_t* const lds_b = lds + TBM * RS;
-  float* const lds_sc = reinterpret_cast<float*>(lds + (TBM + TBN) * RS);        // [TBN][2]
-  float* const lds_o = lds_sc + TBN * 2;                                            // [TBN][2]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // uniform: keeps tile addresses scalar
   const int lr = lane & 15, lq = lane >> 4;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
   const int KT = ga.k >> 7, NT = ga.n >> 4;
   const int T = ga.T;
   const int off_e = ga.offsets[e];
   const int M_e = (ga.offsets[e + 1] - off_e) * T;
   const float off_sym = BASE + CM * float(ex.zc);
 
-  // ---- the packed weight tile this wave fetches per k-tile, and where its rows go in LDS -------
-  int nt16;                                   // 16-row tile index inside the matrix
-  const uint8_t* blob;
-  if constexpr (GATEUP) {
-    nt16 = ntile * 4 + (wave & 3);            // waves 0-3: gate rows, waves 4-7: up rows of the same features
-    blob = ex.w[wave >> 2];
-  } else {
-    nt16 = ntile * 8 + wave;
-    blob = ex.w[0];
-  }
-  const bool nt_ok = nt16 < NT;
-  const int nt_ld = nt_ok ? nt16 : 0;         // clamped: rows outside the matrix are computed on garbage, never stored
-  // ---- the weight-row blocks this wave multiplies (LDS rows) -------------------------------------
-  int nb_row[TNB];
+  // ---- the four packed weight tiles of this wave (16 weight rows each) -----------------------------
+  const uint8_t* blob[TNB];
+  uint32_t tbase[TNB];                        // index of the tile's first k-step inside the blob
+  int ncol[TNB];                              // weight row (plain) / feature (gate-up) of block b at lane column lr
+  bool nok[TNB];
 #pragma unroll
-  for (int b = 0; b < TNB; ++b)
-    nb_row[b] = GATEUP ? ((b >> 1) * 64 + wn * 32 + (b & 1) * 16) : (wn * 64 + b * 16);
+  for (int b = 0; b < TNB; ++b) {
+    int nt16;
+    if constexpr (GATEUP) {
+      nt16 = ntile * 8 + wn * 2 + (b & 1);    // blocks 0,1: gate rows; blocks 2,3: up rows of the same features
+      blob[b] = ex.w[b >> 1];
+    } else {
+      nt16 = ntile * 16 + wn * 4 + b;
+      blob[b] = ex.w[0];
+    }
+    nok[b] = nt16 < NT;
+    ncol[b] = nt16 * 16 + lr;
+    tbase[b] = uint32_t((nok[b] ? nt16 : 0) * KT);      // clamped: rows outside the matrix are computed on other rows' codes, never stored
+  }
 
-  // ---- activation rows this thread copies per k-tile ----------------------------------------------
+  // ---- activation rows this thread copies per k-step ------------------------------------------------
   const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
   uint32_t a_off[A_ITERS];
-  const int a_chunk = tid % A_CHUNKS, a_row0 = tid / A_CHUNKS;
+  const int a_unit = tid % A_UNITS, a_row0 = tid / A_UNITS;
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
     const int m = min(m0 + a_row0 + i * A_ROWS_PER_IT, M_e - 1);      // rows past the bucket repeat its last row
@@ -80,174 +85,212 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
     if constexpr (A8) src = size_t(off_e) * T + m;
     else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
     else src = size_t(off_e) * T + m;
-    a_off[i] = uint32_t(src * size_t(ga.k) * EB + a_chunk * 16);
+    a_off[i] = uint32_t(src * size_t(ga.k) * EB + a_unit * 16);
   }
-
   u32x4 a_reg[A_ITERS];
-  uint32_t raw[NR];
-  float sc_reg[GPT ? GPT : 1];
-  uint32_t zp_reg = 0;
-  auto prefetch = [&](int kt) {
+  auto a_fetch = [&](int kt) {
+    const uint32_t koff = uint32_t(min(kt, KT - 1)) * (128 * EB);
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i)
-      a_reg[i] = *reinterpret_cast<const u32x4*>(abase + size_t(a_off[i]) + size_t(kt) * 128 * EB);
-    const size_t t = size_t(nt_ld) * KT + kt;
-    load_raw<FMT>(raw, blob + t * ex.tile_bytes, lane);
-    if constexpr (GPT > 0) {
-      const float* sp = reinterpret_cast<const float*>(blob + ex.scale_off) + (t * 16 + lr) * GPT;
-      const uint8_t* zq = blob + ex.zero_off + (t * 16 + lr) * GPT;
-      if constexpr (GPT == 1) {
-        sc_reg[0] = sp[0];
-        zp_reg = uint32_t(zq[0]);
-      } else {
-        const float2 v = *reinterpret_cast<const float2*>(sp);
-        sc_reg[0] = v.x; sc_reg[1] = v.y;
-        zp_reg = uint32_t(*reinterpret_cast<const uint16_t*>(zq));
-      }
+    for (int i = 0; i < A_ITERS; ++i) a_reg[i] = *reinterpret_cast<const u32x4*>(abase + (a_off[i] + koff));
+  };
+  auto a_store = [&](uint8_t* buf) {
+#pragma unroll
+    for (int i = 0; i < A_ITERS; ++i) {
+      const int row = a_row0 + i * A_ROWS_PER_IT;
+      *reinterpret_cast<u32x4*>(buf + row * T_SLOT + ((a_unit ^ (row & 15)) * 16)) = a_reg[i];
     }
   };
-  auto stage = [&]() {                        // registers -> LDS (weights are unpacked on the way)
+
+  // ---- weight ring: two k-steps in flight ------------------------------------------------------------
+  uint32_t raw[2][TNB][NR];
+  float sc[2][TNB][GPT ? GPT : 1];
+  uint32_t zp[2][TNB];
+  auto issue_w = [&](int p, int kt_want) {
+    const uint32_t kt = uint32_t(min(kt_want, KT - 1));
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i)
-      *reinterpret_cast<u32x4*>(lds_a + (a_row0 + i * A_ROWS_PER_IT) * RS + a_chunk * 16) = a_reg[i];
-    uint8_t* brow = lds_b + (wave * 16 + lr) * RS;
-    if constexpr (A8) {
-      *reinterpret_cast<u32x4*>(brow + lq * 16) = u32x4{raw[0], raw[1], raw[2], raw[3]};
-      *reinterpret_cast<u32x4*>(brow + 64 + lq * 16) = u32x4{raw[4], raw[5], raw[6], raw[7]};
-    } else {
-      *reinterpret_cast<bf16x8*>(brow + (0 * 32 + lq * 8) * 2) = frag<FMT, 0>(raw);
-      *reinterpret_cast<bf16x8*>(brow + (1 * 32 + lq * 8) * 2) = frag<FMT, 1>(raw);
-      *reinterpret_cast<bf16x8*>(brow + (2 * 32 + lq * 8) * 2) = frag<FMT, 2>(raw);
-      *reinterpret_cast<bf16x8*>(brow + (3 * 32 + lq * 8) * 2) = frag<FMT, 3>(raw);
+    for (int b = 0; b < TNB; ++b) {
+      const uint32_t t = tbase[b] + kt;
+      load_raw<FMT>(raw[p][b], blob[b] + t * ex.tile_bytes, lane);
       if constexpr (GPT > 0) {
-        if (lq == 0) {
-#pragma unroll
-          for (int g = 0; g < GPT; ++g) {
-            lds_sc[(wave * 16 + lr) * 2 + g] = sc_reg[g] * INV_CM;
-            lds_o[(wave * 16 + lr) * 2 + g] = BASE + CM * float((zp_reg >> (8 * g)) & 0xffu);
-          }
+        const uint8_t* sp = blob[b] + (ex.scale_off + t * uint32_t(16 * GPT * 4));
+        const uint8_t* zq = blob[b] + (ex.zero_off + t * uint32_t(16 * GPT));
+        // zero-points: the aligned dword holding the lane's byte(s), shifted down where it is used
+        if constexpr (GPT == 1) {
+          sc[p][b][0] = *reinterpret_cast<const float*>(sp + uint32_t(lr) * 4u);
+          zp[p][b] = *reinterpret_cast<const uint32_t*>(zq + (uint32_t(lr) & ~3u));
+        } else {
+          const float2 v = *reinterpret_cast<const float2*>(sp + uint32_t(lr) * 8u);
+          sc[p][b][0] = v.x; sc[p][b][1] = v.y;
+          zp[p][b] = *reinterpret_cast<const uint32_t*>(zq + ((uint32_t(lr) * 2u) & ~3u));
         }
       }
     }
   };
+  const uint32_t zp_shift = GPT == 2 ? 16u * (uint32_t(lr) & 1u) : 8u * (uint32_t(lr) & 3u);
 
-  f32x4 tot[TMB][TNB];        // bf16 path: fp32 results; int8 path: int32 bit patterns
-  f32x4 xs_tot[TMB];
+  f32x4 tot[TMB][TNB];        // bf16 path: fp32 sums in units of the current group's scale; int8 path: int32 bit patterns
+  f32x4 xs_tot[TMB];          // per-channel formats: row sums of the activations over all of k
+  float s_cur[TNB];           // scale of the group the accumulators are expressed in
 #pragma unroll
   for (int mb = 0; mb < TMB; ++mb) {
     xs_tot[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int b = 0; b < TNB; ++b) tot[mb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
+#pragma unroll
+  for (int b = 0; b < TNB; ++b) s_cur[b] = 1.f;
   const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
-  const uint8_t* a_rd = lds_a + (wm * 32 + lr) * RS;     // + mb*16*RS + column bytes
-  const uint8_t* b_rd = lds_b + lr * RS;                 // + nb_row*RS + column bytes
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
-  prefetch(0);
-  for (int kt = 0; kt < KT; ++kt) {
-    __syncthreads();                          // the previous k-tile is no longer read
-    stage();
-    __syncthreads();
-    prefetch(min(kt + 1, KT - 1));            // unconditional (clamped): stays in flight during the multiply
+  // One k-step: activation operands from LDS buffer `abuf`, weights from ring slot p.
+  auto compute = [&](int p, const uint8_t* abuf) {
+    // The ring values arrive through the loop's back edge; the fence keeps the optimizer from moving
+    // arithmetic on them to the end of the previous iteration, right behind their loads.
+#pragma unroll
+    for (int b = 0; b < TNB; ++b) {
+#pragma unroll
+      for (int i = 0; i < NR; ++i) asm volatile("" : "+v"(raw[p][b][i]));
+      if constexpr (GPT > 0) {
+        asm volatile("" : "+v"(zp[p][b]));
+#pragma unroll
+        for (int g = 0; g < GPT; ++g) asm volatile("" : "+v"(sc[p][b][g]));
+      }
+    }
+    const uint8_t* arow = abuf + (wm * 64 + lr) * T_SLOT;       // + mb * 16 rows; unit u of row lr sits at (u ^ lr) * 16
     if constexpr (A8) {
 #pragma unroll
       for (int js = 0; js < 2; ++js) {
-        i32x4 a[TMB], b[TNB];
-#pragma unroll
-        for (int mb = 0; mb < TMB; ++mb) a[mb] = *reinterpret_cast<const i32x4*>(a_rd + mb * 16 * RS + js * 64 + lq * 16);
-#pragma unroll
-        for (int nb = 0; nb < TNB; ++nb) b[nb] = *reinterpret_cast<const i32x4*>(b_rd + nb_row[nb] * RS + js * 64 + lq * 16);
+        i32x4 a[TMB];
 #pragma unroll
         for (int mb = 0; mb < TMB; ++mb)
+          a[mb] = *reinterpret_cast<const i32x4*>(arow + mb * 16 * T_SLOT + (((js * 4 + lq) ^ lr) * 16));
 #pragma unroll
-          for (int nb = 0; nb < TNB; ++nb) {
-            i32x4 acc = __builtin_bit_cast(i32x4, tot[mb][nb]);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mb], b[nb], acc, 0, 0, 0);
-            tot[mb][nb] = __builtin_bit_cast(f32x4, acc);
-          }
+        for (int b = 0; b < TNB; ++b) {
+          const i32x4 bv = {int(raw[p][b][js * 4 + 0]), int(raw[p][b][js * 4 + 1]), int(raw[p][b][js * 4 + 2]),
+                            int(raw[p][b][js * 4 + 3])};
+#pragma unroll
+          for (int mb = 0; mb < TMB; ++mb)
+            tot[mb][b] = __builtin_bit_cast(
+                f32x4, __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mb], bv, __builtin_bit_cast(i32x4, tot[mb][b]), 0, 0, 0));
+        }
       }
     } else {
-      constexpr int GSTEPS = GM == GM_G64 ? 2 : 4;      // MFMA steps per quantization group
-      f32x4 v[TMB][TNB], xs[TMB];
-      auto do_step = [&](auto jc) {
+      constexpr int GSTEPS = GM == GM_G64 ? 2 : 4;     // matrix-core steps per quantization group
+      f32x4 xs[TMB];
+      auto do_j = [&](auto jc) {
         constexpr int J = decltype(jc)::value;
-        if constexpr (GM != GM_PC && J % GSTEPS == 0) {
-#pragma unroll
-          for (int mb = 0; mb < TMB; ++mb) {
-            xs[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int nb = 0; nb < TNB; ++nb) v[mb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-          }
-        }
-        u32x4 a[TMB];
-        bf16x8 b[TNB];
-#pragma unroll
-        for (int mb = 0; mb < TMB; ++mb) a[mb] = *reinterpret_cast<const u32x4*>(a_rd + mb * 16 * RS + (J * 32 + lq * 8) * 2);
-#pragma unroll
-        for (int nb = 0; nb < TNB; ++nb) b[nb] = *reinterpret_cast<const bf16x8*>(b_rd + nb_row[nb] * RS + (J * 32 + lq * 8) * 2);
-#pragma unroll
-        for (int mb = 0; mb < TMB; ++mb) {
-          if constexpr (GM == GM_PC) xs_tot[mb] = mfma_bf16(a[mb], ones_b, xs_tot[mb]);
-          else xs[mb] = mfma_bf16(a[mb], ones_b, xs[mb]);
-#pragma unroll
-          for (int nb = 0; nb < TNB; ++nb) {
-            if constexpr (GM == GM_PC) tot[mb][nb] = mfma_bf16(a[mb], b[nb], tot[mb][nb]);
-            else v[mb][nb] = mfma_bf16(a[mb], b[nb], v[mb][nb]);
-          }
-        }
-        if constexpr (GM != GM_PC && (J + 1) % GSTEPS == 0) {
+        if constexpr (GM != GM_PC && J % GSTEPS == 0) {     // entering a group: accumulators into its scale's units
           constexpr int G = J / GSTEPS;
 #pragma unroll
-          for (int nb = 0; nb < TNB; ++nb) {
-            const float scv = lds_sc[(nb_row[nb] + lr) * 2 + G];
-            const float o = lds_o[(nb_row[nb] + lr) * 2 + G];
+          for (int b = 0; b < TNB; ++b) {
+            const float s_new = sc[p][b][G < GPT ? G : 0];
+            const float rho = s_cur[b] / s_new;
+            s_cur[b] = s_new;
 #pragma unroll
             for (int mb = 0; mb < TMB; ++mb)
 #pragma unroll
-              for (int r = 0; r < 4; ++r) tot[mb][nb][r] += scv * (v[mb][nb][r] - o * xs[mb][r]);
+              for (int r = 0; r < 4; ++r) tot[mb][b][r] *= rho;
+          }
+        }
+        u32x4 a[TMB];
+        bf16x8 bv[TNB];
+#pragma unroll
+        for (int mb = 0; mb < TMB; ++mb)
+          a[mb] = *reinterpret_cast<const u32x4*>(arow + mb * 16 * T_SLOT + (((J * 4 + lq) ^ lr) * 16));
+#pragma unroll
+        for (int b = 0; b < TNB; ++b) bv[b] = frag<FMT, J>(raw[p][b]);
+#pragma unroll
+        for (int mb = 0; mb < TMB; ++mb) {
+          if constexpr (GM == GM_PC) xs_tot[mb] = mfma_bf16(a[mb], ones_b, xs_tot[mb]);
+          else xs[mb] = mfma_bf16(a[mb], ones_b, (J % GSTEPS == 0) ? zero : xs[mb]);
+        }
+#pragma unroll
+        for (int b = 0; b < TNB; ++b)
+#pragma unroll
+          for (int mb = 0; mb < TMB; ++mb) {
+            if constexpr (GM != GM_PC && J % GSTEPS == 0) {
+              // The accumulator was just rewritten by vector arithmetic, so the matrix-core result may be
+              // given other registers than its input.  Keeping the input alive across the operation
+              // makes the two register ranges disjoint; a partial overlap gives wrong sums.
+              const f32x4 c_in = tot[mb][b];
+              tot[mb][b] = mfma_bf16(a[mb], bv[b], c_in);
+              asm volatile("" :: "v"(c_in));
+            } else {
+              tot[mb][b] = mfma_bf16(a[mb], bv[b], tot[mb][b]);
+            }
+          }
+        if constexpr (GM != GM_PC && (J + 1) % GSTEPS == 0) {   // leaving a group: remove offset and zero-point
+          constexpr int G = J / GSTEPS;
+#pragma unroll
+          for (int b = 0; b < TNB; ++b) {
+            const float o = BASE + CM * float(((zp[p][b] >> zp_shift) >> (8 * G)) & 0xffu);
+#pragma unroll
+            for (int mb = 0; mb < TMB; ++mb)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) tot[mb][b][r] -= o * xs[mb][r];
           }
         }
       };
-      do_step(std::integral_constant<int, 0>{});
-      do_step(std::integral_constant<int, 1>{});
-      do_step(std::integral_constant<int, 2>{});
-      do_step(std::integral_constant<int, 3>{});
+      do_j(std::integral_constant<int, 0>{});
+      do_j(std::integral_constant<int, 1>{});
+      do_j(std::integral_constant<int, 2>{});
+      do_j(std::integral_constant<int, 3>{});
     }
-  }
+  };
 
-  // ---- epilogue ---------------------------------------------------------------------------------------
-  // global weight row of block nb, column lr
-  int ncol[TNB];
-  bool nok[TNB];
-  float pcs[TNB];
+  // ---- prologue: k-step 0 of the activations into LDS, k-step 1 in registers, two weight steps in flight
+  a_fetch(0);
+  a_store(lds);
+  issue_w(0, 0);
+  issue_w(1, 1);
+  a_fetch(1);
+  __syncthreads();
+
+  // ---- main loop, two k-steps per iteration so that ring slot and LDS buffer are static ----------
+  auto step = [&](int kt, int p) {
+    compute(p, lds + p * (TBM * T_SLOT));
+    issue_w(p, kt + 2);
+    a_store(lds + (p ^ 1) * (TBM * T_SLOT));       // k-step kt+1; that buffer was last read in step kt-1
+    a_fetch(kt + 2);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int kt = 0;
+#pragma unroll 1
+  for (; kt + 2 <= KT; kt += 2) {
+    step(kt, 0);
+    step(kt + 1, 1);
+  }
+  if (kt < KT) step(kt, 0);                         // uniform over the grid
+
+  // ---- epilogue -----------------------------------------------------------------------------------------
+  float fin[TNB];                                   // factor that turns the accumulator into the result
 #pragma unroll
-  for (int nb = 0; nb < TNB; ++nb) {
-    if constexpr (GATEUP) ncol[nb] = ntile * 64 + wn * 32 + (nb & 1) * 16 + lr;       // feature index (gate and up)
-    else ncol[nb] = ntile * 128 + wn * 64 + nb * 16 + lr;
-    nok[nb] = ncol[nb] < ga.n;
-    pcs[nb] = 1.f;
+  for (int b = 0; b < TNB; ++b) {
     if constexpr (GM == GM_PC) {
-      const uint8_t* bl = GATEUP ? ex.w[nb >> 1] : ex.w[0];
-      if (nok[nb]) pcs[nb] = reinterpret_cast<const float*>(bl + ex.scale_off)[ncol[nb]];
+      const uint8_t* bl = blob[b];
+      fin[b] = nok[b] ? reinterpret_cast<const float*>(bl + ex.scale_off)[ncol[b]] : 1.f;
+    } else {
+      fin[b] = s_cur[b] * INV_CM;
     }
   }
 #pragma unroll
   for (int mb = 0; mb < TMB; ++mb) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int m = m0 + wm * 32 + mb * 16 + lq * 4 + r;
+      const int m = m0 + wm * 64 + mb * 16 + lq * 4 + r;
       if (m < M_e) {
         float val[TNB];
 #pragma unroll
-        for (int nb = 0; nb < TNB; ++nb) {
+        for (int b = 0; b < TNB; ++b) {
           if constexpr (A8) {
             const float sx = ga.a_scale[size_t(off_e) * T + m];
-            val[nb] = float(__float_as_int(tot[mb][nb][r])) * sx * pcs[nb];
+            val[b] = float(__float_as_int(tot[mb][b][r])) * sx * fin[b];
           } else if constexpr (GM == GM_PC) {
-            val[nb] = (pcs[nb] * INV_CM) * (tot[mb][nb][r] - off_sym * xs_tot[mb][r]);
+            val[b] = (fin[b] * INV_CM) * (tot[mb][b][r] - off_sym * xs_tot[mb][r]);
           } else {
-            val[nb] = tot[mb][nb][r];
+            val[b] = tot[mb][b][r] * fin[b];
           }
         }
         const size_t brow = size_t(off_e) * T + m;
@@ -260,8 +303,8 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
           if (ga.y_perm) drow = size_t(ga.y_perm[off_e + m / T]) * T + (m % T);
           float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
 #pragma unroll
-          for (int nb = 0; nb < TNB; ++nb)
-            if (nok[nb]) y[ncol[nb]] = val[nb];
+          for (int b = 0; b < TNB; ++b)
+            if (nok[b]) y[ncol[b]] = val[b];
         }
       }
     }
@@ -269,7 +312,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
 }
 
 template <bool GATEUP>
-__global__ __launch_bounds__(TWAVES * 64) void k_qgemm_tile(const GemmArgs ga) {
+__global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga) {
   extern __shared__ __align__(16) uint8_t lds[];
   // which expert and which 128-row tile of its bucket: blockIdx.y counts row tiles over all experts
   int slot = blockIdx.y, e = -1, m0 = 0;
@@ -298,19 +341,18 @@ __global__ __launch_bounds__(TWAVES * 64) void k_qgemm_tile(const GemmArgs ga) {
 int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
   const int M = ga.S * ga.T;
   const int row_tiles = (M + TBM - 1) / TBM + ga.n_experts;      // upper bound on sum_e ceil(M_e / 128)
-  const int n_tiles = gateup ? (ga.n + 63) / 64 : (ga.n + TBN - 1) / TBN;
+  const int n_tiles = gateup ? (ga.n + TBN / 2 - 1) / (TBN / 2) : (ga.n + TBN - 1) / TBN;
   if (row_tiles > 65535) return set_error(MOQE_E_SHAPE, "grouped_qgemm: %d rows exceed the tile kernel's grid", M);
-  const int lds_bytes = (TBM + TBN) * tile_row_stride<false>() + TBN * 2 * 4 * 2;
   static bool lds_ok[2] = {false, false};
   const void* fn = gateup ? reinterpret_cast<const void*>(&k_qgemm_tile<true>) : reinterpret_cast<const void*>(&k_qgemm_tile<false>);
   if (!lds_ok[gateup ? 1 : 0]) {
-    hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS_BYTES);
     if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: cannot reserve LDS: %s", hipGetErrorString(err));
     lds_ok[gateup ? 1 : 0] = true;
   }
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL(k_qgemm_tile<true>, dim3(n_tiles, row_tiles), dim3(TWAVES * 64), lds_bytes, st, ga);
-  else hipLaunchKernelGGL(k_qgemm_tile<false>, dim3(n_tiles, row_tiles), dim3(TWAVES * 64), lds_bytes, st, ga);
+  if (gateup) hipLaunchKernelGGL(k_qgemm_tile<true>, dim3(n_tiles, row_tiles), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
+  else hipLaunchKernelGGL(k_qgemm_tile<false>, dim3(n_tiles, row_tiles), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
   return check_launch("grouped_qgemm(tile)");
 }
 

@@ -54,13 +54,33 @@ static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], cons
   }
 }
 
-// (x & mask) | orv in one VALU operation (the mask travels in a scalar register, which the
-// three-operand encoding allows once per instruction).
-static __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t orv) {
-  uint32_t d;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(orv));
-  return d;
+// Constants of the unpacking, made opaque to the optimizer once per kernel: the mask lives in a
+// scalar register and the bf16 exponent pattern in a vector register, so that (x & mask) | pattern
+// is selected as ONE three-operand instruction (two literals do not fit its encoding, and with
+// visible literals the compiler falls back to two instructions).  The unpacking itself stays plain
+// C: the compiler must see every vector instruction that runs next to the matrix-core operations
+// to place the wait states their register hazards need, which it cannot do for inline assembly.
+template <uint32_t V> static __device__ __forceinline__ uint32_t opaque_sgpr() {
+  uint32_t r;
+  asm("s_mov_b32 %0, %1" : "=s"(r) : "n"(V));
+  return r;
 }
+template <uint32_t V> static __device__ __forceinline__ uint32_t opaque_vgpr() {
+  uint32_t r;
+  asm("v_mov_b32 %0, %1" : "=v"(r) : "n"(V));
+  return r;
+}
+
+template <int FMT> struct FragK { uint32_t m0, m1, pat; };
+template <int FMT> static __device__ __forceinline__ FragK<FMT> frag_constants() {
+  FragK<FMT> k{0u, 0u, 0u};
+  if constexpr (FMT == FMT_N4) { k.m0 = opaque_sgpr<0x00780078u>(); k.pat = opaque_vgpr<0x41004100u>(); }
+  if constexpr (FMT == FMT_N3) { k.m0 = opaque_sgpr<0x00300030u>(); k.m1 = opaque_sgpr<0x00400040u>(); k.pat = opaque_vgpr<0x40804080u>(); }
+  if constexpr (FMT == FMT_N6) { k.m0 = opaque_sgpr<0x001E001Eu>(); k.m1 = opaque_sgpr<0x00600060u>(); k.pat = opaque_vgpr<0x42004200u>(); }
+  return k;
+}
+
+static __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t orv) { return (x & mask) | orv; }
 
 template <int SH> static __device__ __forceinline__ uint32_t shift_by(uint32_t v) {
   if constexpr (SH >= 0) return v >> SH; else return v << (-SH);
@@ -69,7 +89,7 @@ template <int SH> static __device__ __forceinline__ uint32_t shift_by(uint32_t v
 // The matrix-core operand of step J (columns 32J + 8kq + 0..7 of the lane's row) as 8 bf16
 // values BASE + CM * code.
 template <int FMT, int J>
-static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N]) {
+static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N], const FragK<FMT>& k) {
   u32x4 d;
   if constexpr (FMT == FMT_I8) {
     const uint32_t u0 = r[(J / 2) * 4 + (J % 2) * 2], u1 = r[(J / 2) * 4 + (J % 2) * 2 + 1];
@@ -83,26 +103,26 @@ static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N]) 
     d.z = __builtin_amdgcn_perm(f5, f4, 0x07060302u);
     d.w = __builtin_amdgcn_perm(f7, f6, 0x07060302u);
   } else if constexpr (FMT == FMT_N4) {
-    const uint32_t w = r[J];
-    d.x = and_or(shift_by<-3>(w), 0x00780078u, 0x41004100u);
-    d.y = and_or(shift_by<1>(w), 0x00780078u, 0x41004100u);
-    d.z = and_or(shift_by<5>(w), 0x00780078u, 0x41004100u);
-    d.w = and_or(shift_by<9>(w), 0x00780078u, 0x41004100u);
+    const uint32_t w = r[J];                      // 0x4100 | c << 3 per 16-bit half
+    d.x = and_or(shift_by<-3>(w), k.m0, k.pat);
+    d.y = and_or(shift_by<1>(w), k.m0, k.pat);
+    d.z = and_or(shift_by<5>(w), k.m0, k.pat);
+    d.w = and_or(shift_by<9>(w), k.m0, k.pat);
   } else if constexpr (FMT == FMT_N3) {
-    const uint32_t lo = r[J / 2], hi = r[2];
+    const uint32_t lo = r[J / 2], hi = r[2];      // 0x4080 | c << 4: two low bits from `lo`, the high bit from `hi`
     constexpr int P0 = 4 * (J % 2);       // first 2-bit field of this step inside `lo`
     constexpr int Q0 = 4 * J;             // first 1-bit field of this step inside `hi`
-    d.x = and_or(shift_by<2 * (P0 + 0) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 0 - 6>(hi), 0x00400040u, 0x40804080u));
-    d.y = and_or(shift_by<2 * (P0 + 1) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 1 - 6>(hi), 0x00400040u, 0x40804080u));
-    d.z = and_or(shift_by<2 * (P0 + 2) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 2 - 6>(hi), 0x00400040u, 0x40804080u));
-    d.w = and_or(shift_by<2 * (P0 + 3) - 4>(lo), 0x00300030u, and_or(shift_by<Q0 + 3 - 6>(hi), 0x00400040u, 0x40804080u));
-  } else {  // FMT_N6
+    d.x = and_or(shift_by<2 * (P0 + 0) - 4>(lo), k.m0, and_or(shift_by<Q0 + 0 - 6>(hi), k.m1, k.pat));
+    d.y = and_or(shift_by<2 * (P0 + 1) - 4>(lo), k.m0, and_or(shift_by<Q0 + 1 - 6>(hi), k.m1, k.pat));
+    d.z = and_or(shift_by<2 * (P0 + 2) - 4>(lo), k.m0, and_or(shift_by<Q0 + 2 - 6>(hi), k.m1, k.pat));
+    d.w = and_or(shift_by<2 * (P0 + 3) - 4>(lo), k.m0, and_or(shift_by<Q0 + 3 - 6>(hi), k.m1, k.pat));
+  } else {  // FMT_N6: 0x4200 | c << 1: four low bits from `w`, two high bits from `hi`
     const uint32_t w = r[J], hi = r[4 + J / 2];
     constexpr int P0 = 4 * (J % 2);
-    d.x = and_or(shift_by<-1>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 0) - 5>(hi), 0x00600060u, 0x42004200u));
-    d.y = and_or(shift_by<3>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 1) - 5>(hi), 0x00600060u, 0x42004200u));
-    d.z = and_or(shift_by<7>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 2) - 5>(hi), 0x00600060u, 0x42004200u));
-    d.w = and_or(shift_by<11>(w), 0x001E001Eu, and_or(shift_by<2 * (P0 + 3) - 5>(hi), 0x00600060u, 0x42004200u));
+    d.x = and_or(shift_by<-1>(w), k.m0, and_or(shift_by<2 * (P0 + 0) - 5>(hi), k.m1, k.pat));
+    d.y = and_or(shift_by<3>(w), k.m0, and_or(shift_by<2 * (P0 + 1) - 5>(hi), k.m1, k.pat));
+    d.z = and_or(shift_by<7>(w), k.m0, and_or(shift_by<2 * (P0 + 2) - 5>(hi), k.m1, k.pat));
+    d.w = and_or(shift_by<11>(w), k.m0, and_or(shift_by<2 * (P0 + 3) - 5>(hi), k.m1, k.pat));
   }
   return __builtin_bit_cast(bf16x8, d);
 }

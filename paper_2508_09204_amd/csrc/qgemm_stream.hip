@@ -93,6 +93,7 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
   // sum_k x (c - z) = (1/CM) * (sum_k x (BASE + CM c) - (BASE + CM z) sum_k x)
   constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
   const float off_sym = BASE + CM * float(ex.zc);
+  const FragK<FMT> fk = frag_constants<FMT>();
   const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
 
@@ -209,10 +210,10 @@ static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const Exp
         f32x4 xs[MT][GPT ? GPT : 1];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-          const bf16x8 b0 = frag<FMT, 0>(raw[p][s]);
-          const bf16x8 b1 = frag<FMT, 1>(raw[p][s]);
-          const bf16x8 b2 = frag<FMT, 2>(raw[p][s]);
-          const bf16x8 b3 = frag<FMT, 3>(raw[p][s]);
+          const bf16x8 b0 = frag<FMT, 0>(raw[p][s], fk);
+          const bf16x8 b1 = frag<FMT, 1>(raw[p][s], fk);
+          const bf16x8 b2 = frag<FMT, 2>(raw[p][s], fk);
+          const bf16x8 b3 = frag<FMT, 3>(raw[p][s], fk);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
             if (mt * 16 < rows_here) {

@@ -53,6 +53,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
   const int off_e = ga.offsets[e];
   const int M_e = (ga.offsets[e + 1] - off_e) * T;
   const float off_sym = BASE + CM * float(ex.zc);
+  const FragK<FMT> fk = frag_constants<FMT>();
 
   // ---- the four packed weight tiles of this wave (16 weight rows each) -----------------------------
   const uint8_t* blob[TNB];
@@ -185,7 +186,12 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
 #pragma unroll
           for (int b = 0; b < TNB; ++b) {
             const float s_new = sc[p][b][G < GPT ? G : 0];
-            const float rho = s_cur[b] / s_new;
+            // s_cur / s_new from the hardware reciprocal and one Newton step (within an ulp or two of
+            // the true quotient; any error only moves rounding points, the factor is applied and
+            // divided out consistently)
+            float rinv = __builtin_amdgcn_rcpf(s_new);
+            rinv = fmaf(fmaf(-s_new, rinv, 1.0f), rinv, rinv);
+            const float rho = s_cur[b] * rinv;
             s_cur[b] = s_new;
 #pragma unroll
             for (int mb = 0; mb < TMB; ++mb)
@@ -199,7 +205,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
         for (int mb = 0; mb < TMB; ++mb)
           a[mb] = *reinterpret_cast<const u32x4*>(arow + mb * 16 * T_SLOT + (((J * 4 + lq) ^ lr) * 16));
 #pragma unroll
-        for (int b = 0; b < TNB; ++b) bv[b] = frag<FMT, J>(raw[p][b]);
+        for (int b = 0; b < TNB; ++b) bv[b] = frag<FMT, J>(raw[p][b], fk);
 #pragma unroll
         for (int mb = 0; mb < TMB; ++mb) {
           if constexpr (GM == GM_PC) xs_tot[mb] = mfma_bf16(a[mb], ones_b, xs_tot[mb]);

@@ -173,6 +173,12 @@ def test_forward_large_workloads_sampled_rows(name):
         ok, worst = ob.tolerance_ok(y[s][rows], y_ref)
         assert ok, (s, e, worst)
         if blk.w0[e].act_mode == 0:
+            # End to end against the oracle's own H.  The two sides may round a few H values to
+            # neighbouring bfloat16 numbers (checked and counted above); what such a difference adds to
+            # an output is at most sum_f |w2[n, f]| * |dH_f|, and a single flipped large H value can by
+            # itself exceed 2e-3 of the output's rms, so that bound is granted on top of the tolerance.
             y_e2e = oc.qlinear(h_ref, blk.w2[e])
-            ok, worst = ob.tolerance_ok(y[s][rows], y_e2e)
-            assert ok, (s, e, worst)
+            flip_allowance = np.abs(hg - h_ref) @ np.abs(oc._dequant_memo(blk.w2[e])).T
+            rms = float(np.sqrt(np.mean(y_e2e * y_e2e)))
+            bound = 2e-3 * np.maximum(np.abs(y_e2e), rms) + flip_allowance
+            assert np.all(np.abs(y[s][rows] - y_e2e) <= bound), (s, e)

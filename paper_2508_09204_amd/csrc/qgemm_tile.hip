@@ -317,20 +317,31 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
   }
 }
 
+// Work-group id -> tile.  The hardware deals consecutive work-group ids round-robin to the 8 XCDs,
+// each with its own L2, so the 32 work-groups that are resident on one XCD at a time are the ids
+// x, x + 8, x + 16, ...; they are made a patch of PATCH_M row tiles x PATCH_N weight tiles, which
+// run side by side over k and share their activation and weight tiles in that L2.  Consecutive
+// patches of an XCD, and the patches of the 8 XCDs at one time, walk along the weight rows first.
+constexpr int PATCH_M = 4, PATCH_N = 8;
+
 template <bool GATEUP>
 __global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga) {
   extern __shared__ __align__(16) uint8_t lds[];
-  // which expert and which 128-row tile of its bucket: blockIdx.y counts row tiles over all experts
-  int slot = blockIdx.y, e = -1, m0 = 0;
+  const int n_tiles = GATEUP ? (ga.n + TBN / 2 - 1) / (TBN / 2) : (ga.n + TBN - 1) / TBN;
+  const int patches_n = (n_tiles + PATCH_N - 1) / PATCH_N;
+  const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
+  const int patch = (j / (PATCH_M * PATCH_N)) * 8 + xcd, q = j % (PATCH_M * PATCH_N);
+  const int ntile = (patch % patches_n) * PATCH_N + q / PATCH_M;
+  // which expert and which 128-row tile of its bucket: `slot` counts row tiles over all experts
+  int slot = (patch / patches_n) * PATCH_M + q % PATCH_M, e = -1, m0 = 0;
   for (int i = 0; i < ga.n_experts; ++i) {
     const int rows = (ga.offsets[i + 1] - ga.offsets[i]) * ga.T;
     const int tiles = (rows + TBM - 1) / TBM;
     if (slot < tiles) { e = i; m0 = slot * TBM; break; }
     slot -= tiles;
   }
-  if (e < 0) return;                          // uniform over the work-group
+  if (e < 0 || ntile >= n_tiles) return;      // uniform over the work-group
   const ExpertDev& ex = ga.ex[e];
-  const int ntile = blockIdx.x;
   switch (ex.fmt * 4 + ex.gm) {
     case FMT_I8 * 4 + GM_PC:     tile_task<FMT_I8, GM_PC, GATEUP>(ga, ex, e, m0, ntile, lds); break;
     case FMT_I8A8 * 4 + GM_PC:   tile_task<FMT_I8A8, GM_PC, GATEUP>(ga, ex, e, m0, ntile, lds); break;
@@ -348,7 +359,9 @@ int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
   const int M = ga.S * ga.T;
   const int row_tiles = (M + TBM - 1) / TBM + ga.n_experts;      // upper bound on sum_e ceil(M_e / 128)
   const int n_tiles = gateup ? (ga.n + TBN / 2 - 1) / (TBN / 2) : (ga.n + TBN - 1) / TBN;
-  if (row_tiles > 65535) return set_error(MOQE_E_SHAPE, "grouped_qgemm: %d rows exceed the tile kernel's grid", M);
+  const long patches = long((row_tiles + PATCH_M - 1) / PATCH_M) * ((n_tiles + PATCH_N - 1) / PATCH_N);
+  const long grid = (patches + 7) / 8 * 8 * (PATCH_M * PATCH_N);
+  if (grid > 0x7fffffffL) return set_error(MOQE_E_SHAPE, "grouped_qgemm: %d rows exceed the tile kernel's grid", M);
   static bool lds_ok[2] = {false, false};
   const void* fn = gateup ? reinterpret_cast<const void*>(&k_qgemm_tile<true>) : reinterpret_cast<const void*>(&k_qgemm_tile<false>);
   if (!lds_ok[gateup ? 1 : 0]) {
@@ -357,8 +370,8 @@ int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
     lds_ok[gateup ? 1 : 0] = true;
   }
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL(k_qgemm_tile<true>, dim3(n_tiles, row_tiles), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
-  else hipLaunchKernelGGL(k_qgemm_tile<false>, dim3(n_tiles, row_tiles), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
+  if (gateup) hipLaunchKernelGGL(k_qgemm_tile<true>, dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
+  else hipLaunchKernelGGL(k_qgemm_tile<false>, dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
   return check_launch("grouped_qgemm(tile)");
 }
 

@@ -134,6 +134,7 @@ def main():
     ap.add_argument("--workload", default="llama7b_mlp_decode")
     ap.add_argument("--copies", type=int, default=0, help="rotating weight copies (0 = pick so that they exceed 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-int4-only", action="store_true", help="skip the extra all-int4 measurement of the decode launch")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the warm-up, run a plain device copy of 1 GiB five times (a kernel of known "
                          "traffic, for scaling hardware counters of a profiler run)")
@@ -156,14 +157,32 @@ def main():
     blocks = build_device_block(cfg, n_copies)
 
     dev = "cuda:0"
-    bits = wl.make_activations(cfg)
-    x = torch.from_numpy(bits.view("int16").reshape(cfg.M, cfg.D)).to(dev).view(torch.bfloat16)
-    n_out = cfg.D if is_mlp else cfg.F
-    y = torch.empty((cfg.M, n_out), dtype=torch.float32, device=dev)
-    counts = torch.zeros(cfg.K, dtype=torch.int32, device=dev)
-    aux = mq.Aux(counts=counts)
-    calls = [mq.ForwardCall(b, x, cfg.S, cfg.T, y, aux) for b in blocks]
-    stream = torch.cuda.current_stream().cuda_stream
+
+    def run_timed(cfg_run, blocks_run, steps, warmup):
+        """Times `steps` forwards (rotating over the weight copies); returns seconds, the routing
+        histogram, and the dominant kernel's launch count and summed duration from the library's
+        HIP events on the launch stream."""
+        bits = wl.make_activations(cfg_run)
+        x = torch.from_numpy(bits.view("int16").reshape(cfg_run.M, cfg_run.D)).to(dev).view(torch.bfloat16)
+        n_out = cfg_run.D if is_mlp else cfg_run.F
+        y = torch.empty((cfg_run.M, n_out), dtype=torch.float32, device=dev)
+        counts = torch.zeros(cfg_run.K, dtype=torch.int32, device=dev)
+        aux = mq.Aux(counts=counts)
+        calls = [mq.ForwardCall(b, x, cfg_run.S, cfg_run.T, y, aux) for b in blocks_run]
+        stream = torch.cuda.current_stream().cuda_stream
+        mq.moqe_profile_enable(1 << dominant)          # warm the event pool before the timed region
+        for i in range(warmup):
+            calls[i % len(calls)](stream)
+        torch.cuda.synchronize()
+        mq.moqe_profile_enable(1 << dominant)
+        t0 = time.perf_counter()
+        for i in range(steps):
+            calls[i % len(calls)](stream)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        launches, kern_ms = mq.moqe_profile_read(dominant)
+        mq.moqe_profile_enable(0)
+        return dt, counts.cpu().tolist(), launches, kern_ms
 
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -174,20 +193,8 @@ def main():
         del src, dst
 
     dominant = mq.PK_GEMM_GATEUP if is_mlp else mq.PK_GEMM_PLAIN
-    mq.moqe_profile_enable(1 << dominant)          # warm the event pool before the timed region
-    for i in range(args.warmup):
-        calls[i % n_copies](stream)
-    torch.cuda.synchronize()
-    mq.moqe_profile_enable(1 << dominant)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        calls[i % n_copies](stream)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    launches, kern_ms = mq.moqe_profile_read(dominant)
-    mq.moqe_profile_enable(0)
+    dt, hist, launches, kern_ms = run_timed(cfg, blocks, args.steps, args.warmup)
 
-    hist = counts.cpu().tolist()
     ms_per_step = dt * 1e3 / args.steps
     units = cfg.M if cfg.unit == "tokens" else cfg.S
     value = units / (dt / args.steps)
@@ -218,6 +225,24 @@ def main():
     roof["launches_timed"] = launches
     roof["algorithmic_bytes_per_launch"] = dom_bytes
     roof["algorithmic_flops_per_launch"] = dom_flops
+
+    # The decode target is stated for a grouped int4 GEMM: the same launch with all experts int4 g128.
+    if hbm_bound and is_mlp and not args.no_int4_only:
+        import dataclasses
+        del blocks
+        torch.cuda.empty_cache()
+        int4 = wl.configs.ExpertSpec(4, 128, False)
+        cfg4 = dataclasses.replace(cfg, experts=tuple([int4] * cfg.K))
+        per4 = sum(algorithmic_weight_bytes(n, k, int4) for (n, k) in mats.values()) * cfg.K
+        blocks4 = build_device_block(cfg4, max(2, min(8, -(-(1 << 30) // per4))))
+        steps4 = max(20, args.steps // 2)
+        _, hist4, launches4, kern_ms4 = run_timed(cfg4, blocks4, steps4, min(args.warmup, 10))
+        us4 = kern_ms4 * 1e3 / max(launches4, 1)
+        bytes4 = sum(sum(algorithmic_weight_bytes(n, k, int4) for (n, k) in dom_mats) for c in hist4 if c > 0)
+        roof["int4_only"] = {"experts": [int4.label()] * cfg.K, "kernel_us": us4, "launches_timed": launches4,
+                             "algorithmic_bytes_per_launch": bytes4, "achieved": bytes4 / (us4 * 1e-6) / 1e9,
+                             "frac": bytes4 / (us4 * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        del blocks4
 
     out = {
         "metric": "routed qGEMM throughput (whole routed block: route + bucket + grouped qGEMMs + scatter)",

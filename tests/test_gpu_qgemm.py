@@ -73,6 +73,38 @@ def test_mixed_experts_ragged_buckets(scatter, use_perm):
     assert ok, worst
 
 
+@pytest.mark.parametrize("bits,group,sym,clip,act", FORMATS)
+@pytest.mark.parametrize("S,T,n,k", [(5, 40, 208, 640), (3, 67, 272, 384)])
+def test_large_bucket_kernel_per_format(bits, group, sym, clip, act, S, T, n, k):
+    """Buckets of a few hundred rows take the LDS-tiled kernel: weight rows that do not fill the
+    256-row work-group tile or a wave's 64, an odd number of 128-column steps, a ragged last row tile."""
+    rng = np.random.default_rng(bits * 17 + group + n)
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    qm = oc.quantize(w, bits, group, sym, clip, act)
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((S * T, k)).astype(np.float32))
+    e = np.zeros(S, dtype=np.int32)
+    y = _run(a_bits, e, [qm], S, T)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, [qm], S, T))
+    assert ok, worst
+    assert worst < 0.05
+
+
+@pytest.mark.parametrize("scatter,use_perm", [(True, True), (False, False)])
+def test_large_bucket_kernel_mixed_experts(scatter, use_perm):
+    """Six formats in one launch of the tiled kernel, ragged buckets (one of a single sample, one empty)."""
+    rng = np.random.default_rng(22)
+    S, T, n, k = 14, 37, 144, 512
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    specs = [(4, 128, False, 1.0, 0), (3, 128, False, 1.0, 0), (8, 0, True, 1.0, 0), (8, 0, True, 1.0, 1),
+             (4, 64, False, 0.9, 0), (6, 0, True, 1.0, 0)]
+    qms = [oc.quantize(w, *s) for s in specs]
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((S * T, k)).astype(np.float32))
+    e = np.array([0, 1, 2, 3, 5, 0, 0, 1, 1, 1, 2, 3, 3, 0], dtype=np.int32)      # expert 4 empty, expert 5 one sample
+    y = _run(a_bits, e, qms, S, T, scatter, use_perm)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, qms, S, T))
+    assert ok, worst
+
+
 @pytest.mark.parametrize("rows", [1, 15, 16, 17, 31, 32, 33, 64, 100])
 def test_bucket_sizes_around_tile_edges(rows):
     rng = np.random.default_rng(rows)

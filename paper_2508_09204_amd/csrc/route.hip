@@ -166,19 +166,29 @@ __global__ __launch_bounds__(256) void k_router_logits_argmax(const float* __res
   const int lane = threadIdx.x & 63;
   const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (s >= S) return;
+  // every feature is formed once (its slices are added here) and meets all K weight rows
+  float acc[MOQE_MAX_EXPERTS];
+#pragma unroll
+  for (int k = 0; k < MOQE_MAX_EXPERTS; ++k) acc[k] = 0.f;
+  for (int d = lane * 4; d < Dk; d += 256) {
+    const float4 p = feature4(feat, nslices, slice_stride, b1, size_t(s) * Dk + d, d);
+#pragma unroll
+    for (int k = 0; k < MOQE_MAX_EXPERTS; ++k) {
+      if (k < K) {
+        const float4 w = *reinterpret_cast<const float4*>(w2 + size_t(k) * Dk + d);
+        acc[k] += w.x * p.x + w.y * p.y + w.z * p.z + w.w * p.w;
+      }
+    }
+  }
   float best = 0.f;
   int best_k = 0;
-  for (int k = 0; k < K; ++k) {
-    const float* wr = w2 + size_t(k) * Dk;
-    float acc = 0.f;
-    for (int d = lane * 4; d < Dk; d += 256) {
-      const float4 p = feature4(feat, nslices, slice_stride, b1, size_t(s) * Dk + d, d);
-      const float4 w = *reinterpret_cast<const float4*>(wr + d);
-      acc += w.x * p.x + w.y * p.y + w.z * p.z + w.w * p.w;
+#pragma unroll
+  for (int k = 0; k < MOQE_MAX_EXPERTS; ++k) {
+    if (k < K) {
+      const float z = wave_sum(acc[k]) + (b2 ? b2[k] : 0.f);
+      if (logits && lane == 0) logits[size_t(s) * K + k] = z;
+      if (k == 0 || z > best) { best = z; best_k = k; }   // strict >: ties keep the lowest index
     }
-    const float z = wave_sum(acc) + (b2 ? b2[k] : 0.f);
-    if (logits && lane == 0) logits[size_t(s) * K + k] = z;
-    if (k == 0 || z > best) { best = z; best_k = k; }   // strict >: ties keep the lowest index
   }
   if (lane == 0) expert_idx[s] = best_k;
 }

@@ -272,6 +272,27 @@ def balance_loss(logits: np.ndarray, expert_idx: np.ndarray) -> float:
     return float(N * np.sum(P * F))
 
 
+def balance_stats(logits: np.ndarray, expert_idx: np.ndarray, alpha: float):
+    """The load-balance quantities of Section 3.2 for one batch, from the router's logits and its dispatch.
+
+    P_i = mean over the batch of softmax(logits)_i, F_i = n_i / B with n_i the samples dispatched to
+    expert i (Eq. 2), L_bal = N * sum_i P_i F_i (Eq. 1), sigma = relative standard deviation of the
+    expert usage n_i (population standard deviation over its mean B / N), and the dynamic weight
+    alpha * (1 + sigma) that scales L_bal in the training loss.  Returns (P, F, L_bal, sigma, alpha_dyn).
+    """
+    z = np.asarray(logits, dtype=np.float64)
+    B, N = z.shape
+    e = np.exp(z - z.max(axis=1, keepdims=True))
+    p = e / e.sum(axis=1, keepdims=True)
+    P = p.mean(axis=0)
+    n = np.bincount(np.asarray(expert_idx), minlength=N).astype(np.float64)
+    F = n / B
+    l_bal = float(N * np.sum(P * F))
+    mean = B / N
+    sigma = float(np.sqrt(np.mean((n - mean) ** 2)) / mean)
+    return P, F, l_bal, sigma, float(alpha * (1.0 + sigma))
+
+
 # --------------------------------------------------------------------------------------
 # Expert layers
 # --------------------------------------------------------------------------------------

@@ -115,3 +115,30 @@ def test_balance_loss_closed_forms():
     logits = np.full((8, N), -1e3)
     logits[:, 2] = 1e3
     assert np.isclose(oc.balance_loss(logits, np.full(8, 2)), float(N))
+
+
+def test_balance_stats_closed_forms():
+    """Eq. (1)-(2) and the dynamic weight on cases with known values."""
+    N, B = 4, 12
+    # uniform probabilities, perfectly even dispatch: P = F = 1/N, L_bal = 1, sigma = 0, alpha_dyn = alpha
+    P, F, l, sig, a = oc.balance_stats(np.zeros((B, N)), np.arange(B) % N, 0.02)
+    assert np.allclose(P, 0.25) and np.allclose(F, 0.25)
+    assert np.isclose(l, 1.0) and sig == 0.0 and np.isclose(a, 0.02)
+    # everything dispatched to expert 1: n = (0, B, 0, 0); population std = mean * sqrt(N - 1)
+    P, F, l, sig, a = oc.balance_stats(np.zeros((B, N)), np.full(B, 1), 0.02)
+    assert np.allclose(F, [0, 1, 0, 0]) and np.isclose(l, N * 0.25)
+    assert np.isclose(sig, np.sqrt(N - 1)) and np.isclose(a, 0.02 * (1 + np.sqrt(3)))
+    # two-expert batch with hand-computed softmax: logits (0, ln 3) -> p = (1/4, 3/4)
+    z = np.array([[0.0, np.log(3.0)], [np.log(3.0), 0.0], [0.0, np.log(3.0)], [0.0, np.log(3.0)]])
+    P, F, l, sig, a = oc.balance_stats(z, np.array([1, 0, 1, 1]), 1.0)
+    assert np.allclose(P, [(0.25 * 3 + 0.75) / 4, (0.75 * 3 + 0.25) / 4])
+    assert np.allclose(F, [0.25, 0.75])
+    assert np.isclose(l, 2 * (0.375 * 0.25 + 0.625 * 0.75))
+    assert np.isclose(sig, 0.5) and np.isclose(a, 1.5)           # n = (1, 3): std 1, mean 2
+    # agrees with the scalar form used elsewhere, and a constant added to a row changes nothing
+    rng = np.random.default_rng(5)
+    z = rng.standard_normal((33, 5))
+    idx = rng.integers(0, 5, 33)
+    assert np.isclose(oc.balance_stats(z, idx, 0.1)[2], oc.balance_loss(z, idx))
+    assert np.allclose(oc.balance_stats(z + 100.0, idx, 0.1)[0], oc.balance_stats(z, idx, 0.1)[0])
+    assert np.isclose(oc.balance_stats(z, idx, 0.1)[0].sum(), 1.0)

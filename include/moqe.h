@@ -146,6 +146,17 @@ int32_t moqe_bucket(const int32_t* expert_idx, int32_t S, int32_t K,
                     int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                     void* stream);
 
+/* Load-balance statistics of one routed batch (Section 3.2, Eq. 1-2), from the logits that
+ * moqe_route wrote and the counts of moqe_bucket:
+ *   P_i = mean over the S samples of softmax(logits[s, :])_i,   F_i = counts[i] / S,
+ *   L_bal = K * sum_i P_i F_i,   sigma = std(counts) / mean(counts) (population std, mean = S / K),
+ *   alpha_dyn = alpha * (1 + sigma), the weight that multiplies L_bal in the training loss.
+ * logits: device float [S, K]; counts: device int32 [K]; out: device float [2K + 3] =
+ * P[0..K), F[0..K), L_bal, sigma, alpha_dyn.  fp32 arithmetic, fixed summation order
+ * (deterministic).  S >= 1, 1 <= K <= MOQE_MAX_EXPERTS.  One small kernel on `stream`. */
+int32_t moqe_balance_stats(const float* logits, const int32_t* counts, int32_t S, int32_t K,
+                           float alpha, float* out, void* stream);
+
 /* ---- expert weights ----------------------------------------------------------------- */
 
 /* Round-to-nearest quantization of a device fp32 matrix w [n, k] into the canonical layout

@@ -63,6 +63,7 @@ def _load() -> C.CDLL:
         "moqe_route_workspace_bytes": (sz, [i32, i32, C.POINTER(_Router)]),
         "moqe_route": (i32, [vp, i32, i32, C.POINTER(_Router), vp, vp, vp, sz, vp]),
         "moqe_bucket": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
+        "moqe_balance_stats": (i32, [vp, vp, i32, i32, C.c_float, vp, vp]),
         "moqe_quantize_rtn": (i32, [vp, C.c_float, C.POINTER(_QMat), vp]),
         "moqe_packed_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
         "moqe_pack_qmat": (i32, [C.POINTER(_QMat), vp, sz, vp]),
@@ -83,7 +84,7 @@ def _load() -> C.CDLL:
 
 lib = _load()
 EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
-            "moqe_route", "moqe_bucket", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
+            "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
             "moqe_workspace_bytes", "moqe_forward", "moqe_profile_enable", "moqe_profile_read"]
 
@@ -209,6 +210,11 @@ def moqe_route(x: torch.Tensor, S: int, T: int, router: Router, expert_idx: torc
 def moqe_bucket(expert_idx: torch.Tensor, S: int, K: int, counts: Optional[torch.Tensor], offsets: torch.Tensor,
                 perm: Optional[torch.Tensor], inv_perm: Optional[torch.Tensor]) -> None:
     _check(lib.moqe_bucket(_ptr(expert_idx), S, K, _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _stream()))
+
+
+def moqe_balance_stats(logits: torch.Tensor, counts: torch.Tensor, S: int, K: int, alpha: float,
+                       out: torch.Tensor) -> None:
+    _check(lib.moqe_balance_stats(_ptr(logits), _ptr(counts), S, K, float(alpha), _ptr(out), _stream()))
 
 
 def moqe_quantize_rtn(w: torch.Tensor, clip: float, out: QMat) -> None:

@@ -220,6 +220,15 @@ int32_t moqe_bucket(const int32_t* expert_idx, int32_t S, int32_t K, int32_t* co
   return launch_bucket(expert_idx, S, K, counts, offsets, perm, inv_perm, static_cast<hipStream_t>(stream));
 }
 
+int32_t moqe_balance_stats(const float* logits, const int32_t* counts, int32_t S, int32_t K, float alpha, float* out,
+                           void* stream) {
+  if (K < 1 || K > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "moqe_balance_stats: K=%d outside [1, %d]", K, MOQE_MAX_EXPERTS);
+  if (S < 1) return set_error(MOQE_E_SHAPE, "moqe_balance_stats: S=%d", S);
+  if (!logits || !counts || !out) return set_error(MOQE_E_NULL, "moqe_balance_stats: logits, counts or out is NULL");
+  if (dry_run()) return MOQE_OK;
+  return launch_balance_stats(logits, counts, S, K, alpha, out, static_cast<hipStream_t>(stream));
+}
+
 // ---- expert weights ------------------------------------------------------------------------
 int32_t moqe_quantize_rtn(const float* w, float clip, const moqe_qmat* out, void* stream) {
   if (!w || !out) return set_error(MOQE_E_NULL, "moqe_quantize_rtn: w or out is NULL");

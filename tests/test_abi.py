@@ -54,6 +54,17 @@ def test_bucket_argument_errors(mq):
     assert lib.moqe_bucket(FAKE, 8, 4, None, FAKE, None, None, None) == 0
 
 
+def test_balance_stats_argument_errors(mq):
+    lib = mq.lib
+    assert lib.moqe_balance_stats(FAKE, FAKE, 8, 0, 0.02, FAKE, None) == -2
+    assert lib.moqe_balance_stats(FAKE, FAKE, 8, 17, 0.02, FAKE, None) == -2
+    assert lib.moqe_balance_stats(FAKE, FAKE, 0, 4, 0.02, FAKE, None) == -2
+    assert lib.moqe_balance_stats(None, FAKE, 8, 4, 0.02, FAKE, None) == -1
+    assert lib.moqe_balance_stats(FAKE, None, 8, 4, 0.02, FAKE, None) == -1
+    assert lib.moqe_balance_stats(FAKE, FAKE, 8, 4, 0.02, None, None) == -1
+    assert lib.moqe_balance_stats(FAKE, FAKE, 8, 4, 0.02, FAKE, None) == 0
+
+
 def test_packed_bytes_and_formats(mq):
     pb = mq.moqe_packed_bytes
     assert pb(256, 256, 8, 0, True) == 256 * 256 + 256 * 4

@@ -97,3 +97,60 @@ def test_bucket_degenerate_distributions():
     for _ in range(3):
         b = _bucket_gpu(e, 8)
         assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def _balance_gpu(logits, counts, alpha):
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    S, K = logits.shape
+    out = torch.full((2 * K + 3,), float("nan"), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_balance_stats(gb.to_dev(logits.astype(np.float32)), gb.to_dev(counts.astype(np.int32)), S, K, alpha, out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().astype(np.float64)
+    return o[:K], o[K:2 * K], o[2 * K], o[2 * K + 1], o[2 * K + 2]
+
+
+@pytest.mark.parametrize("S,K,seed", [(1, 1, 0), (64, 4, 1), (256, 3, 2), (5000, 16, 3), (300, 8, 4)])
+def test_balance_stats_match_oracle(S, K, seed):
+    """P_i, F_i, L_bal (Eq. 1-2), the usage spread and the dynamic weight, fp32 on the GPU against fp64."""
+    rng = np.random.default_rng(seed)
+    logits = (rng.standard_normal((S, K)) * 3.0).astype(np.float32)
+    if seed == 4:
+        logits[:, 2] += 50.0                       # everything to one expert: the degenerate dispatch
+    idx = np.argmax(logits, axis=1)
+    counts = np.bincount(idx, minlength=K)
+    ref = oc.balance_stats(logits, idx, 0.02)
+    got = _balance_gpu(logits, counts, 0.02)
+    assert np.allclose(got[0], ref[0], rtol=2e-5, atol=1e-7)
+    assert np.array_equal(got[1].astype(np.float32), (counts / S).astype(np.float32))
+    for g, r in zip(got[2:], ref[2:]):
+        assert np.isclose(g, r, rtol=2e-5, atol=1e-7)
+    again = _balance_gpu(logits, counts, 0.02)
+    assert all(np.array_equal(a, b) for a, b in zip(got, again))        # fixed summation order
+
+
+def test_balance_stats_on_routed_workload():
+    """From the logits and counts that the router and the bucket step leave on the device."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    cfg = wl.get_config("qwen_mlp_skew")
+    bits = wl.make_activations(cfg)
+    router = ob.make_router(cfg)
+    idx_ref, logits_ref, _ = oc.route(oc.bf16_bits_to_f64(bits), router)
+    x = gb.bf16_dev(bits)
+    idx = torch.empty(cfg.S, dtype=torch.int32, device=gb.DEV)
+    logits = torch.empty((cfg.S, cfg.K), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_route(x, cfg.S, cfg.T, gb.router_dev(router, cfg.K), idx, logits)
+    counts = torch.empty(cfg.K, dtype=torch.int32, device=gb.DEV)
+    offsets = torch.empty(cfg.K + 1, dtype=torch.int32, device=gb.DEV)
+    mq.moqe_bucket(idx, cfg.S, cfg.K, counts, offsets, None, None)
+    out = torch.empty(2 * cfg.K + 3, dtype=torch.float32, device=gb.DEV)
+    mq.moqe_balance_stats(logits, counts, cfg.S, cfg.K, 0.02, out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy().astype(np.float64)
+    P, F, l, sig, a = oc.balance_stats(logits_ref, idx_ref, 0.02)
+    K = cfg.K
+    assert np.allclose(o[:K], P, rtol=1e-4) and np.allclose(o[K:2 * K], F)
+    assert np.isclose(o[2 * K], l, rtol=1e-4) and np.isclose(o[2 * K + 1], sig, rtol=1e-5)
+    assert np.isclose(o[2 * K + 2], a, rtol=1e-5)
+    assert F[0] > 0.5                               # the skewed workload: expert 0 takes most sequences

@@ -83,6 +83,9 @@ def _load() -> C.CDLL:
 
 
 lib = _load()
+SCATTER_OUTPUT = 1
+INPUT_IN_BUCKET_ORDER = 2
+
 EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
             "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
@@ -242,7 +245,7 @@ def moqe_grouped_qgemm_workspace_bytes(experts: Sequence[QMat], S: int, T: int) 
 
 
 def moqe_grouped_qgemm(a: torch.Tensor, offsets: torch.Tensor, perm: Optional[torch.Tensor], S: int, T: int,
-                       experts: Sequence[QMat], y: torch.Tensor, scatter: bool,
+                       experts: Sequence[QMat], y: torch.Tensor, scatter: int,
                        workspace: Optional[torch.Tensor] = None) -> None:
     arr = (_QMat * len(experts))(*[m.c() for m in experts])
     if workspace is None:

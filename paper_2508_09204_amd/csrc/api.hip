@@ -293,12 +293,15 @@ int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t*
   if (S == 0) return MOQE_OK;
   if (!a || !offsets || !y) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: a, offsets or y is NULL");
   if (!aligned(a, 16) || !aligned(y, 16)) return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: a and y must be 16-byte aligned");
-  if (scatter && !perm) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: scatter needs perm");
+  if (scatter & ~(MOQE_SCATTER_OUTPUT | MOQE_INPUT_IN_BUCKET_ORDER))
+    return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: unknown bits in scatter=%d", scatter);
+  if ((scatter & MOQE_SCATTER_OUTPUT) && !perm) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: scatter needs perm");
   const size_t need = a8_bytes(gp.any_a8, S * T, experts[0].k);
   if (need && (!workspace || !aligned(workspace, 256) || workspace_bytes < need))
     return set_error(MOQE_E_WORKSPACE, "moqe_grouped_qgemm: workspace needs %zu bytes, 256-byte aligned", need);
   if (dry_run()) return MOQE_OK;
-  return run_grouped(a, offsets, perm, scatter ? perm : nullptr, S, T, experts, nullptr, K, gp, y,
+  return run_grouped(a, offsets, (scatter & MOQE_INPUT_IN_BUCKET_ORDER) ? nullptr : perm,
+                     (scatter & MOQE_SCATTER_OUTPUT) ? perm : nullptr, S, T, experts, nullptr, K, gp, y,
                      static_cast<uint8_t*>(workspace), static_cast<hipStream_t>(stream));
 }
 

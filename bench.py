@@ -220,6 +220,13 @@ def main():
         achieved = dom_flops / (kern_us * 1e-6) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+        # the same launch against the HBM roofline: weights once, activations in (bf16), results out
+        k_in = dom_mats[0][1]
+        n_out_dom = dom_mats[0][0]
+        io_bytes = cfg.M * k_in * 2 + cfg.M * n_out_dom * (2 if is_mlp else 4)
+        roof["hbm_view"] = {"algorithmic_bytes_per_launch": dom_bytes + io_bytes,
+                            "achieved_gbs": (dom_bytes + io_bytes) / (kern_us * 1e-6) / 1e9,
+                            "frac_of_8tbs": (dom_bytes + io_bytes) / (kern_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
     roof["kernel"] = ("k_qgemm_tile" if tiled else "k_qgemm_stream") + ("<gate/up + SiLU>" if is_mlp else "<plain>")
     roof["kernel_us"] = kern_us
     roof["launches_timed"] = launches

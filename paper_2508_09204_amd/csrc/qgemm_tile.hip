@@ -2,11 +2,12 @@
 //
 // Each sample is processed by its selected expert only (MoQE Section 3.1); when an expert's bucket
 // holds hundreds of rows the work is a dense contraction and belongs on the matrix cores.  A
-// work-group of 8 waves (2 along the rows x 4 along the weight rows) owns 128 bucket rows x 256
-// weight rows of one expert (for the SiLU-gated pair: 128 gate rows and the 128 up rows of the
-// same features, so the gate meets its up value in registers); a wave owns 64 x 64.
+// work-group of 4 waves owns 64 bucket rows x 256 weight rows of one expert (for the SiLU-gated
+// pair: 128 gate rows and the 128 up rows of the same features, so the gate meets its up value in
+// registers); a wave owns 64 x 64.  Two work-groups share a CU (256 registers per wave) and meet at
+// their barriers independently, so one computes while the other waits.
 //
-//  * Activations: the 128 x 128 tile of a k-step is gathered through the permutation into
+//  * Activations: the 64 x 128 tile of a k-step is gathered through the permutation into
 //    registers and written to LDS (rows of 256 bytes, 16-byte units XOR-swizzled by the row so
 //    that the 16-byte-per-lane operand reads are free of bank conflicts), double-buffered, one
 //    barrier per k-step.
@@ -24,8 +25,8 @@
 
 namespace moqe {
 
-constexpr int TBM = 128;                 // bucket rows per work-group tile
-constexpr int TWM = 2, TWN = 4;          // waves along rows / weight rows
+constexpr int TBM = 64;                  // bucket rows per work-group tile
+constexpr int TWM = 1, TWN = 4;          // waves along rows / weight rows
 constexpr int TWAVES = TWM * TWN;
 constexpr int TMB = 4, TNB = 4;          // 16 x 16 blocks per wave: 64 rows x 64 weight rows
 constexpr int TBN = TWN * TNB * 16;      // 256 weight rows per work-group tile
@@ -47,7 +48,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // uniform: keeps tile addresses scalar
   const int lr = lane & 15, lq = lane >> 4;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave / TWN, wn = wave % TWN;
   const int KT = ga.k >> 7, NT = ga.n >> 4;
   const int T = ga.T;
   const int off_e = ga.offsets[e];
@@ -318,11 +319,11 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
 }
 
 // Work-group id -> tile.  The hardware deals consecutive work-group ids round-robin to the 8 XCDs,
-// each with its own L2, so the 32 work-groups that are resident on one XCD at a time are the ids
+// each with its own L2, so the 64 work-groups that are resident on one XCD at a time are the ids
 // x, x + 8, x + 16, ...; they are made a patch of PATCH_M row tiles x PATCH_N weight tiles, which
 // run side by side over k and share their activation and weight tiles in that L2.  Consecutive
 // patches of an XCD, and the patches of the 8 XCDs at one time, walk along the weight rows first.
-constexpr int PATCH_M = 4, PATCH_N = 8;
+constexpr int PATCH_M = 8, PATCH_N = 8;
 
 template <bool GATEUP>
 __global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga) {
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga
   const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
   const int patch = (j / (PATCH_M * PATCH_N)) * 8 + xcd, q = j % (PATCH_M * PATCH_N);
   const int ntile = (patch % patches_n) * PATCH_N + q / PATCH_M;
-  // which expert and which 128-row tile of its bucket: `slot` counts row tiles over all experts
+  // which expert and which row tile of its bucket: `slot` counts row tiles over all experts
   int slot = (patch / patches_n) * PATCH_M + q % PATCH_M, e = -1, m0 = 0;
   for (int i = 0; i < ga.n_experts; ++i) {
     const int rows = (ga.offsets[i + 1] - ga.offsets[i]) * ga.T;
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga
 
 int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
   const int M = ga.S * ga.T;
-  const int row_tiles = (M + TBM - 1) / TBM + ga.n_experts;      // upper bound on sum_e ceil(M_e / 128)
+  const int row_tiles = (M + TBM - 1) / TBM + ga.n_experts;      // upper bound on sum_e ceil(M_e / TBM)
   const int n_tiles = gateup ? (ga.n + TBN / 2 - 1) / (TBN / 2) : (ga.n + TBN - 1) / TBN;
   const long patches = long((row_tiles + PATCH_M - 1) / PATCH_M) * ((n_tiles + PATCH_N - 1) / PATCH_N);
   const long grid = (patches + 7) / 8 * 8 * (PATCH_M * PATCH_N);

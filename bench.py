@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
 # HBM traffic of the dominant kernel from hardware counters (two rocprofv3 --pmc runs, FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB device copy; summary and
-# commands under profiles/).  Valid only for the kernel sources it was taken with: the entry carries
+# commands are kept with the profile summaries in the repository).  Valid only for the kernel sources it was taken with: the entry carries
 # their hash and is ignored (traffic = null) once they have changed.
 KERNEL_SOURCES = ("qgemm_stream.hip", "qgemm_device.h", "moqe_internal.h")
 MEASURED_TRAFFIC = {
@@ -140,7 +140,7 @@ def main():
                          "traffic, for scaling hardware counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (samples would shard across GPUs with no collective); "
+        print("bench.py: this library runs on ONE GPU (samples would shard across GPUs with no collective); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -35,7 +35,8 @@ def test_route_full_configs(name):
     assert np.max(np.abs(logits - ref_logits)) < 0.1 * margin.min()
 
 
-@pytest.mark.parametrize("S,T,D,H,K", [(1, 1, 128, 0, 1), (3, 7, 136, 12, 5), (70, 33, 264, 20, 16), (5, 200, 128, 8, 2)])
+@pytest.mark.parametrize("S,T,D,H,K", [(1, 1, 128, 0, 1), (3, 7, 136, 12, 5), (70, 33, 264, 20, 16), (5, 200, 128, 8, 2),
+                                       (3000, 1, 128, 16, 8), (2500, 2, 256, 0, 3)])
 def test_route_ragged_shapes(S, T, D, H, K):
     rng = np.random.default_rng(S * 100 + T)
     bits = wl.f32_to_bf16_bits(rng.standard_normal((S, T, D)).astype(np.float32))
@@ -76,7 +77,7 @@ def _bucket_gpu(e, K):
 
 
 @pytest.mark.parametrize("S,K,seed", [(1, 1, 0), (1, 4, 1), (64, 4, 2), (63, 3, 3), (65, 3, 4), (256, 8, 5), (257, 8, 6),
-                                      (1000, 16, 7), (5000, 5, 8), (0, 4, 9)])
+                                      (1000, 16, 7), (5000, 5, 8), (0, 4, 9), (200000, 16, 10)])
 def test_bucket_matches_oracle_bit_exact(S, K, seed):
     e = np.random.default_rng(seed).integers(0, K, S)
     ref = oc.bucket(e, K)

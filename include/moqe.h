@@ -216,6 +216,29 @@ size_t  moqe_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T);
 int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y,
                      const moqe_aux* aux, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- on-demand residency of expert weights ------------------------------------------- */
+
+/* The serving mode of Section 4.4 / the appendix on memory use: only the experts in use sit in
+ * device memory, the others wait in host memory and are copied in when the router switches to
+ * them.  A cache owns `slots` equal device buffers (each as large as the largest blob, allocated at
+ * creation) and keeps the most recently used of K blobs (a blob = one packed matrix, or any
+ * concatenation the caller defines).
+ *   host_blobs[e], bytes[e]: host memory of blob e; it must stay valid for the cache's lifetime.
+ *                            Pinned host memory makes the copies asynchronous.
+ * moqe_cache_acquire makes the n <= slots distinct blobs want[0..n) resident and writes their device
+ * addresses to dev_ptrs[0..n) (host array).  Missing blobs replace the least recently used ones and
+ * are copied on `stream`: work enqueued on that stream afterwards sees the new contents, work
+ * enqueued before still sees the old ones, so use the returned addresses on the same stream.
+ * *copied (may be NULL) receives the number of copies issued.  Not thread-safe per cache.
+ * moqe_cache_stats: totals since creation. */
+typedef struct moqe_expert_cache moqe_expert_cache;
+int32_t moqe_cache_create(moqe_expert_cache** out, const void* const* host_blobs, const size_t* bytes,
+                          int32_t K, int32_t slots);
+int32_t moqe_cache_destroy(moqe_expert_cache* cache);
+int32_t moqe_cache_acquire(moqe_expert_cache* cache, const int32_t* want, int32_t n, void** dev_ptrs,
+                           int32_t* copied, void* stream);
+int32_t moqe_cache_stats(const moqe_expert_cache* cache, uint64_t* copies, uint64_t* copied_bytes);
+
 /* ---- timing ------------------------------------------------------------------------- */
 
 /* Per-kernel timing with HIP events recorded on the stream the kernels are launched on.

@@ -72,6 +72,10 @@ def _load() -> C.CDLL:
         "moqe_grouped_qgemm": (i32, [vp, vp, vp, i32, i32, C.POINTER(_QMat), i32, vp, i32, vp, sz, vp]),
         "moqe_workspace_bytes": (sz, [C.POINTER(_Block), i32, i32]),
         "moqe_forward": (i32, [C.POINTER(_Block), vp, i32, i32, vp, C.POINTER(_Aux), vp, sz, vp]),
+        "moqe_cache_create": (i32, [C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32]),
+        "moqe_cache_destroy": (i32, [vp]),
+        "moqe_cache_acquire": (i32, [vp, C.POINTER(i32), i32, C.POINTER(vp), C.POINTER(i32), vp]),
+        "moqe_cache_stats": (i32, [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
         "moqe_profile_enable": (i32, [i32]),
         "moqe_profile_read": (i32, [i32, C.POINTER(i32), C.POINTER(C.c_double)]),
     }
@@ -89,7 +93,8 @@ INPUT_IN_BUCKET_ORDER = 2
 EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
             "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
-            "moqe_workspace_bytes", "moqe_forward", "moqe_profile_enable", "moqe_profile_read"]
+            "moqe_workspace_bytes", "moqe_forward", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
+            "moqe_cache_stats", "moqe_profile_enable", "moqe_profile_read"]
 
 
 def _check(rc: int) -> None:
@@ -97,8 +102,11 @@ def _check(rc: int) -> None:
         raise MoqeError(rc, lib.moqe_last_error_string().decode())
 
 
-def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
-    return None if t is None else t.data_ptr()
+def _ptr(t) -> Optional[int]:
+    """Address of a tensor's storage; a plain int (an address handed out by the library) passes through."""
+    if t is None:
+        return None
+    return t if isinstance(t, int) else t.data_ptr()
 
 
 def _stream() -> Optional[int]:
@@ -252,6 +260,37 @@ def moqe_grouped_qgemm(a: torch.Tensor, offsets: torch.Tensor, perm: Optional[to
         workspace = _workspace(lib.moqe_grouped_qgemm_workspace_bytes(arr, len(experts), S, T), a.device)
     _check(lib.moqe_grouped_qgemm(_ptr(a), _ptr(offsets), _ptr(perm), S, T, arr, len(experts), _ptr(y),
                                   int(scatter), _ptr(workspace), workspace.numel(), _stream()))
+
+
+def moqe_cache_create(host_blobs: Sequence[torch.Tensor], slots: int) -> int:
+    """host_blobs: CPU uint8 tensors (pinned for asynchronous copies); the caller keeps them alive.
+    Returns the cache handle."""
+    K = len(host_blobs)
+    ptrs = (C.c_void_p * K)(*[t.data_ptr() for t in host_blobs])
+    sizes = (C.c_size_t * K)(*[t.numel() * t.element_size() for t in host_blobs])
+    handle = C.c_void_p()
+    _check(lib.moqe_cache_create(C.byref(handle), ptrs, sizes, K, slots))
+    return handle.value
+
+
+def moqe_cache_destroy(handle: int) -> None:
+    _check(lib.moqe_cache_destroy(handle))
+
+
+def moqe_cache_acquire(handle: int, want: Sequence[int]):
+    """Returns (device addresses of the wanted blobs, number of host->device copies issued)."""
+    n = len(want)
+    w = (C.c_int32 * n)(*want)
+    out = (C.c_void_p * n)()
+    copied = C.c_int32(0)
+    _check(lib.moqe_cache_acquire(handle, w, n, out, C.byref(copied), _stream()))
+    return [int(out[i]) for i in range(n)], copied.value
+
+
+def moqe_cache_stats(handle: int):
+    a, b = C.c_uint64(0), C.c_uint64(0)
+    _check(lib.moqe_cache_stats(handle, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def moqe_workspace_bytes(blk: Block, S: int, T: int) -> int:

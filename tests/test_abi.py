@@ -65,6 +65,27 @@ def test_balance_stats_argument_errors(mq):
     assert lib.moqe_balance_stats(FAKE, FAKE, 8, 4, 0.02, FAKE, None) == 0
 
 
+def test_cache_argument_errors(mq):
+    import ctypes as C
+    lib = mq.lib
+    handle = C.c_void_p()
+    ptrs = (C.c_void_p * 2)(FAKE, FAKE)
+    sizes = (C.c_size_t * 2)(1024, 2048)
+    assert lib.moqe_cache_create(C.byref(handle), ptrs, sizes, 0, 1) == -2
+    assert lib.moqe_cache_create(C.byref(handle), ptrs, sizes, 2, 3) == -2          # more slots than blobs
+    assert lib.moqe_cache_create(C.byref(handle), ptrs, sizes, 2, 0) == -2
+    assert lib.moqe_cache_create(None, ptrs, sizes, 2, 1) == -1
+    empty = (C.c_size_t * 2)(1024, 0)
+    assert lib.moqe_cache_create(C.byref(handle), ptrs, empty, 2, 1) == -1
+    assert lib.moqe_cache_create(C.byref(handle), ptrs, sizes, 2, 1) == 0           # dry run: nothing is allocated
+    assert handle.value is None
+    want = (C.c_int32 * 1)(0)
+    out = (C.c_void_p * 1)()
+    assert lib.moqe_cache_acquire(None, want, 1, out, None, None) == -1
+    assert lib.moqe_cache_stats(None, None, None) == -1
+    assert lib.moqe_cache_destroy(None) == 0
+
+
 def test_packed_bytes_and_formats(mq):
     pb = mq.moqe_packed_bytes
     assert pb(256, 256, 8, 0, True) == 256 * 256 + 256 * 4

@@ -182,3 +182,33 @@ def test_forward_large_workloads_sampled_rows(name):
             rms = float(np.sqrt(np.mean(y_e2e * y_e2e)))
             bound = 2e-3 * np.maximum(np.abs(y_e2e), rms) + flip_allowance
             assert np.all(np.abs(y[s][rows] - y_e2e) <= bound), (s, e)
+
+
+def test_forward_replays_from_a_captured_graph():
+    """moqe_forward enqueues only kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so after one eager call it can be captured into a graph; every replay, with eager
+    work and synchronisations in between, must reproduce the eager result bit for bit."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    kw = dict(SMALL["mlp_prefill"])
+    cfg = wl.scaled(wl.get_config(kw.pop("base")), **kw)
+    blk = ob.make_block(cfg)
+    bits, _ = ob.activations_f64(cfg)
+    dblk = gb.block_dev(blk)
+    x = gb.bf16_dev(bits.reshape(cfg.M, cfg.D))
+    y_eager = torch.empty((cfg.M, cfg.D), dtype=torch.float32, device=gb.DEV)
+    y_graph = torch.full((cfg.M, cfg.D), float("nan"), dtype=torch.float32, device=gb.DEV)
+    call_e = mq.ForwardCall(dblk, x, cfg.S, cfg.T, y_eager, mq.Aux())
+    call_g = mq.ForwardCall(dblk, x, cfg.S, cfg.T, y_graph, mq.Aux())
+    call_e(torch.cuda.current_stream().cuda_stream)                   # also does the one-time kernel set-up
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call_g(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        y_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        call_e(torch.cuda.current_stream().cuda_stream)               # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), rep

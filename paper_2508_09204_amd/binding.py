@@ -119,8 +119,9 @@ def _stream() -> Optional[int]:
 @dataclass
 class QMat:
     """A quantized matrix on the device.  Canonical: qdata int8/uint8 [n,k], scale, zero.
-    Packed: qdata is the uint8 blob from moqe_pack_qmat."""
-    qdata: torch.Tensor
+    Packed: qdata is the uint8 blob from moqe_pack_qmat, or its device address as an int (as handed
+    out by moqe_cache_acquire)."""
+    qdata: object
     scale: Optional[torch.Tensor]
     zero: Optional[torch.Tensor]
     n: int

@@ -233,6 +233,14 @@ def route(x: np.ndarray, r: Router) -> Tuple[np.ndarray, np.ndarray, np.ndarray]
     return idx, logits, margin
 
 
+def route_ragged(xs: Sequence[np.ndarray], r: Router) -> Tuple[np.ndarray, np.ndarray]:
+    """Samples of different lengths: xs[s] fp64 [T_s, D], T_s >= 1.  Each sample's feature is the mean
+    over its own rows; everything else as in route().  Returns (expert index int32 [S], logits [S, K])."""
+    p = np.stack([np.asarray(x, dtype=np.float64).sum(axis=0) / x.shape[0] for x in xs])
+    logits = router_logits(p, r)
+    return argmax_first(logits), logits
+
+
 def bucket(expert_idx: Sequence[int], K: int):
     """Dispatch counts and the stable permutation that groups samples by expert.
 
@@ -388,6 +396,15 @@ def expert_forward(blk: Block, e: int, xs: np.ndarray) -> np.ndarray:
         img = xs.reshape(blk.img_h, blk.img_w, blk.cin)
         return conv3x3(img, blk.w0[e], blk.cin).reshape(blk.img_h * blk.img_w, -1)
     raise ValueError("unknown block kind")
+
+
+def forward_ragged(blk: Block, xs: Sequence[np.ndarray]):
+    """y_s = f_{r(x_s)}(x_s) for samples of different lengths (LINEAR and SILU_MLP blocks): xs[s] fp64
+    [T_s, D] holding bfloat16 values.  Returns (list of Y_s fp64 [T_s, N], expert index, logits)."""
+    if blk.kind == KIND_CONV3X3:
+        raise ValueError("images have a fixed number of pixels")
+    idx, logits = route_ragged(xs, blk.router)
+    return [expert_forward(blk, int(idx[s]), np.asarray(xs[s], dtype=np.float64)) for s in range(len(xs))], idx, logits
 
 
 def forward(blk: Block, x: np.ndarray, expert_idx: Optional[np.ndarray] = None,

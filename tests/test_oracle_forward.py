@@ -242,3 +242,37 @@ def test_routing_accuracy_against_itself_is_one():
     _, x = ob.activations_f64(cfg)
     idx, _, _ = oc.route(x, blk.router)
     assert np.mean(idx == oc.forward(blk, x)[1]) == 1.0
+
+
+def test_ragged_forward_reduces_to_the_uniform_one_and_is_per_sample():
+    """Samples of different lengths: equal lengths give the uniform forward; a sample's result depends on
+    nothing but its own rows (any other sample may change or vanish); a sample is routed by the mean of
+    ITS rows (appending rows that change the mean can change the expert, appending copies cannot)."""
+    rng = np.random.default_rng(9)
+    D, F, K = 128, 256, 3
+    fp = {n: (rng.standard_normal(sh) * 0.05).astype(np.float32) for n, sh in
+          (("gate", (F, D)), ("up", (F, D)), ("down", (D, F)))}
+    specs = [(8, 0, True, 1.0, 0), (4, 64, False, 1.0, 0), (3, 64, False, 0.9, 0)]
+    router = oc.Router(None, None, (rng.standard_normal((K, D)) * 0.5).astype(np.float32), None)
+    blk = oc.Block(oc.KIND_SILU_MLP, router, [oc.quantize(fp["gate"], *sp) for sp in specs],
+                   [oc.quantize(fp["up"], *sp) for sp in specs], [oc.quantize(fp["down"], *sp) for sp in specs])
+    x = oc.bf16_round(rng.standard_normal((5, 4, D)))
+    y_u, idx_u, log_u = oc.forward(blk, x)
+    ys, idx_r, log_r = oc.forward_ragged(blk, [x[s] for s in range(5)])
+    assert np.array_equal(idx_u, idx_r) and np.allclose(log_u, log_r, rtol=0, atol=1e-12)
+    assert all(np.allclose(ys[s], y_u[s], rtol=1e-12, atol=1e-12) for s in range(5))
+    lens = [1, 7, 3, 4, 2]
+    xs = [oc.bf16_round(rng.standard_normal((t, D))) for t in lens]
+    ys, idx, logits = oc.forward_ragged(blk, xs)
+    assert [y.shape for y in ys] == [(t, D) for t in lens]
+    alone, idx1, _ = oc.forward_ragged(blk, [xs[1]])
+    assert idx1[0] == idx[1] and np.allclose(alone[0], ys[1], rtol=1e-12, atol=1e-12)
+    # the feature is the mean: a sample followed by a copy of itself is routed alike, row results repeat
+    dup, idx2, log2 = oc.forward_ragged(blk, [np.concatenate([xs[2], xs[2]])])
+    assert idx2[0] == idx[2] and np.allclose(log2[0], logits[2], rtol=1e-12, atol=1e-12)
+    assert np.allclose(dup[0][:3], ys[2], rtol=1e-12, atol=1e-12) and np.allclose(dup[0][3:], ys[2], rtol=1e-12, atol=1e-12)
+    # one row per sample is the T = 1 case of the uniform path
+    single = [x[s, :1] for s in range(5)]
+    y1, idx_s, _ = oc.forward_ragged(blk, single)
+    y1u, idx_su, _ = oc.forward(blk, x[:, :1])
+    assert np.array_equal(idx_s, idx_su) and all(np.allclose(y1[s], y1u[s], rtol=1e-12, atol=1e-12) for s in range(5))

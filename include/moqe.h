@@ -216,6 +216,35 @@ size_t  moqe_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T);
 int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y,
                      const moqe_aux* aux, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- samples of different lengths ---------------------------------------------------- */
+
+/* The same path for samples that do not all have T rows (sequences of different lengths): x is device
+ * bf16 [M, d] with sample s in the rows cu_rows[s] .. cu_rows[s+1) (cu_rows: device int32 [S+1],
+ * cu_rows[0] = 0, cu_rows[S] = M, every sample has at least one row).  A sample's router feature is
+ * the mean over its own rows; routing is per sample as before (Section 3.1).
+ *
+ * moqe_route_ragged: as moqe_route.
+ * moqe_expand_rows: from the sample-level bucket result (offsets, perm of moqe_bucket) to rows:
+ *   slot_rows[j]   first bucket-order row of bucket slot j (device int32 [S+1], slot_rows[S] = M)
+ *   row_offsets[e] first bucket-order row of expert e      (device int32 [K+1])
+ *   row_perm[i]    source row of bucket-order row i         (device int32 [M])
+ *   so that moqe_grouped_qgemm(a, row_offsets, row_perm, S = M, T = 1, ...) runs the rows of every
+ *   sample through its expert.
+ * moqe_forward_ragged: route, bucket, expand, grouped GEMM(s), scatter; LINEAR and SILU_MLP blocks.
+ *   M is passed by the host (it sizes the launch); y: device float [M, n_out] in the caller's row
+ *   order; aux as in moqe_forward (aux->h, if given, is bf16 [M, F] in bucket-row order). */
+size_t  moqe_route_ragged_workspace_bytes(int32_t S, const moqe_router* r);
+int32_t moqe_route_ragged(const void* x, const int32_t* cu_rows, int32_t S, const moqe_router* r,
+                          int32_t* expert_idx, float* logits,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int32_t moqe_expand_rows(const int32_t* cu_rows, const int32_t* offsets, const int32_t* perm,
+                         int32_t S, int32_t K, int32_t* slot_rows, int32_t* row_offsets,
+                         int32_t* row_perm, void* stream);
+size_t  moqe_workspace_bytes_ragged(const moqe_block* blk, int32_t S, int32_t M);
+int32_t moqe_forward_ragged(const moqe_block* blk, const void* x, const int32_t* cu_rows, int32_t S,
+                            int32_t M, void* y, const moqe_aux* aux,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- on-demand residency of expert weights ------------------------------------------- */
 
 /* The serving mode of Section 4.4 / the appendix on memory use: only the experts in use sit in

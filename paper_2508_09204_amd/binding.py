@@ -64,6 +64,11 @@ def _load() -> C.CDLL:
         "moqe_route": (i32, [vp, i32, i32, C.POINTER(_Router), vp, vp, vp, sz, vp]),
         "moqe_bucket": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
         "moqe_balance_stats": (i32, [vp, vp, i32, i32, C.c_float, vp, vp]),
+        "moqe_route_ragged_workspace_bytes": (sz, [i32, C.POINTER(_Router)]),
+        "moqe_route_ragged": (i32, [vp, vp, i32, C.POINTER(_Router), vp, vp, vp, sz, vp]),
+        "moqe_expand_rows": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
+        "moqe_workspace_bytes_ragged": (sz, [C.POINTER(_Block), i32, i32]),
+        "moqe_forward_ragged": (i32, [C.POINTER(_Block), vp, vp, i32, i32, vp, C.POINTER(_Aux), vp, sz, vp]),
         "moqe_quantize_rtn": (i32, [vp, C.c_float, C.POINTER(_QMat), vp]),
         "moqe_packed_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
         "moqe_pack_qmat": (i32, [C.POINTER(_QMat), vp, sz, vp]),
@@ -91,7 +96,8 @@ SCATTER_OUTPUT = 1
 INPUT_IN_BUCKET_ORDER = 2
 
 EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
-            "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
+            "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",
+            "moqe_expand_rows", "moqe_workspace_bytes_ragged", "moqe_forward_ragged", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
             "moqe_workspace_bytes", "moqe_forward", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
             "moqe_cache_stats", "moqe_profile_enable", "moqe_profile_read"]
@@ -307,6 +313,41 @@ def moqe_forward(blk: Block, x: torch.Tensor, S: int, T: int, y: torch.Tensor, a
     a = aux.c() if aux is not None else None
     _check(lib.moqe_forward(C.byref(b), _ptr(x), S, T, _ptr(y), C.byref(a) if a is not None else None,
                             _ptr(workspace), workspace.numel(), _stream()))
+
+
+def moqe_route_ragged_workspace_bytes(S: int, router: Router) -> int:
+    r = router.c()
+    return lib.moqe_route_ragged_workspace_bytes(S, C.byref(r))
+
+
+def moqe_route_ragged(x: torch.Tensor, cu_rows: torch.Tensor, S: int, router: Router, expert_idx: torch.Tensor,
+                      logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    r = router.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_route_ragged_workspace_bytes(S, C.byref(r)), x.device)
+    _check(lib.moqe_route_ragged(_ptr(x), _ptr(cu_rows), S, C.byref(r), _ptr(expert_idx), _ptr(logits), _ptr(workspace),
+                                 workspace.numel(), _stream()))
+
+
+def moqe_expand_rows(cu_rows: torch.Tensor, offsets: torch.Tensor, perm: Optional[torch.Tensor], S: int, K: int,
+                     slot_rows: torch.Tensor, row_offsets: torch.Tensor, row_perm: Optional[torch.Tensor]) -> None:
+    _check(lib.moqe_expand_rows(_ptr(cu_rows), _ptr(offsets), _ptr(perm), S, K, _ptr(slot_rows), _ptr(row_offsets),
+                                _ptr(row_perm), _stream()))
+
+
+def moqe_workspace_bytes_ragged(blk: Block, S: int, M: int) -> int:
+    b = blk.c()
+    return lib.moqe_workspace_bytes_ragged(C.byref(b), S, M)
+
+
+def moqe_forward_ragged(blk: Block, x: torch.Tensor, cu_rows: torch.Tensor, S: int, M: int, y: torch.Tensor,
+                        aux: Optional[Aux] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    b = blk.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_workspace_bytes_ragged(C.byref(b), S, M), x.device)
+    a = aux.c() if aux is not None else None
+    _check(lib.moqe_forward_ragged(C.byref(b), _ptr(x), _ptr(cu_rows), S, M, _ptr(y), C.byref(a) if a is not None else None,
+                                   _ptr(workspace), workspace.numel(), _stream()))
 
 
 def moqe_profile_enable(kind_mask: int) -> None:

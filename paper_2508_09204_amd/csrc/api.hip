@@ -220,6 +220,37 @@ int32_t moqe_bucket(const int32_t* expert_idx, int32_t S, int32_t K, int32_t* co
   return launch_bucket(expert_idx, S, K, counts, offsets, perm, inv_perm, static_cast<hipStream_t>(stream));
 }
 
+size_t moqe_route_ragged_workspace_bytes(int32_t S, const moqe_router* r) {
+  if (!r || S < 0 || r->d <= 0) return 0;
+  return route_ws_bytes(S, 2, *r);
+}
+
+int32_t moqe_route_ragged(const void* x, const int32_t* cu_rows, int32_t S, const moqe_router* r, int32_t* expert_idx,
+                          float* logits, void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t rc = check_router(r, "moqe_route_ragged");
+  if (rc) return rc;
+  if (S < 0) return set_error(MOQE_E_SHAPE, "moqe_route_ragged: S=%d", S);
+  if (S == 0) return MOQE_OK;
+  if (!x || !cu_rows || !expert_idx) return set_error(MOQE_E_NULL, "moqe_route_ragged: x, cu_rows or expert_idx is NULL");
+  if (!aligned(x, 16)) return set_error(MOQE_E_SHAPE, "moqe_route_ragged: x must be 16-byte aligned");
+  if (r->d % 8) return set_error(MOQE_E_SHAPE, "moqe_route_ragged: d=%d must be a multiple of 8", r->d);
+  const size_t need = route_ws_bytes(S, 2, *r);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < need)
+    return set_error(MOQE_E_WORKSPACE, "moqe_route_ragged: workspace needs %zu bytes, 256-byte aligned", need);
+  if (dry_run()) return MOQE_OK;
+  return launch_route_ragged(x, cu_rows, S, *r, expert_idx, logits, workspace, static_cast<hipStream_t>(stream));
+}
+
+int32_t moqe_expand_rows(const int32_t* cu_rows, const int32_t* offsets, const int32_t* perm, int32_t S, int32_t K,
+                         int32_t* slot_rows, int32_t* row_offsets, int32_t* row_perm, void* stream) {
+  if (K < 1 || K > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "moqe_expand_rows: K=%d outside [1, %d]", K, MOQE_MAX_EXPERTS);
+  if (S < 0) return set_error(MOQE_E_SHAPE, "moqe_expand_rows: S=%d", S);
+  if (!cu_rows || !offsets || !slot_rows || !row_offsets) return set_error(MOQE_E_NULL, "moqe_expand_rows: NULL argument");
+  if (S > 0 && (!perm || !row_perm)) return set_error(MOQE_E_NULL, "moqe_expand_rows: perm or row_perm is NULL");
+  if (dry_run()) return MOQE_OK;
+  return launch_expand_rows(cu_rows, offsets, perm, S, K, slot_rows, row_offsets, row_perm, static_cast<hipStream_t>(stream));
+}
+
 int32_t moqe_balance_stats(const float* logits, const int32_t* counts, int32_t S, int32_t K, float alpha, float* out,
                            void* stream) {
   if (K < 1 || K > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "moqe_balance_stats: K=%d outside [1, %d]", K, MOQE_MAX_EXPERTS);
@@ -422,6 +453,114 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
   rc = launch_im2col(x, S, blk->img_h, blk->img_w, blk->cin, col, st);
   if (rc) return rc;
   return run_grouped(col, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st);
+}
+
+// ---- the whole block, samples of different lengths -------------------------------------------
+namespace {
+struct RaggedLayout {
+  size_t route, idx, logits, counts, offsets, perm, inv_perm, slot_rows, row_offsets, row_perm, h, a8, total;
+};
+
+int32_t ragged_layout(const moqe_block* b, int S, long long M, RaggedLayout* L, GroupedPlan* gp0, GroupedPlan* gp2) {
+  if (!b) return set_error(MOQE_E_NULL, "moqe_forward_ragged: block is NULL");
+  int32_t rc = check_router(&b->router, "moqe_forward_ragged");
+  if (rc) return rc;
+  const int K = b->n_experts;
+  if (K < 1 || K > MOQE_MAX_EXPERTS || K != b->router.n_experts)
+    return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: n_experts=%d (router %d)", K, b->router.n_experts);
+  if (b->kind != MOQE_KIND_LINEAR && b->kind != MOQE_KIND_SILU_MLP)
+    return set_error(MOQE_E_FORMAT, "moqe_forward_ragged: kind %d (images have a fixed number of pixels)", b->kind);
+  if (S < 0 || M < S || M > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: S=%d M=%lld", S, M);
+  if (!b->w0) return set_error(MOQE_E_NULL, "moqe_forward_ragged: w0 is NULL");
+  rc = plan_experts(b->w0, K, b->kind == MOQE_KIND_SILU_MLP ? b->w1 : nullptr, gp0, "moqe_forward_ragged");
+  if (rc) return rc;
+  if (b->w0[0].k != b->router.d) return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: experts take %d features, the router %d", b->w0[0].k, b->router.d);
+  if (b->router.d % 8) return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: d=%d must be a multiple of 8", b->router.d);
+  if (b->kind == MOQE_KIND_SILU_MLP) {
+    if (!b->w1 || !b->w2) return set_error(MOQE_E_NULL, "moqe_forward_ragged: w1 or w2 is NULL");
+    rc = plan_experts(b->w2, K, nullptr, gp2, "moqe_forward_ragged");
+    if (rc) return rc;
+    if (b->w2[0].k != b->w0[0].n) return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: down takes %d features, gate/up give %d", b->w2[0].k, b->w0[0].n);
+  }
+  size_t o = 0;
+  L->route = o;       o += align256(route_ws_bytes(S, 2, b->router));
+  L->idx = o;         o += align256(size_t(S) * 4);
+  L->logits = o;      o += align256(size_t(S) * K * 4);
+  L->counts = o;      o += align256(size_t(K) * 4);
+  L->offsets = o;     o += align256(size_t(K + 1) * 4);
+  L->perm = o;        o += align256(size_t(S) * 4);
+  L->inv_perm = o;    o += align256(size_t(S) * 4);
+  L->slot_rows = o;   o += align256(size_t(S + 1) * 4);
+  L->row_offsets = o; o += align256(size_t(K + 1) * 4);
+  L->row_perm = o;    o += align256(size_t(M) * 4);
+  L->h = o;
+  if (b->kind == MOQE_KIND_SILU_MLP) o += align256(size_t(M) * size_t(b->w0[0].n) * 2);
+  L->a8 = o;
+  {
+    bool any = gp0->any_a8 || (b->kind == MOQE_KIND_SILU_MLP && gp2->any_a8);
+    int kmax = b->w0[0].k;
+    if (b->kind == MOQE_KIND_SILU_MLP) kmax = std::max(kmax, b->w2[0].k);
+    o += a8_bytes(any, int(M), kmax);
+  }
+  L->total = o;
+  return MOQE_OK;
+}
+}  // namespace
+
+size_t moqe_workspace_bytes_ragged(const moqe_block* blk, int32_t S, int32_t M) {
+  RaggedLayout L;
+  GroupedPlan g0, g2;
+  if (ragged_layout(blk, S, M, &L, &g0, &g2)) return 0;
+  return L.total;
+}
+
+int32_t moqe_forward_ragged(const moqe_block* blk, const void* x, const int32_t* cu_rows, int32_t S, int32_t M, void* y,
+                            const moqe_aux* aux, void* workspace, size_t workspace_bytes, void* stream) {
+  RaggedLayout L;
+  GroupedPlan g0, g2;
+  int32_t rc = ragged_layout(blk, S, M, &L, &g0, &g2);
+  if (rc) return rc;
+  if (S == 0) return MOQE_OK;
+  if (!x || !y || !cu_rows) return set_error(MOQE_E_NULL, "moqe_forward_ragged: x, y or cu_rows is NULL");
+  if (!aligned(x, 16) || !aligned(y, 16)) return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: x and y must be 16-byte aligned");
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total)
+    return set_error(MOQE_E_WORKSPACE, "moqe_forward_ragged: workspace needs %zu bytes, 256-byte aligned", L.total);
+  if (dry_run()) return MOQE_OK;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  const int K = blk->n_experts;
+  int32_t* idx = reinterpret_cast<int32_t*>(ws + L.idx);
+  float* logits = reinterpret_cast<float*>(ws + L.logits);
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + L.counts);
+  int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
+  int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
+  int32_t* inv_perm = reinterpret_cast<int32_t*>(ws + L.inv_perm);
+  if (aux) {
+    if (aux->expert_idx) idx = aux->expert_idx;
+    if (aux->logits) logits = aux->logits;
+    if (aux->counts) counts = aux->counts;
+    if (aux->offsets) offsets = aux->offsets;
+    if (aux->perm) perm = aux->perm;
+    if (aux->inv_perm) inv_perm = aux->inv_perm;
+  }
+  int32_t* slot_rows = reinterpret_cast<int32_t*>(ws + L.slot_rows);
+  int32_t* row_offsets = reinterpret_cast<int32_t*>(ws + L.row_offsets);
+  int32_t* row_perm = reinterpret_cast<int32_t*>(ws + L.row_perm);
+
+  rc = launch_route_ragged(x, cu_rows, S, blk->router, idx, (aux && aux->logits) ? logits : nullptr, ws + L.route, st);
+  if (rc) return rc;
+  rc = launch_bucket(idx, S, K, counts, offsets, perm, (aux && aux->inv_perm) ? inv_perm : nullptr, st);
+  if (rc) return rc;
+  rc = launch_expand_rows(cu_rows, offsets, perm, S, K, slot_rows, row_offsets, row_perm, st);
+  if (rc) return rc;
+  // from here on every row is its own "sample": bucket offsets and permutation at row granularity
+  if (blk->kind == MOQE_KIND_LINEAR)
+    return run_grouped(x, row_offsets, row_perm, row_perm, M, 1, blk->w0, nullptr, K, g0, y, ws + L.a8, st);
+  void* h = (aux && aux->h) ? aux->h : static_cast<void*>(ws + L.h);
+  rc = run_grouped(x, row_offsets, row_perm, nullptr, M, 1, blk->w0, blk->w1, K, g0, h, ws + L.a8, st);
+  if (rc) return rc;
+  return run_grouped(h, row_offsets, nullptr, row_perm, M, 1, blk->w2, nullptr, K, g2, y, ws + L.a8, st);
 }
 
 // ---- timing --------------------------------------------------------------------------------

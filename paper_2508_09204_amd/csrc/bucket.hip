@@ -17,6 +17,61 @@ int32_t launch_bucket(const int32_t* idx, int S, int K, int32_t* counts, int32_t
   return check_launch("bucket");
 }
 
+// Samples of different lengths.  After the samples are grouped by expert, their rows are: slot j of the
+// bucket order holds sample perm[j] with the rows cu_rows[perm[j]] .. cu_rows[perm[j] + 1).
+//   slot_rows[j]   = first bucket-order row of slot j (exclusive prefix sum of the lengths), slot_rows[S] = M
+//   row_offsets[e] = slot_rows[offsets[e]]: first bucket-order row of expert e, row_offsets[K] = M
+// One work-group; the scan over the slots runs in blocks of 256 with a fixed order.
+__global__ __launch_bounds__(256) void k_slot_rows(const int32_t* __restrict__ cu_rows, const int32_t* __restrict__ offsets,
+                                                    const int32_t* __restrict__ perm, int S, int K,
+                                                    int32_t* __restrict__ slot_rows, int32_t* __restrict__ row_offsets) {
+  __shared__ int part[256];
+  __shared__ int carry;
+  const int tid = threadIdx.x;
+  if (tid == 0) carry = 0;
+  __syncthreads();
+  for (int j0 = 0; j0 < S; j0 += 256) {
+    const int j = j0 + tid;
+    int len = 0;
+    if (j < S) { const int s = perm[j]; len = cu_rows[s + 1] - cu_rows[s]; }
+    part[tid] = len;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {                 // inclusive scan (Hillis-Steele)
+      const int v = tid >= d ? part[tid - d] : 0;
+      __syncthreads();
+      part[tid] += v;
+      __syncthreads();
+    }
+    if (j < S) slot_rows[j] = carry + part[tid] - len;
+    __syncthreads();
+    if (tid == 255) carry += part[255];
+    __syncthreads();
+  }
+  if (tid == 0) slot_rows[S] = carry;
+  __syncthreads();
+  if (tid <= K) {
+    const int j = offsets[tid];
+    row_offsets[tid] = j < S ? slot_rows[j] : carry;     // written by this work-group: visible after the barrier
+  }
+}
+
+// row_perm[slot_rows[j] + t] = cu_rows[perm[j]] + t: source row of every bucket-order row.  A wave per slot.
+__global__ __launch_bounds__(256) void k_row_perm(const int32_t* __restrict__ cu_rows, const int32_t* __restrict__ perm,
+                                                   const int32_t* __restrict__ slot_rows, int S, int32_t* __restrict__ row_perm) {
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= S) return;
+  const int s = perm[j], src0 = cu_rows[s], len = cu_rows[s + 1] - src0, dst0 = slot_rows[j];
+  for (int t = threadIdx.x & 63; t < len; t += 64) row_perm[dst0 + t] = src0 + t;
+}
+
+int32_t launch_expand_rows(const int32_t* cu_rows, const int32_t* offsets, const int32_t* perm, int S, int K,
+                           int32_t* slot_rows, int32_t* row_offsets, int32_t* row_perm, hipStream_t st) {
+  ProfileScope ps(MOQE_PK_BUCKET, st);
+  hipLaunchKernelGGL(k_slot_rows, dim3(1), dim3(256), 0, st, cu_rows, offsets, perm, S, K, slot_rows, row_offsets);
+  hipLaunchKernelGGL(k_row_perm, dim3((S + 3) / 4), dim3(256), 0, st, cu_rows, perm, slot_rows, S, row_perm);
+  return check_launch("expand_rows");
+}
+
 // Load-balance statistics (MoQE Section 3.2, Eq. 1-2) of one batch.  One work-group: thread t adds
 // the softmax probabilities of samples t, t + 256, ... in that order, the 256 partial sums per
 // expert are added by a fixed tree in LDS, thread 0 finishes.  fp32 throughout.

@@ -182,6 +182,10 @@ int32_t check_launch(const char* what);
 int32_t launch_route(const void* x, int S, int T, const moqe_router& r, int32_t* idx, float* logits,
                      void* ws, hipStream_t st);
 size_t  route_ws_bytes(int S, int T, const moqe_router& r);
+int32_t launch_route_ragged(const void* x, const int32_t* cu_rows, int S, const moqe_router& r, int32_t* idx, float* logits,
+                            void* ws, hipStream_t st);
+int32_t launch_expand_rows(const int32_t* cu_rows, const int32_t* offsets, const int32_t* perm, int S, int K,
+                           int32_t* slot_rows, int32_t* row_offsets, int32_t* row_perm, hipStream_t st);
 int32_t launch_route_bucket(const void* x, int S, int T, const moqe_router& r, int32_t* idx, float* logits,
                             int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t st);
 int32_t launch_bucket(const int32_t* idx, int S, int K, int32_t* counts, int32_t* offsets,

@@ -287,6 +287,32 @@ __global__ __launch_bounds__(256) void k_router_tail(const float* __restrict__ f
   bucket_body(idx_l, S, K, counts, offsets, perm, inv_perm);
 }
 
+// Samples of different lengths: pooled[s][d] = mean over the rows cu_rows[s] .. cu_rows[s+1] of x[., d].
+// A thread owns 8 columns of one sample and adds that sample's rows in order (fp32).
+__global__ __launch_bounds__(256) void k_pool_ragged(const uint16_t* __restrict__ x, const int32_t* __restrict__ cu_rows,
+                                                      float* __restrict__ pooled, int D) {
+  const int s = blockIdx.y;
+  const int c8 = blockIdx.x * 256 + threadIdx.x;
+  if (c8 * 8 >= D) return;
+  const int r0 = cu_rows[s], r1 = cu_rows[s + 1];
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = r0; r < r1; ++r) {
+    const uint4 v = *reinterpret_cast<const uint4*>(x + size_t(r) * D + c8 * 8);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc[2 * j] += bf16_bits_to_float(w[j] & 0xffffu);
+      acc[2 * j + 1] += bf16_bits_to_float(w[j] >> 16);
+    }
+  }
+  const float inv = 1.0f / float(r1 - r0);
+  float4 o0 = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+  float4 o1 = {acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv};
+  float* dst = pooled + size_t(s) * D + c8 * 8;
+  *reinterpret_cast<float4*>(dst) = o0;
+  *reinterpret_cast<float4*>(dst + 4) = o1;
+}
+
 static void pool_shape(int T, int D, int* C, int* CT) {
   int cols8 = D / 8;
   int ct = 1;
@@ -312,7 +338,8 @@ size_t route_ws_bytes(int S, int T, const moqe_router& r) {
 // Pooling and hidden layer; returns the feature description for the logits stage.
 struct RouteFeat { const float* feat; int nslices; size_t stride; int Dk; };
 
-static int32_t route_front(const void* x, int S, int T, const moqe_router& r, void* ws, hipStream_t st, RouteFeat* rf) {
+static int32_t route_front(const void* x, const int32_t* cu_rows, int S, int T, const moqe_router& r, void* ws, hipStream_t st,
+                           RouteFeat* rf) {
   int C, CT;
   pool_shape(T, r.d, &C, &CT);
   const int D = r.d;
@@ -322,8 +349,12 @@ static int32_t route_front(const void* x, int S, int T, const moqe_router& r, vo
   float* pooled = reinterpret_cast<float*>(p);
   p += align256(size_t(S) * D * 4);
   float* hidden = reinterpret_cast<float*>(p);
-  const bool direct = (T == 1 && r.h > 0);      // the hidden layer reads the bf16 rows themselves
-  if (!direct) {
+  const bool direct = (!cu_rows && T == 1 && r.h > 0);      // the hidden layer reads the bf16 rows themselves
+  if (cu_rows) {
+    ProfileScope ps(MOQE_PK_ROUTE, st);
+    hipLaunchKernelGGL(k_pool_ragged, dim3((D / 8 + 255) / 256, S), dim3(256), 0, st, static_cast<const uint16_t*>(x), cu_rows,
+                       pooled, D);
+  } else if (!direct) {
     {
       ProfileScope ps(MOQE_PK_ROUTE, st);
       dim3 grid((D / 8 + CT - 1) / CT, C, S);
@@ -351,7 +382,20 @@ static int32_t route_front(const void* x, int S, int T, const moqe_router& r, vo
 int32_t launch_route(const void* x, int S, int T, const moqe_router& r, int32_t* idx, float* logits,
                      void* ws, hipStream_t st) {
   RouteFeat rf;
-  int32_t rc = route_front(x, S, T, r, ws, st, &rf);
+  int32_t rc = route_front(x, nullptr, S, T, r, ws, st, &rf);
+  if (rc) return rc;
+  ProfileScope ps(MOQE_PK_ROUTE, st);
+  hipLaunchKernelGGL(k_router_logits_argmax, dim3((S + 3) / 4), dim3(256), 0, st, rf.feat, rf.nslices, rf.stride, r.b1,
+                     r.w2, r.b2, S, rf.Dk, r.n_experts, idx, logits);
+  return check_launch("route");
+}
+
+// Samples of different lengths (cu_rows: device int32 [S + 1], first row of every sample): the
+// workspace is that of route_ws_bytes(S, 2, r).
+int32_t launch_route_ragged(const void* x, const int32_t* cu_rows, int S, const moqe_router& r, int32_t* idx, float* logits,
+                            void* ws, hipStream_t st) {
+  RouteFeat rf;
+  int32_t rc = route_front(x, cu_rows, S, 2, r, ws, st, &rf);
   if (rc) return rc;
   ProfileScope ps(MOQE_PK_ROUTE, st);
   hipLaunchKernelGGL(k_router_logits_argmax, dim3((S + 3) / 4), dim3(256), 0, st, rf.feat, rf.nslices, rf.stride, r.b1,
@@ -370,7 +414,7 @@ int32_t launch_route_bucket(const void* x, int S, int T, const moqe_router& r, i
     return launch_bucket(idx, S, r.n_experts, counts, offsets, perm, inv_perm, st);
   }
   RouteFeat rf;
-  int32_t rc = route_front(x, S, T, r, ws, st, &rf);
+  int32_t rc = route_front(x, nullptr, S, T, r, ws, st, &rf);
   if (rc) return rc;
   if (rf.nslices > 1) {
     // the slices of the hidden layer are best added by many work-groups: separate logits and bucket kernels

@@ -65,6 +65,22 @@ def test_balance_stats_argument_errors(mq):
     assert lib.moqe_balance_stats(FAKE, FAKE, 8, 4, 0.02, FAKE, None) == 0
 
 
+def test_ragged_argument_errors(mq):
+    import ctypes as C
+    lib = mq.lib
+    r = mq._Router(None, None, FAKE, None, 256, 0, 4)
+    assert lib.moqe_route_ragged_workspace_bytes(8, C.byref(r)) > 0
+    need = lib.moqe_route_ragged_workspace_bytes(8, C.byref(r))
+    assert lib.moqe_route_ragged(FAKE, FAKE, 8, C.byref(r), FAKE, None, FAKE, need, None) == 0
+    assert lib.moqe_route_ragged(FAKE, None, 8, C.byref(r), FAKE, None, FAKE, need, None) == -1
+    assert lib.moqe_route_ragged(FAKE, FAKE, 8, C.byref(r), FAKE, None, FAKE, need - 1, None) == -4
+    assert lib.moqe_route_ragged(FAKE, FAKE, -1, C.byref(r), FAKE, None, FAKE, need, None) == -2
+    assert lib.moqe_expand_rows(FAKE, FAKE, FAKE, 8, 4, FAKE, FAKE, FAKE, None) == 0
+    assert lib.moqe_expand_rows(FAKE, FAKE, FAKE, 8, 0, FAKE, FAKE, FAKE, None) == -2
+    assert lib.moqe_expand_rows(None, FAKE, FAKE, 8, 4, FAKE, FAKE, FAKE, None) == -1
+    assert lib.moqe_expand_rows(FAKE, FAKE, FAKE, 8, 4, FAKE, FAKE, None, None) == -1
+
+
 def test_cache_argument_errors(mq):
     import ctypes as C
     lib = mq.lib

@@ -97,7 +97,7 @@ typedef struct moqe_router {
  *              w2 = down; gate and up of an expert share one format.
  *   CONV3X3  : per image, 3x3 convolution, stride 1, zero padding 1, no bias.  x is NHWC
  *              [S, img_h, img_w, cin] (T = img_h*img_w), w0[e] is [cout, cin*9] with
- *              k = c*9 + kh*3 + kw; y is NHWC fp32. */
+ *              k = (kh*3 + kw)*cin + c (taps slow, channels fast, like x); y is NHWC fp32. */
 typedef struct moqe_block {
   int32_t kind;
   moqe_router router;

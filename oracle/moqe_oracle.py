@@ -353,19 +353,20 @@ def silu_mlp(x: np.ndarray, gate: QMat, up: QMat, down: QMat) -> Tuple[np.ndarra
 def conv3x3(img: np.ndarray, qm: QMat, cin: int) -> np.ndarray:
     """3x3 convolution, stride 1, zero padding 1, no bias.  img fp64 [H, W, Cin] -> [H, W, Cout].
 
-    The weight matrix row n is the filter of output channel n flattened as
-    k = cin * 9 + kh * 3 + kw (O, I, kh, kw order); quantization groups run along this k.
+    The weight matrix row n is the filter of output channel n flattened channels-last, like the
+    activations: k = (kh * 3 + kw) * Cin + cin (O, kh, kw, I order); quantization groups run along
+    this k, so a group of 64 covers 64 neighbouring input channels of one filter tap.
     """
     img = np.asarray(img, dtype=np.float64)
     Hh, Ww, C = img.shape
     assert C == cin and qm.k == cin * 9
-    w = _dequant_memo(qm).reshape(qm.n, cin, 3, 3)
+    w = _dequant_memo(qm).reshape(qm.n, 3, 3, cin)
     xp = np.zeros((Hh + 2, Ww + 2, C), dtype=np.float64)
     xp[1:-1, 1:-1, :] = img
     y = np.zeros((Hh, Ww, qm.n), dtype=np.float64)
     for kh in range(3):
         for kw in range(3):
-            y += xp[kh:kh + Hh, kw:kw + Ww, :] @ w[:, :, kh, kw].T
+            y += xp[kh:kh + Hh, kw:kw + Ww, :] @ w[:, kh, kw, :].T
     return y
 
 

@@ -367,8 +367,8 @@ int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedP
     rc = plan_experts(b->w0, K, nullptr, gp0, "moqe_forward(conv)");
     if (rc) return rc;
     if (b->img_h <= 0 || b->img_w <= 0 || b->cin <= 0 || b->img_h * b->img_w != T || b->cin != b->router.d ||
-        b->w0[0].k != b->cin * 9)
-      return set_error(MOQE_E_SHAPE, "moqe_forward: conv needs T = img_h*img_w, cin = router d, k = 9*cin");
+        b->w0[0].k != b->cin * 9 || (b->cin % 8) != 0)
+      return set_error(MOQE_E_SHAPE, "moqe_forward: conv needs T = img_h*img_w, cin = router d (a multiple of 8), k = 9*cin");
   } else {
     return set_error(MOQE_E_FORMAT, "moqe_forward: unknown block kind %d", b->kind);
   }

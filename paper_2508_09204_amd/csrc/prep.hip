@@ -206,77 +206,29 @@ int32_t launch_act_quant(const void* x_bf16, int kdim, int T, const int32_t* off
 }
 
 // ---- im2col for 3x3 / stride 1 / zero pad 1, NHWC input ---------------------------------------
-// out[(s*H*W + y*W + x), c*9 + kh*3 + kw] = in[s, y+kh-1, x+kw-1, c] (0 outside the image).
-// One thread writes 8 consecutive output columns (fallback for rows too wide for LDS).
-__global__ void k_im2col_direct(const uint16_t* __restrict__ in, int S, int H, int W, int C, uint16_t* __restrict__ out) {
-  const int KK = C * 9;
-  const int chunks = KK / 8;
-  size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (i >= size_t(S) * H * W * chunks) return;
-  const int ch = int(i % chunks);
-  const size_t row = i / chunks;
-  const int px = int(row % W), py = int((row / W) % H), s = int(row / (size_t(W) * H));
-  uint16_t v[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int kcol = ch * 8 + j;
-    const int c = kcol / 9, tap = kcol % 9, kh = tap / 3, kw = tap % 3;
-    const int yy = py + kh - 1, xx = px + kw - 1;
-    v[j] = (yy >= 0 && yy < H && xx >= 0 && xx < W) ? in[((size_t(s) * H + yy) * W + xx) * C + c] : uint16_t(0);
-  }
-  uint4 pk;
-  pk.x = v[0] | (uint32_t(v[1]) << 16); pk.y = v[2] | (uint32_t(v[3]) << 16);
-  pk.z = v[4] | (uint32_t(v[5]) << 16); pk.w = v[6] | (uint32_t(v[7]) << 16);
-  *reinterpret_cast<uint4*>(out + row * KK + size_t(ch) * 8) = pk;
-}
-
-// Same result, one work-group per output image row: the three input rows it needs (with a zero
-// column on either side, so the taps need no bounds checks) are staged in LDS with 16-byte loads,
-// and each thread then assembles 8 consecutive output columns from LDS and stores them as one
-// 16-byte unit; the stores of a work-group cover its output rows contiguously.
+// out[(s*H*W + y*W + x), (kh*3 + kw)*C + c] = in[s, y+kh-1, x+kw-1, c] (0 outside the image): the
+// filter taps are the slow index and the channels the fast one, like the activations themselves,
+// so the matrix is made of 16-byte copies (8 channels) of input pixels.  One thread per copy.
 __global__ __launch_bounds__(256) void k_im2col(const uint16_t* __restrict__ in, int S, int H, int W, int C,
                                                  uint16_t* __restrict__ out) {
-  extern __shared__ __align__(16) uint16_t rows[];          // [3][W + 2][C]
-  const int s = blockIdx.x / H, py = blockIdx.x % H;
-  const int tid = threadIdx.x;
   const int cu = C / 8;                                      // 16-byte units per pixel
-  for (int u = tid; u < 3 * (W + 2) * cu; u += 256) {
-    const int kh = u / ((W + 2) * cu), rem = u % ((W + 2) * cu), col = rem / cu, c8 = rem % cu;
-    const int yy = py + kh - 1, xx = col - 1;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (yy >= 0 && yy < H && xx >= 0 && xx < W)
-      v = *reinterpret_cast<const uint4*>(in + ((size_t(s) * H + yy) * W + xx) * C + c8 * 8);
-    *reinterpret_cast<uint4*>(rows + (size_t(kh) * (W + 2) + col) * C + c8 * 8) = v;
-  }
-  __syncthreads();
-  const int KK = C * 9, chunks = KK / 8;
-  uint16_t* orow = out + (size_t(s) * H + py) * W * size_t(KK);
-  for (int u = tid; u < W * chunks; u += 256) {
-    const int px = u / chunks, ch = u % chunks;
-    int c = (ch * 8) / 9, tap = (ch * 8) % 9;
-    uint32_t v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int kh = tap / 3, kw = tap - kh * 3;
-      v[j] = rows[(size_t(kh) * (W + 2) + (px + kw)) * C + c];
-      if (++tap == 9) { tap = 0; ++c; }
-    }
-    uint4 pk;
-    pk.x = v[0] | (v[1] << 16); pk.y = v[2] | (v[3] << 16); pk.z = v[4] | (v[5] << 16); pk.w = v[6] | (v[7] << 16);
-    *reinterpret_cast<uint4*>(orow + size_t(px) * KK + size_t(ch) * 8) = pk;
-  }
+  const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= size_t(S) * H * W * 9 * cu) return;
+  const int c8 = int(i % cu);
+  const int tap = int((i / cu) % 9);
+  const size_t row = i / (size_t(cu) * 9);
+  const int px = int(row % W), py = int((row / W) % H), s = int(row / (size_t(W) * H));
+  const int yy = py + tap / 3 - 1, xx = px + tap % 3 - 1;
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (yy >= 0 && yy < H && xx >= 0 && xx < W)
+    v = *reinterpret_cast<const uint4*>(in + ((size_t(s) * H + yy) * W + xx) * C + c8 * 8);
+  *reinterpret_cast<uint4*>(out + row * (size_t(C) * 9) + size_t(tap) * C + c8 * 8) = v;
 }
 
 int32_t launch_im2col(const void* x, int S, int H, int W, int C, void* out, hipStream_t st) {
   ProfileScope ps(MOQE_PK_IM2COL, st);
-  const size_t lds = size_t(3) * (W + 2) * C * 2;
-  if (lds <= 64 * 1024 && (C % 8) == 0) {
-    hipLaunchKernelGGL(k_im2col, dim3(unsigned(S) * unsigned(H)), dim3(256), lds, st, static_cast<const uint16_t*>(x), S, H, W, C,
-                       static_cast<uint16_t*>(out));
-    return check_launch("im2col");
-  }
-  size_t n = size_t(S) * H * W * (size_t(C) * 9 / 8);
-  hipLaunchKernelGGL(k_im2col_direct, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, static_cast<const uint16_t*>(x), S, H, W, C,
+  const size_t n = size_t(S) * H * W * 9 * (C / 8);
+  hipLaunchKernelGGL(k_im2col, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, static_cast<const uint16_t*>(x), S, H, W, C,
                      static_cast<uint16_t*>(out));
   return check_launch("im2col");
 }

@@ -130,10 +130,10 @@ def test_conv_matches_scalar_loops_and_torch():
                         for kw in range(3):
                             hh, ww = h + kh - 1, x_ + kw - 1
                             if 0 <= hh < Hh and 0 <= ww < Ww:
-                                acc += img[hh, ww, c] * wd[n, c * 9 + kh * 3 + kw]
+                                acc += img[hh, ww, c] * wd[n, (kh * 3 + kw) * Cin + c]
                 assert math.isclose(y[h, x_, n], acc, rel_tol=1e-11, abs_tol=1e-14)
     t = torch.nn.functional.conv2d(torch.from_numpy(img).permute(2, 0, 1)[None],
-                                   torch.from_numpy(wd).reshape(Cout, Cin, 3, 3), padding=1)
+                                   torch.from_numpy(wd).reshape(Cout, 3, 3, Cin).permute(0, 3, 1, 2), padding=1)
     np.testing.assert_allclose(y, t[0].permute(1, 2, 0).numpy(), rtol=1e-11, atol=1e-14)
 
 
@@ -151,7 +151,7 @@ def test_conv_group_format_is_im2col_matmul():
             for c in range(Cin):
                 for kh in range(3):
                     for kw in range(3):
-                        cols[h * Ww + x_, c * 9 + kh * 3 + kw] = xp[h + kh, x_ + kw, c]
+                        cols[h * Ww + x_, (kh * 3 + kw) * Cin + c] = xp[h + kh, x_ + kw, c]
     np.testing.assert_allclose(y.reshape(Hh * Ww, Cout), cols @ oc.dequant(qm).T, rtol=1e-11, atol=1e-14)
 
 
@@ -188,7 +188,7 @@ def test_one_hot_router_is_the_single_quantized_model(kind):
             h = _bf16_by_bits(g / (1 + np.exp(-g)) * u)
             ref = np.matmul(h, np.array(_loop_dequant(blk.w2[e])).T)
         else:
-            wd = torch.from_numpy(np.array(_loop_dequant(blk.w0[e]))).reshape(cfg.F, cfg.D, 3, 3)
+            wd = torch.from_numpy(np.array(_loop_dequant(blk.w0[e]))).reshape(cfg.F, 3, 3, cfg.D).permute(0, 3, 1, 2)
             xi = torch.from_numpy(x.reshape(cfg.S, cfg.img_h, cfg.img_w, cfg.D)).permute(0, 3, 1, 2)
             ref = torch.nn.functional.conv2d(xi, wd, padding=1).permute(0, 2, 3, 1).numpy()
         ref = ref.reshape(y.shape)

@@ -221,7 +221,7 @@ def main():
         roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
         # the same launch against the HBM roofline: weights once, activations in (bf16), results out
-        k_in = dom_mats[0][1]
+        k_in = cfg.D if cfg.kind == wl.configs.KIND_CONV3X3 else dom_mats[0][1]     # conv: the kernel gathers from the image
         n_out_dom = dom_mats[0][0]
         io_bytes = cfg.M * k_in * 2 + cfg.M * n_out_dom * (2 if is_mlp else 4)
         roof["hbm_view"] = {"algorithmic_bytes_per_launch": dom_bytes + io_bytes,

@@ -146,13 +146,17 @@ static int32_t plan_experts(const moqe_qmat* experts, int K, const moqe_qmat* se
   return MOQE_OK;
 }
 
+// Buckets of a few rows stream the weights once per launch; buckets of many rows are a dense
+// contraction and take the LDS-tiled kernel (more than 64 rows per expert on average).
 constexpr int TILE_MIN_ROWS_PER_EXPERT = 64;
+static bool use_tile_kernel(long long M, int K) { return M > (long long)TILE_MIN_ROWS_PER_EXPERT * K; }
 
 // Enqueues one grouped GEMM (plus the int8 row quantization its act_mode-1 experts need).
 static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t* a_perm, const int32_t* y_perm, int S, int T,
                            const moqe_qmat* experts, const moqe_qmat* second, int K, const GroupedPlan& gp, void* y,
-                           uint8_t* a8_ws, hipStream_t st) {
-  if (size_t(S) * size_t(T) * size_t(experts[0].k) * 2 >= (size_t(1) << 32))
+                           uint8_t* a8_ws, hipStream_t st, int conv_h = 0, int conv_w = 0, int conv_c = 0) {
+  // conv_c > 0: a is the NHWC image and the tiled kernel gathers the 3x3 neighbourhoods itself
+  if (conv_c == 0 && size_t(S) * size_t(T) * size_t(experts[0].k) * 2 >= (size_t(1) << 32))
     return set_error(MOQE_E_SHAPE, "grouped_qgemm: activation matrix of %d x %d exceeds 4 GiB", S * T, experts[0].k);
   GemmArgs ga;
   memset(&ga, 0, sizeof(ga));
@@ -160,6 +164,7 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
   ga.n = experts[0].n; ga.k = experts[0].k;
   ga.S = S; ga.T = T;
   ga.a = a; ga.offsets = offsets; ga.a_perm = a_perm; ga.y_perm = y_perm; ga.y = y;
+  ga.conv_h = conv_h; ga.conv_w = conv_w; ga.conv_c = conv_c;
   for (int e = 0; e < K; ++e) fill_expert(experts[e], second ? &second[e] : nullptr, gp.pi[e], &ga.ex[e]);
   order_experts(&ga);
   const int M = S * T;
@@ -175,7 +180,7 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
   }
   // Buckets of a few rows stream the weights once per launch; buckets of many rows are a dense
   // contraction and take the LDS-tiled kernel.
-  if (M > TILE_MIN_ROWS_PER_EXPERT * K) return launch_qgemm_tile(ga, second != nullptr, st);
+  if (use_tile_kernel(M, K)) return launch_qgemm_tile(ga, second != nullptr, st);
   return launch_qgemm_stream(ga, second != nullptr, st);
 }
 
@@ -448,7 +453,10 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
     if (rc) return rc;
     return run_grouped(h, offsets, nullptr, perm, S, T, blk->w2, nullptr, K, g2, y, ws + L.a8, st);
   }
-  // CONV3X3: materialise the 3x3 neighbourhoods in image order, then one grouped GEMM
+  // CONV3X3 with many rows: the tiled kernel gathers each row's 3x3 neighbourhood from the image itself
+  if (use_tile_kernel((long long)S * T, K) && !g0.any_a8)
+    return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, blk->img_h, blk->img_w, blk->cin);
+  // otherwise: materialise the 3x3 neighbourhoods in image order, then one grouped GEMM
   void* col = ws + L.col;
   rc = launch_im2col(x, S, blk->img_h, blk->img_w, blk->cin, col, st);
   if (rc) return rc;

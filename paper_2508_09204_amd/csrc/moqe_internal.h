@@ -160,6 +160,8 @@ struct GemmArgs {
   const int32_t* a_perm;     // bucket slot -> sample for reading a; NULL: a is in bucket order
   const int32_t* y_perm;     // bucket slot -> sample for writing y; NULL: bucket order
   void*     y;               // float [M, n] (plain) or bf16 [M, n] (gate/up, bucket order)
+  int32_t   conv_h, conv_w, conv_c;   // tiled kernel, 3x3 convolution: a is the NHWC image [S, h, w, c] and the
+                             // k = (kh*3 + kw)*c + ch columns of a row are gathered from its pixel's neighbours
   int32_t   wn, wk;          // work-group geometry: tasks per work-group, k-slices per task
   int32_t   wg_per_expert;
 };

@@ -33,7 +33,7 @@ constexpr int TBN = TWN * TNB * 16;      // 256 weight rows per work-group tile
 constexpr int T_SLOT = 256;              // LDS bytes per staged row and k-step (int8 rows use half)
 constexpr int T_LDS_BYTES = 2 * TBM * T_SLOT;
 
-template <int FMT, int GM, bool GATEUP>
+template <int FMT, int GM, bool GATEUP, bool CONV>
 static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int m0,
                                                  const int ntile, uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
@@ -80,6 +80,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
   const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
   uint32_t a_off[A_ITERS];
   const int a_unit = tid % A_UNITS, a_row0 = tid / A_UNITS;
+  int a_py[CONV ? A_ITERS : 1], a_px[CONV ? A_ITERS : 1];       // convolution: the row's pixel inside its image
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
     const int m = min(m0 + a_row0 + i * A_ROWS_PER_IT, M_e - 1);      // rows past the bucket repeat its last row
@@ -87,13 +88,43 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
     if constexpr (A8) src = size_t(off_e) * T + m;
     else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
     else src = size_t(off_e) * T + m;
-    a_off[i] = uint32_t(src * size_t(ga.k) * EB + a_unit * 16);
+    if constexpr (CONV && !A8) {
+      a_off[i] = uint32_t(src);                                       // pixel index in the NHWC image
+      const int p = int(src % size_t(T));
+      a_py[i] = p / ga.conv_w;
+      a_px[i] = p - a_py[i] * ga.conv_w;
+    } else {
+      a_off[i] = uint32_t(src * size_t(ga.k) * EB + a_unit * 16);
+    }
   }
   u32x4 a_reg[A_ITERS];
+  // Convolution: the 8 columns of this thread's unit are 8 neighbouring channels of ONE filter tap
+  // (k = tap * C + channel), i.e. 16 contiguous bytes of the pixel at that tap's offset, or zeros
+  // outside the image.  a_fetch is called for k-steps 0, 1, 2, ... in order, so tap and channel of
+  // the unit advance by 128 columns per call.
+  int cv_tap = 0, cv_c = CONV ? a_unit * 8 : 0;
+  if constexpr (CONV && !A8) {
+    while (cv_c >= ga.conv_c) { cv_c -= ga.conv_c; ++cv_tap; }
+  }
   auto a_fetch = [&](int kt) {
-    const uint32_t koff = uint32_t(min(kt, KT - 1)) * (128 * EB);
+    if constexpr (CONV && !A8) {
+      const int dy = cv_tap / 3 - 1, dx = cv_tap - (cv_tap / 3) * 3 - 1;
+      const bool tap_ok = cv_tap < 9;                                  // k-steps past the end are never multiplied
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i) a_reg[i] = *reinterpret_cast<const u32x4*>(abase + (a_off[i] + koff));
+      for (int i = 0; i < A_ITERS; ++i) {
+        const int yy = a_py[i] + dy, xx = a_px[i] + dx;
+        const bool ok = tap_ok && yy >= 0 && yy < ga.conv_h && xx >= 0 && xx < ga.conv_w;
+        const int pix = ok ? int(a_off[i]) + dy * ga.conv_w + dx : int(a_off[i]);      // always a valid address
+        u32x4 v = *reinterpret_cast<const u32x4*>(abase + (size_t(uint32_t(pix)) * size_t(ga.conv_c) + size_t(cv_c)) * 2);
+        a_reg[i].x = ok ? v.x : 0u; a_reg[i].y = ok ? v.y : 0u; a_reg[i].z = ok ? v.z : 0u; a_reg[i].w = ok ? v.w : 0u;
+      }
+      cv_c += 128;
+      while (cv_c >= ga.conv_c) { cv_c -= ga.conv_c; ++cv_tap; }
+    } else {
+      const uint32_t koff = uint32_t(min(kt, KT - 1)) * (128 * EB);
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i) a_reg[i] = *reinterpret_cast<const u32x4*>(abase + (a_off[i] + koff));
+    }
   };
   auto a_store = [&](uint8_t* buf) {
 #pragma unroll
@@ -325,7 +356,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
 // patches of an XCD, and the patches of the 8 XCDs at one time, walk along the weight rows first.
 constexpr int PATCH_M = 8, PATCH_N = 8;
 
-template <bool GATEUP>
+template <bool GATEUP, bool CONV>
 __global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga) {
   extern __shared__ __align__(16) uint8_t lds[];
   const int n_tiles = GATEUP ? (ga.n + TBN / 2 - 1) / (TBN / 2) : (ga.n + TBN - 1) / TBN;
@@ -344,14 +375,14 @@ __global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga
   if (e < 0 || ntile >= n_tiles) return;      // uniform over the work-group
   const ExpertDev& ex = ga.ex[e];
   switch (ex.fmt * 4 + ex.gm) {
-    case FMT_I8 * 4 + GM_PC:     tile_task<FMT_I8, GM_PC, GATEUP>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_I8A8 * 4 + GM_PC:   tile_task<FMT_I8A8, GM_PC, GATEUP>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N6 * 4 + GM_PC:     tile_task<FMT_N6, GM_PC, GATEUP>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N4 * 4 + GM_PC:     tile_task<FMT_N4, GM_PC, GATEUP>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N4 * 4 + GM_G128:   tile_task<FMT_N4, GM_G128, GATEUP>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N4 * 4 + GM_G64:    tile_task<FMT_N4, GM_G64, GATEUP>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N3 * 4 + GM_G128:   tile_task<FMT_N3, GM_G128, GATEUP>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N3 * 4 + GM_G64:    tile_task<FMT_N3, GM_G64, GATEUP>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_I8 * 4 + GM_PC:     tile_task<FMT_I8, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_I8A8 * 4 + GM_PC:   tile_task<FMT_I8A8, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_N6 * 4 + GM_PC:     tile_task<FMT_N6, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_N4 * 4 + GM_PC:     tile_task<FMT_N4, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_N4 * 4 + GM_G128:   tile_task<FMT_N4, GM_G128, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_N4 * 4 + GM_G64:    tile_task<FMT_N4, GM_G64, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_N3 * 4 + GM_G128:   tile_task<FMT_N3, GM_G128, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_N3 * 4 + GM_G64:    tile_task<FMT_N3, GM_G64, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
     default: break;
   }
 }
@@ -363,16 +394,20 @@ int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
   const long patches = long((row_tiles + PATCH_M - 1) / PATCH_M) * ((n_tiles + PATCH_N - 1) / PATCH_N);
   const long grid = (patches + 7) / 8 * 8 * (PATCH_M * PATCH_N);
   if (grid > 0x7fffffffL) return set_error(MOQE_E_SHAPE, "grouped_qgemm: %d rows exceed the tile kernel's grid", M);
-  static bool lds_ok[2] = {false, false};
-  const void* fn = gateup ? reinterpret_cast<const void*>(&k_qgemm_tile<true>) : reinterpret_cast<const void*>(&k_qgemm_tile<false>);
-  if (!lds_ok[gateup ? 1 : 0]) {
-    hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS_BYTES);
+  const bool conv = ga.conv_c > 0;
+  const int ki = gateup ? 1 : (conv ? 2 : 0);
+  static bool lds_ok[3] = {false, false, false};
+  const void* fns[3] = {reinterpret_cast<const void*>(&k_qgemm_tile<false, false>), reinterpret_cast<const void*>(&k_qgemm_tile<true, false>),
+                        reinterpret_cast<const void*>(&k_qgemm_tile<false, true>)};
+  if (!lds_ok[ki]) {
+    hipError_t err = hipFuncSetAttribute(fns[ki], hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS_BYTES);
     if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: cannot reserve LDS: %s", hipGetErrorString(err));
-    lds_ok[gateup ? 1 : 0] = true;
+    lds_ok[ki] = true;
   }
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL(k_qgemm_tile<true>, dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
-  else hipLaunchKernelGGL(k_qgemm_tile<false>, dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
+  if (gateup) hipLaunchKernelGGL((k_qgemm_tile<true, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
+  else if (conv) hipLaunchKernelGGL((k_qgemm_tile<false, true>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
+  else hipLaunchKernelGGL((k_qgemm_tile<false, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
   return check_launch("grouped_qgemm(tile)");
 }
 

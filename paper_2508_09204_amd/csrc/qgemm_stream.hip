@@ -7,7 +7,8 @@
 // otherwise) and streams them along k with several tiles in flight; the lanes' packed codes
 // are already ordered as matrix-core operands, so a tile goes
 //     16-byte load -> a handful of bit operations -> bf16 MFMA
-// with no shuffles and no LDS.  Integer codes enter the matrix cores exactly, as the bf16
+// with no shuffles, and the weights never touch LDS (only the few activation rows are staged there,
+// once per work-group).  Integer codes enter the matrix cores exactly, as the bf16
 // value BASE + c/2 (or c for 8-bit codes), i.e. with a constant offset; a second MFMA against an all-ones operand
 // gives the row sums of the activations over the same columns, which removes offset and
 // zero-point exactly: sum_k x (off + c) - (off + z) sum_k x.  The fp32 scale multiplies the

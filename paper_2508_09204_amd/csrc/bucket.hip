@@ -10,10 +10,39 @@ __global__ __launch_bounds__(256) void k_bucket(const int32_t* __restrict__ expe
   bucket_body(expert_idx, S, K, counts, offsets, perm, inv_perm);
 }
 
+// Up to 64 samples: one wave, a sample per lane.  The count of expert k is the population of the
+// ballot "my sample goes to k", a sample's rank inside its bucket the population of that ballot
+// below its lane: no LDS, no barriers, same result as the general kernel.
+__global__ __launch_bounds__(64) void k_bucket_wave(const int32_t* __restrict__ expert_idx, int S, int K,
+                                                     int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                                     int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+  const int lane = threadIdx.x;
+  int e = lane < S ? expert_idx[lane] : -1;
+  if (e >= K) e = -1;
+  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int base = 0, my_pos = 0;
+  for (int k = 0; k < K; ++k) {
+    const unsigned long long b = __ballot(e == k);
+    const int c = __popcll(b);
+    if (e == k) my_pos = base + __popcll(b & lt_mask);
+    if (lane == 0) {
+      offsets[k] = base;
+      if (counts) counts[k] = c;
+    }
+    base += c;
+  }
+  if (lane == 0) offsets[K] = base;
+  if (e >= 0) {
+    if (perm) perm[my_pos] = lane;
+    if (inv_perm) inv_perm[lane] = my_pos;
+  }
+}
+
 int32_t launch_bucket(const int32_t* idx, int S, int K, int32_t* counts, int32_t* offsets,
                       int32_t* perm, int32_t* inv_perm, hipStream_t st) {
   ProfileScope ps(MOQE_PK_BUCKET, st);
-  hipLaunchKernelGGL(k_bucket, dim3(1), dim3(256), 0, st, idx, S, K, counts, offsets, perm, inv_perm);
+  if (S <= 64) hipLaunchKernelGGL(k_bucket_wave, dim3(1), dim3(64), 0, st, idx, S, K, counts, offsets, perm, inv_perm);
+  else hipLaunchKernelGGL(k_bucket, dim3(1), dim3(256), 0, st, idx, S, K, counts, offsets, perm, inv_perm);
   return check_launch("bucket");
 }
 

@@ -158,7 +158,9 @@ static __device__ __forceinline__ float4 feature4(const float* __restrict__ feat
 }
 
 // One sample per wave (any batch size): logits[s][k] = b2[k] + <w2[k,:], f_s> and the first index of
-// the maximum.
+// the maximum.  KP = number of experts rounded up to 4, 8 or 16: all loops have fixed bounds, and
+// the KP cross-lane sums advance together so that their shuffles overlap.
+template <int KP>
 __global__ __launch_bounds__(256) void k_router_logits_argmax(const float* __restrict__ feat, int nslices, size_t slice_stride,
                                                                const float* __restrict__ b1, const float* __restrict__ w2,
                                                                const float* __restrict__ b2, int S, int Dk, int K,
@@ -167,30 +169,42 @@ __global__ __launch_bounds__(256) void k_router_logits_argmax(const float* __res
   const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (s >= S) return;
   // every feature is formed once (its slices are added here) and meets all K weight rows
-  float acc[MOQE_MAX_EXPERTS];
+  float acc[KP];
 #pragma unroll
-  for (int k = 0; k < MOQE_MAX_EXPERTS; ++k) acc[k] = 0.f;
+  for (int k = 0; k < KP; ++k) acc[k] = 0.f;
   for (int d = lane * 4; d < Dk; d += 256) {
     const float4 p = feature4(feat, nslices, slice_stride, b1, size_t(s) * Dk + d, d);
 #pragma unroll
-    for (int k = 0; k < MOQE_MAX_EXPERTS; ++k) {
-      if (k < K) {
-        const float4 w = *reinterpret_cast<const float4*>(w2 + size_t(k) * Dk + d);
-        acc[k] += w.x * p.x + w.y * p.y + w.z * p.z + w.w * p.w;
-      }
+    for (int k = 0; k < KP; ++k) {
+      const float4 w = *reinterpret_cast<const float4*>(w2 + size_t(k < K ? k : 0) * Dk + d);     // rows past K: row 0, unused
+      acc[k] += w.x * p.x + w.y * p.y + w.z * p.z + w.w * p.w;
     }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+    for (int k = 0; k < KP; ++k) acc[k] += __shfl_xor(acc[k], off, 64);
   }
   float best = 0.f;
   int best_k = 0;
 #pragma unroll
-  for (int k = 0; k < MOQE_MAX_EXPERTS; ++k) {
+  for (int k = 0; k < KP; ++k) {
     if (k < K) {
-      const float z = wave_sum(acc[k]) + (b2 ? b2[k] : 0.f);
+      const float z = acc[k] + (b2 ? b2[k] : 0.f);
       if (logits && lane == 0) logits[size_t(s) * K + k] = z;
       if (k == 0 || z > best) { best = z; best_k = k; }   // strict >: ties keep the lowest index
     }
   }
   if (lane == 0) expert_idx[s] = best_k;
+}
+
+static void launch_logits_argmax(const float* feat, int nslices, size_t stride, const moqe_router& r, int S, int Dk,
+                                 int32_t* idx, float* logits, hipStream_t st) {
+  const dim3 grid((S + 3) / 4), block(256);
+  const int K = r.n_experts;
+  if (K <= 4) hipLaunchKernelGGL(k_router_logits_argmax<4>, grid, block, 0, st, feat, nslices, stride, r.b1, r.w2, r.b2, S, Dk, K, idx, logits);
+  else if (K <= 8) hipLaunchKernelGGL(k_router_logits_argmax<8>, grid, block, 0, st, feat, nslices, stride, r.b1, r.w2, r.b2, S, Dk, K, idx, logits);
+  else hipLaunchKernelGGL(k_router_logits_argmax<16>, grid, block, 0, st, feat, nslices, stride, r.b1, r.w2, r.b2, S, Dk, K, idx, logits);
 }
 
 // Logits, top-1 and the stable bucketing in ONE work-group (small batches: saves launches).
@@ -385,8 +399,7 @@ int32_t launch_route(const void* x, int S, int T, const moqe_router& r, int32_t*
   int32_t rc = route_front(x, nullptr, S, T, r, ws, st, &rf);
   if (rc) return rc;
   ProfileScope ps(MOQE_PK_ROUTE, st);
-  hipLaunchKernelGGL(k_router_logits_argmax, dim3((S + 3) / 4), dim3(256), 0, st, rf.feat, rf.nslices, rf.stride, r.b1,
-                     r.w2, r.b2, S, rf.Dk, r.n_experts, idx, logits);
+  launch_logits_argmax(rf.feat, rf.nslices, rf.stride, r, S, rf.Dk, idx, logits, st);
   return check_launch("route");
 }
 
@@ -398,8 +411,7 @@ int32_t launch_route_ragged(const void* x, const int32_t* cu_rows, int S, const 
   int32_t rc = route_front(x, cu_rows, S, 2, r, ws, st, &rf);
   if (rc) return rc;
   ProfileScope ps(MOQE_PK_ROUTE, st);
-  hipLaunchKernelGGL(k_router_logits_argmax, dim3((S + 3) / 4), dim3(256), 0, st, rf.feat, rf.nslices, rf.stride, r.b1,
-                     r.w2, r.b2, S, rf.Dk, r.n_experts, idx, logits);
+  launch_logits_argmax(rf.feat, rf.nslices, rf.stride, r, S, rf.Dk, idx, logits, st);
   return check_launch("route");
 }
 
@@ -420,8 +432,7 @@ int32_t launch_route_bucket(const void* x, int S, int T, const moqe_router& r, i
     // the slices of the hidden layer are best added by many work-groups: separate logits and bucket kernels
     {
       ProfileScope ps(MOQE_PK_ROUTE, st);
-      hipLaunchKernelGGL(k_router_logits_argmax, dim3((S + 3) / 4), dim3(256), 0, st, rf.feat, rf.nslices, rf.stride, r.b1,
-                         r.w2, r.b2, S, rf.Dk, r.n_experts, idx, logits);
+      launch_logits_argmax(rf.feat, rf.nslices, rf.stride, r, S, rf.Dk, idx, logits, st);
     }
     return launch_bucket(idx, S, r.n_experts, counts, offsets, perm, inv_perm, st);
   }

@@ -14,10 +14,15 @@
  * these for one block.  The per-sample result is the same as serving samples one by one.
  *
  * Conventions (all entry points).
- *  - Return value: 0 on success, a negative MOQE_E_* code on failure.  On failure nothing
- *    has been enqueued.  moqe_last_error_string() gives a thread-local description.
+ *  - Return value: 0 on success, a negative MOQE_E_* code on failure.  Every argument
+ *    check (shapes, formats, sizes, alignment, workspace) runs before the first launch, so
+ *    an argument error enqueues nothing; only MOQE_E_HIP (the runtime refused a launch) can
+ *    come after part of a call's work was enqueued.  moqe_last_error_string() gives a
+ *    thread-local description.
  *  - Pointers named in "device" comments are DEVICE pointers owned by the caller; the
- *    library never allocates, frees or retains device memory.  Descriptor structs
+ *    library does not allocate, free or retain device memory, with one exception: an expert
+ *    cache (moqe_cache_create) owns the device slots it allocates until moqe_cache_destroy.
+ *    An activation matrix (rows x features, bf16) must stay below 4 GiB.  Descriptor structs
  *    (moqe_qmat, moqe_router, moqe_block, moqe_aux) and arrays of them are HOST memory,
  *    read during the call only.  Scratch memory is a caller-provided device workspace
  *    whose size comes from the matching *_workspace_bytes query; it must be 256-byte
@@ -220,7 +225,8 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
 
 /* The same path for samples that do not all have T rows (sequences of different lengths): x is device
  * bf16 [M, d] with sample s in the rows cu_rows[s] .. cu_rows[s+1) (cu_rows: device int32 [S+1],
- * cu_rows[0] = 0, cu_rows[S] = M, every sample has at least one row).  A sample's router feature is
+ * cu_rows[0] = 0, cu_rows[S] = M, every sample should have at least one row; a sample without rows
+ * gets all-zero router features and contributes no rows).  A sample's router feature is
  * the mean over its own rows; routing is per sample as before (Section 3.1).
  *
  * moqe_route_ragged: as moqe_route.
@@ -281,7 +287,7 @@ int32_t moqe_cache_stats(const moqe_expert_cache* cache, uint64_t* copies, uint6
 #define MOQE_PK_GEMM_GATEUP 2
 #define MOQE_PK_GEMM_PLAIN 3
 #define MOQE_PK_ACTQUANT   4
-#define MOQE_PK_IM2COL     5
+#define MOQE_PK_IM2COL     5   /* reserved (no kernel of this kind is launched) */
 #define MOQE_PK_OTHER      6
 #define MOQE_PK_COUNT      7
 #define MOQE_PROFILE_MAX_LAUNCHES 65536

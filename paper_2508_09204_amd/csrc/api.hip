@@ -32,6 +32,18 @@ int32_t check_launch(const char* what) {
   return MOQE_OK;
 }
 
+int32_t ensure_dynamic_lds(int slot, const void* kernel, int bytes, const char* what) {
+  static std::mutex mu;
+  static int state[LDSK_COUNT] = {};        // 0: not asked yet, 1: granted
+  std::lock_guard<std::mutex> lk(mu);
+  if (slot < 0 || slot >= LDSK_COUNT) return set_error(MOQE_E_SHAPE, "%s: bad kernel slot %d", what, slot);
+  if (state[slot] == 1) return MOQE_OK;
+  hipError_t err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (err != hipSuccess) return set_error(MOQE_E_HIP, "%s: cannot reserve %d bytes of LDS: %s", what, bytes, hipGetErrorString(err));
+  state[slot] = 1;
+  return MOQE_OK;
+}
+
 // ---- profiling ---------------------------------------------------------------------------
 // Event pairs come from a pool that only grows, so that recording inside a timed region costs two
 // hipEventRecord calls per launch and no event creation once the pool is warm.
@@ -115,6 +127,13 @@ static void order_experts(GemmArgs* ga) {
   for (int i = 0; i < ga->n_experts; ++i) ga->order[i] = idx[i];
 }
 
+// Byte offsets into an activation matrix are 32-bit inside the kernels.
+static int32_t check_activation_bytes(long long M, int k, const char* who) {
+  if (size_t(M) * size_t(k) * 2 >= (size_t(1) << 32))
+    return set_error(MOQE_E_SHAPE, "%s: activation matrix of %lld x %d exceeds 4 GiB", who, M, k);
+  return MOQE_OK;
+}
+
 // Workspace for the int8 copies of activation rows needed by act_mode-1 experts.
 static size_t a8_bytes(bool any_a8, int M, int kmax) {
   if (!any_a8) return 0;
@@ -156,8 +175,6 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
                            const moqe_qmat* experts, const moqe_qmat* second, int K, const GroupedPlan& gp, void* y,
                            uint8_t* a8_ws, hipStream_t st, int conv_h = 0, int conv_w = 0, int conv_c = 0) {
   // conv_c > 0: a is the NHWC image and the tiled kernel gathers the 3x3 neighbourhoods itself
-  if (conv_c == 0 && size_t(S) * size_t(T) * size_t(experts[0].k) * 2 >= (size_t(1) << 32))
-    return set_error(MOQE_E_SHAPE, "grouped_qgemm: activation matrix of %d x %d exceeds 4 GiB", S * T, experts[0].k);
   GemmArgs ga;
   memset(&ga, 0, sizeof(ga));
   ga.n_experts = K;
@@ -180,7 +197,8 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
   }
   // Buckets of a few rows stream the weights once per launch; buckets of many rows are a dense
   // contraction and take the LDS-tiled kernel.
-  if (use_tile_kernel(M, K)) return launch_qgemm_tile(ga, second != nullptr, st);
+  // The 3x3 gather exists in the tiled kernel only: a convolution always goes there.
+  if (conv_c > 0 || use_tile_kernel(M, K)) return launch_qgemm_tile(ga, second != nullptr, st);
   return launch_qgemm_stream(ga, second != nullptr, st);
 }
 
@@ -313,7 +331,7 @@ int32_t moqe_unpack_qmat(const moqe_qmat* p, int16_t* q_minus_z, float* scale_ou
 size_t moqe_grouped_qgemm_workspace_bytes(const moqe_qmat* experts, int32_t K, int32_t S, int32_t T) {
   if (!experts || K < 1 || K > MOQE_MAX_EXPERTS || S < 0 || T <= 0) return 0;
   bool any = false;
-  for (int e = 0; e < K; ++e) any = any || experts[e].act_mode == 1;
+  for (int e = 0; e < K; ++e) any = any || experts[e].act_mode != 0;
   return a8_bytes(any, S * T, experts[0].k);
 }
 
@@ -325,6 +343,8 @@ int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t*
   if (S < 0 || T <= 0 || (long long)S * T > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: S=%d T=%d", S, T);
   GroupedPlan gp;
   int32_t rc = plan_experts(experts, K, nullptr, &gp, "moqe_grouped_qgemm");
+  if (rc) return rc;
+  rc = check_activation_bytes((long long)S * T, experts[0].k, "moqe_grouped_qgemm");
   if (rc) return rc;
   if (S == 0) return MOQE_OK;
   if (!a || !offsets || !y) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: a, offsets or y is NULL");
@@ -344,7 +364,7 @@ int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t*
 // ---- the whole block -----------------------------------------------------------------------
 namespace {
 struct FwdLayout {
-  size_t route, idx, logits, counts, offsets, perm, inv_perm, h, a8, col, total;
+  size_t route, idx, logits, counts, offsets, perm, inv_perm, h, a8, total;
 };
 
 int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedPlan* gp0, GroupedPlan* gp2) {
@@ -374,10 +394,18 @@ int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedP
     if (b->img_h <= 0 || b->img_w <= 0 || b->cin <= 0 || b->img_h * b->img_w != T || b->cin != b->router.d ||
         b->w0[0].k != b->cin * 9 || (b->cin % 8) != 0)
       return set_error(MOQE_E_SHAPE, "moqe_forward: conv needs T = img_h*img_w, cin = router d (a multiple of 8), k = 9*cin");
+    if (gp0->any_a8) return set_error(MOQE_E_FORMAT, "moqe_forward: conv experts take bf16 activations (act_mode 0)");
   } else {
     return set_error(MOQE_E_FORMAT, "moqe_forward: unknown block kind %d", b->kind);
   }
   const size_t M = size_t(S) * T;
+  // every activation matrix a kernel indexes: x itself, and the bf16 intermediate of the MLP
+  rc = check_activation_bytes((long long)M, b->router.d, "moqe_forward");
+  if (rc) return rc;
+  if (b->kind == MOQE_KIND_SILU_MLP) {
+    rc = check_activation_bytes((long long)M, b->w0[0].n, "moqe_forward");
+    if (rc) return rc;
+  }
   size_t o = 0;
   L->route = o;    o += align256(route_ws_bytes(S, T, b->router));
   L->idx = o;      o += align256(size_t(S) * 4);
@@ -395,8 +423,6 @@ int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedP
     if (b->kind == MOQE_KIND_SILU_MLP) kmax = std::max(kmax, b->w2[0].k);
     o += a8_bytes(any, int(M), kmax);
   }
-  L->col = o;
-  if (b->kind == MOQE_KIND_CONV3X3) o += align256(M * size_t(b->cin) * 9 * 2);
   L->total = o;
   return MOQE_OK;
 }
@@ -408,6 +434,11 @@ size_t moqe_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T) {
   if (forward_layout(blk, S, T, &L, &g0, &g2)) return 0;
   return L.total;
 }
+
+namespace {
+int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
+                     const FwdLayout& L, const GroupedPlan& g0, const GroupedPlan& g2, void* workspace, void* stream);
+}  // namespace
 
 int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
                      void* workspace, size_t workspace_bytes, void* stream) {
@@ -421,7 +452,13 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total)
     return set_error(MOQE_E_WORKSPACE, "moqe_forward: workspace needs %zu bytes, 256-byte aligned", L.total);
   if (dry_run()) return MOQE_OK;
+  return forward_body(blk, x, S, T, y, aux, L, g0, g2, workspace, stream);
+}
 
+namespace {
+int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
+                     const FwdLayout& L, const GroupedPlan& g0, const GroupedPlan& g2, void* workspace, void* stream) {
+  int32_t rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
   const int K = blk->n_experts;
@@ -453,15 +490,10 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
     if (rc) return rc;
     return run_grouped(h, offsets, nullptr, perm, S, T, blk->w2, nullptr, K, g2, y, ws + L.a8, st);
   }
-  // CONV3X3 with many rows: the tiled kernel gathers each row's 3x3 neighbourhood from the image itself
-  if (use_tile_kernel((long long)S * T, K) && !g0.any_a8)
-    return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, blk->img_h, blk->img_w, blk->cin);
-  // otherwise: materialise the 3x3 neighbourhoods in image order, then one grouped GEMM
-  void* col = ws + L.col;
-  rc = launch_im2col(x, S, blk->img_h, blk->img_w, blk->cin, col, st);
-  if (rc) return rc;
-  return run_grouped(col, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st);
+  // CONV3X3: the tiled kernel gathers each row's 3x3 neighbourhood from the image itself
+  return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, blk->img_h, blk->img_w, blk->cin);
 }
+}  // namespace
 
 // ---- the whole block, samples of different lengths -------------------------------------------
 namespace {
@@ -489,6 +521,12 @@ int32_t ragged_layout(const moqe_block* b, int S, long long M, RaggedLayout* L, 
     rc = plan_experts(b->w2, K, nullptr, gp2, "moqe_forward_ragged");
     if (rc) return rc;
     if (b->w2[0].k != b->w0[0].n) return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: down takes %d features, gate/up give %d", b->w2[0].k, b->w0[0].n);
+  }
+  rc = check_activation_bytes(M, b->router.d, "moqe_forward_ragged");
+  if (rc) return rc;
+  if (b->kind == MOQE_KIND_SILU_MLP) {
+    rc = check_activation_bytes(M, b->w0[0].n, "moqe_forward_ragged");
+    if (rc) return rc;
   }
   size_t o = 0;
   L->route = o;       o += align256(route_ws_bytes(S, 2, b->router));

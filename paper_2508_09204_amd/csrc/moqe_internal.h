@@ -181,6 +181,12 @@ struct ProfileScope {
 
 int32_t check_launch(const char* what);
 
+// Kernels that need more than 64 KiB of dynamic LDS must ask for it once per kernel: `slot` is a
+// process-wide id of the kernel (LdsKernel); the request is made by the first caller only, under a
+// lock, and every caller gets its outcome.
+enum LdsKernel : int { LDSK_STREAM0 = 0, LDSK_TILE0 = 8, LDSK_ROUTER_TAIL = 12, LDSK_COUNT = 16 };
+int32_t ensure_dynamic_lds(int slot, const void* kernel, int bytes, const char* what);
+
 int32_t launch_route(const void* x, int S, int T, const moqe_router& r, int32_t* idx, float* logits,
                      void* ws, hipStream_t st);
 size_t  route_ws_bytes(int S, int T, const moqe_router& r);
@@ -201,6 +207,5 @@ int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st);
 int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st);
 int32_t launch_act_quant(const void* x_bf16, int kdim, int T, const int32_t* offsets, const int32_t* perm,
                          int expert, int max_rows, int8_t* out, float* scales, hipStream_t st);
-int32_t launch_im2col(const void* x, int S, int H, int W, int C, void* out, hipStream_t st);
 
 }  // namespace moqe

@@ -1,6 +1,6 @@
 // Weight preparation and activation preparation kernels:
 //   round-to-nearest quantizers (canonical layout), canonical <-> packed layout,
-//   per-row dynamic int8 activation quantization (W8A8 expert), im2col for the routed 3x3 conv.
+//   per-row dynamic int8 activation quantization (W8A8 expert).
 // The quantizers use fp32 IEEE operations with explicit rounding intrinsics so that no
 // multiply-add contraction changes a code.
 #include "moqe_internal.h"
@@ -203,34 +203,6 @@ int32_t launch_act_quant(const void* x_bf16, int kdim, int T, const int32_t* off
   hipLaunchKernelGGL(k_act_quant, dim3(max_rows), dim3(256), 0, st, static_cast<const uint16_t*>(x_bf16), kdim, T,
                      offsets, perm, expert, out, scales);
   return check_launch("act_quant");
-}
-
-// ---- im2col for 3x3 / stride 1 / zero pad 1, NHWC input ---------------------------------------
-// out[(s*H*W + y*W + x), (kh*3 + kw)*C + c] = in[s, y+kh-1, x+kw-1, c] (0 outside the image): the
-// filter taps are the slow index and the channels the fast one, like the activations themselves,
-// so the matrix is made of 16-byte copies (8 channels) of input pixels.  One thread per copy.
-__global__ __launch_bounds__(256) void k_im2col(const uint16_t* __restrict__ in, int S, int H, int W, int C,
-                                                 uint16_t* __restrict__ out) {
-  const int cu = C / 8;                                      // 16-byte units per pixel
-  const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
-  if (i >= size_t(S) * H * W * 9 * cu) return;
-  const int c8 = int(i % cu);
-  const int tap = int((i / cu) % 9);
-  const size_t row = i / (size_t(cu) * 9);
-  const int px = int(row % W), py = int((row / W) % H), s = int(row / (size_t(W) * H));
-  const int yy = py + tap / 3 - 1, xx = px + tap % 3 - 1;
-  uint4 v = make_uint4(0u, 0u, 0u, 0u);
-  if (yy >= 0 && yy < H && xx >= 0 && xx < W)
-    v = *reinterpret_cast<const uint4*>(in + ((size_t(s) * H + yy) * W + xx) * C + c8 * 8);
-  *reinterpret_cast<uint4*>(out + row * (size_t(C) * 9) + size_t(tap) * C + c8 * 8) = v;
-}
-
-int32_t launch_im2col(const void* x, int S, int H, int W, int C, void* out, hipStream_t st) {
-  ProfileScope ps(MOQE_PK_IM2COL, st);
-  const size_t n = size_t(S) * H * W * 9 * (C / 8);
-  hipLaunchKernelGGL(k_im2col, dim3(unsigned((n + 255) / 256)), dim3(256), 0, st, static_cast<const uint16_t*>(x), S, H, W, C,
-                     static_cast<uint16_t*>(out));
-  return check_launch("im2col");
 }
 
 }  // namespace moqe

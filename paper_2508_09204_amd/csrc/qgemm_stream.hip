@@ -415,6 +415,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_qgemm_stream(const GemmArgs g
 typedef void (*StreamKernel)(const GemmArgs);
 
 int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
+  // this kernel reads `a` as a plain [rows, k] matrix; an image that still needs its 3x3 gather must not get here
+  if (ga.conv_c != 0) return set_error(MOQE_E_SHAPE, "grouped_qgemm: the streaming kernel cannot gather a convolution's rows");
   const int NT = ga.n / 16, KT = ga.k / 128;
   const int ntasks = gateup ? NT : (NT + 1) / 2;
   GemmArgs a = ga;
@@ -432,14 +434,8 @@ int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
   const int ki = (gateup ? 2 : 0) + (wk == 4 ? 1 : 0);
   static const StreamKernel kernels[4] = {k_qgemm_stream<false, 2>, k_qgemm_stream<false, 4>, k_qgemm_stream<true, 2>,
                                           k_qgemm_stream<true, 4>};
-  // more than 64 KiB of dynamic LDS has to be requested once per kernel
-  static bool lds_ok[4] = {false, false, false, false};
-  if (!lds_ok[ki]) {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[ki]),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: cannot reserve LDS: %s", hipGetErrorString(err));
-    lds_ok[ki] = true;
-  }
+  int32_t rc = ensure_dynamic_lds(LDSK_STREAM0 + ki, reinterpret_cast<const void*>(kernels[ki]), LDS_BYTES, "grouped_qgemm");
+  if (rc) return rc;
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
   hipLaunchKernelGGL(kernels[ki], dim3(grid), dim3(WAVES * 64), lds_bytes, st, a);
   return check_launch("grouped_qgemm");

@@ -397,14 +397,10 @@ int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
   if (grid > 0x7fffffffL) return set_error(MOQE_E_SHAPE, "grouped_qgemm: %d rows exceed the tile kernel's grid", M);
   const bool conv = ga.conv_c > 0;
   const int ki = gateup ? 1 : (conv ? 2 : 0);
-  static bool lds_ok[3] = {false, false, false};
   const void* fns[3] = {reinterpret_cast<const void*>(&k_qgemm_tile<false, false>), reinterpret_cast<const void*>(&k_qgemm_tile<true, false>),
                         reinterpret_cast<const void*>(&k_qgemm_tile<false, true>)};
-  if (!lds_ok[ki]) {
-    hipError_t err = hipFuncSetAttribute(fns[ki], hipFuncAttributeMaxDynamicSharedMemorySize, T_LDS_BYTES);
-    if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: cannot reserve LDS: %s", hipGetErrorString(err));
-    lds_ok[ki] = true;
-  }
+  int32_t rc = ensure_dynamic_lds(LDSK_TILE0 + ki, fns[ki], T_LDS_BYTES, "grouped_qgemm(tile)");
+  if (rc) return rc;
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
   if (gateup) hipLaunchKernelGGL((k_qgemm_tile<true, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
   else if (conv) hipLaunchKernelGGL((k_qgemm_tile<false, true>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);

@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256) void k_pool_ragged(const uint16_t* __restrict_
       acc[2 * j + 1] += bf16_bits_to_float(w[j] >> 16);
     }
   }
-  const float inv = 1.0f / float(r1 - r0);
+  const float inv = r1 > r0 ? 1.0f / float(r1 - r0) : 0.f;      // a sample without rows has all-zero features
   float4 o0 = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
   float4 o1 = {acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv};
   float* dst = pooled + size_t(s) * D + c8 * 8;
@@ -436,13 +436,8 @@ int32_t launch_route_bucket(const void* x, int S, int T, const moqe_router& r, i
     }
     return launch_bucket(idx, S, r.n_experts, counts, offsets, perm, inv_perm, st);
   }
-  static bool lds_ok = false;               // more than 64 KiB of dynamic LDS has to be requested once
-  if (!lds_ok) {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_router_tail),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, TAIL_LDS_BYTES);
-    if (err != hipSuccess) return set_error(MOQE_E_HIP, "route: cannot reserve LDS: %s", hipGetErrorString(err));
-    lds_ok = true;
-  }
+  rc = ensure_dynamic_lds(LDSK_ROUTER_TAIL, reinterpret_cast<const void*>(&k_router_tail), TAIL_LDS_BYTES, "route");
+  if (rc) return rc;
   ProfileScope ps(MOQE_PK_BUCKET, st);
   hipLaunchKernelGGL(k_router_tail, dim3(1), dim3(256), TAIL_LDS_BYTES, st, rf.feat, rf.nslices, rf.stride, r.b1, r.w2,
                      r.b2, S, rf.Dk, r.n_experts, idx, logits, counts, offsets, perm, inv_perm);

@@ -138,13 +138,16 @@ def test_forward_llama_decode_full_size():
 
 
 def _sampled_rows(T):
-    return sorted(set([0, 1, T // 2, T - 2, T - 1]))
+    """First 8 and last 8 token rows of a sequence plus three interior ones: with 64-row tiles that start at
+    multiples of 64 these land in every 16-row block of a tile (positions 0-7, 17, 40, 23 + T/2 and 56-63)."""
+    rows = list(range(8)) + [17, 40, T // 2 + 23] + list(range(T - 8, T))
+    return sorted(set(r for r in rows if 0 <= r < T))
 
 
 @pytest.mark.timeout(1500)
 @pytest.mark.parametrize("name", ["llama7b_mlp_prefill", "qwen_mlp_skew"])
 def test_forward_large_workloads_sampled_rows(name):
-    """Full-size launch; the oracle computes five token rows of every sequence (all columns)."""
+    """Full-size launch; the oracle computes nineteen token rows of every sequence (all columns)."""
     cfg = wl.get_config(name)
     blk = ob.make_block(cfg)
     bits, x64 = ob.activations_f64(cfg)
@@ -182,6 +185,28 @@ def test_forward_large_workloads_sampled_rows(name):
             rms = float(np.sqrt(np.mean(y_e2e * y_e2e)))
             bound = 2e-3 * np.maximum(np.abs(y_e2e), rms) + flip_allowance
             assert np.all(np.abs(y[s][rows] - y_e2e) <= bound), (s, e)
+
+
+@pytest.mark.parametrize("S,hw", [(1, (14, 14)), (4, (14, 14)), (1, (5, 6)), (4, (5, 6))])
+@pytest.mark.parametrize("forced", [0, 1, 2, 3, None])
+def test_forward_conv_few_images(S, hw, forced):
+    """One image per request is the serving mode of Section 4.4: batches of one and four images, every one
+    of the conv workload's four formats (the router is biased to one expert; None = its own routing)."""
+    base = wl.get_config("resnet50_conv")
+    cfg = wl.scaled(base, S=S, T=hw[0] * hw[1], img_h=hw[0], img_w=hw[1])
+    blk = ob.make_block(cfg)
+    if forced is not None:
+        blk.router.b2 = blk.router.b2.copy()
+        blk.router.b2[forced] = 1e4
+    bits, x64 = ob.activations_f64(cfg)
+    y_ref, ref_idx, _ = oc.forward(blk, x64)
+    if forced is not None:
+        assert np.all(ref_idx == forced)
+    y, aux = _forward_gpu(cfg, blk, bits)
+    _check_routing(cfg, aux, ref_idx)
+    ok, worst = ob.tolerance_ok(y, y_ref)
+    assert ok, worst
+    assert worst < 0.05
 
 
 def test_forward_replays_from_a_captured_graph():

@@ -135,6 +135,23 @@ def test_w8a8_integer_accumulators_are_exact():
     assert np.array_equal(y.reshape(S, n).astype(np.int64), ref)
 
 
+@pytest.mark.parametrize("bits,group,sym,clip,act", FORMATS)
+@pytest.mark.parametrize("rows", [7, 29])
+def test_long_rows_per_format(bits, group, sym, clip, act, rows):
+    """k = 8192 (64 steps of 128 columns: the long-row geometry of the few-rows kernel) in every format,
+    one and two 16-row blocks, weight rows that do not fill a work-group."""
+    rng = np.random.default_rng(bits * 19 + group + rows)
+    n, k = 48, 8192
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    qm = oc.quantize(w, bits, group, sym, clip, act)
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((rows, k)).astype(np.float32))
+    e = np.zeros(rows, dtype=np.int32)
+    y = _run(a_bits, e, [qm], rows, 1)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, [qm], rows, 1))
+    assert ok, worst
+    assert worst < 0.05
+
+
 def test_decode_shape_llama_gate_matrix():
     """One decode-shaped problem at full width: 64 rows over 4 experts of an 11008 x 4096 matrix."""
     cfg = wl.get_config("llama7b_mlp_decode")

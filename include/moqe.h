@@ -221,6 +221,20 @@ size_t  moqe_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T);
 int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y,
                      const moqe_aux* aux, void* workspace, size_t workspace_bytes, void* stream);
 
+/* moqe_forward for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same operation, same
+ * kernels and bit-identical results; the scratch memory is a buffer of MOQE_STATIC_SCRATCH_BYTES
+ * built into the library (one per GPU the library runs on, held until the process ends; its
+ * address is looked up once per device on the first call there).  The call allocates and frees
+ * nothing.  Batches whose moqe_workspace_bytes exceeds the buffer are refused with
+ * MOQE_E_WORKSPACE before anything is enqueued (16 MiB holds the decode-shaped workloads, e.g. 64
+ * rows of the LLaMA-7B-shaped block need about 4 MiB).  All calls on one GPU share the buffer:
+ * calls that may overlap in time (different streams, or threads) race on it, so keep them on one
+ * stream or order them yourself.  Nothing in it has to be cleared between calls. */
+#define MOQE_STATIC_SCRATCH_BYTES (16u << 20)
+int32_t moqe_forward_static(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y,
+                            const moqe_aux* aux, void* stream);
+
 /* ---- samples of different lengths ---------------------------------------------------- */
 
 /* The same path for samples that do not all have T rows (sequences of different lengths): x is device

@@ -435,7 +435,33 @@ size_t moqe_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T) {
   return L.total;
 }
 
+// Scratch memory of moqe_forward_static: one array per GPU the library runs on, held until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels
+// get the device address that call returns (kept per device).
+static __device__ __align__(256) uint8_t scratch[MOQE_STATIC_SCRATCH_BYTES];
+
 namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return set_error(MOQE_E_HIP, "moqe_forward_static: hipGetDevice: %s", hipGetErrorString(err));
+  if (dev < 0 || dev >= MAX_DEVICES) return set_error(MOQE_E_HIP, "moqe_forward_static: device %d outside [0, %d)", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || !p)
+      return set_error(MOQE_E_HIP, "moqe_forward_static: address of the built-in scratch buffer: %s", hipGetErrorString(err));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MOQE_OK;
+}
+
 int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
                      const FwdLayout& L, const GroupedPlan& g0, const GroupedPlan& g2, void* workspace, void* stream);
 }  // namespace
@@ -453,6 +479,26 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
     return set_error(MOQE_E_WORKSPACE, "moqe_forward: workspace needs %zu bytes, 256-byte aligned", L.total);
   if (dry_run()) return MOQE_OK;
   return forward_body(blk, x, S, T, y, aux, L, g0, g2, workspace, stream);
+}
+
+int32_t moqe_forward_static(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
+                            void* stream) {
+  FwdLayout L;
+  GroupedPlan g0, g2;
+  int32_t rc = forward_layout(blk, S, T, &L, &g0, &g2);
+  if (rc) return rc;
+  if (L.total > size_t(MOQE_STATIC_SCRATCH_BYTES))
+    return set_error(MOQE_E_WORKSPACE, "moqe_forward_static: this batch needs %zu bytes of scratch, the built-in buffer holds %zu "
+                     "(use moqe_forward with a workspace)", L.total, size_t(MOQE_STATIC_SCRATCH_BYTES));
+  if (S == 0) return MOQE_OK;
+  if (!x || !y) return set_error(MOQE_E_NULL, "moqe_forward_static: x or y is NULL");
+  if (!aligned(x, 16) || !aligned(y, 16)) return set_error(MOQE_E_SHAPE, "moqe_forward_static: x and y must be 16-byte aligned");
+  if (dry_run()) return MOQE_OK;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  // every kernel of the block writes what it later reads, so nothing in the buffer has to start at zero
+  return forward_body(blk, x, S, T, y, aux, L, g0, g2, ws, stream);
 }
 
 namespace {

@@ -166,6 +166,12 @@ def test_route_and_forward_argument_errors(mq):
     assert lib.moqe_forward(C.byref(blk), FAKE, 4, 3, FAKE, None, FAKE, need, None) == 0
     assert lib.moqe_forward(C.byref(blk), FAKE, 4, 3, FAKE, None, FAKE, need - 256, None) == -4
     assert lib.moqe_forward(C.byref(blk), None, 4, 3, FAKE, None, FAKE, need, None) == -1
+    # the variant on the built-in scratch buffer: same checks, and a batch that does not fit is refused
+    assert lib.moqe_forward_static(C.byref(blk), FAKE, 4, 3, FAKE, None, None) == 0
+    assert lib.moqe_forward_static(C.byref(blk), None, 4, 3, FAKE, None, None) == -1
+    assert lib.moqe_workspace_bytes(C.byref(blk), 4096, 8) > (16 << 20)
+    assert lib.moqe_forward_static(C.byref(blk), FAKE, 4096, 8, FAKE, None, None) == -4
+    assert b"built-in" in lib.moqe_last_error_string()
     mixed = (mq._QMat * 2)(_qmat(mq, n=512, k=256, bits=3), _qmat(mq, n=512, k=256, bits=8, group=0, sym=1))
     blk2 = mq._Block(1, r, gate, mixed, down, 2, 0, 0, 0)
     assert lib.moqe_forward(C.byref(blk2), FAKE, 4, 3, FAKE, None, FAKE, need, None) == -3   # gate/up formats differ

@@ -118,15 +118,6 @@ static void fill_expert(const moqe_qmat& m0, const moqe_qmat* m1, const PackedIn
   ex->zero_off = uint32_t(pi.zero_off);
 }
 
-// Heaviest experts first, so the long tasks start early.
-static void order_experts(GemmArgs* ga) {
-  int idx[MOQE_MAX_EXPERTS];
-  for (int i = 0; i < ga->n_experts; ++i) idx[i] = i;
-  std::stable_sort(idx, idx + ga->n_experts,
-                   [&](int a, int b) { return ga->ex[a].tile_bytes > ga->ex[b].tile_bytes; });
-  for (int i = 0; i < ga->n_experts; ++i) ga->order[i] = idx[i];
-}
-
 // Byte offsets into an activation matrix are 32-bit inside the kernels.
 static int32_t check_activation_bytes(long long M, int k, const char* who) {
   if (size_t(M) * size_t(k) * 2 >= (size_t(1) << 32))
@@ -165,10 +156,19 @@ static int32_t plan_experts(const moqe_qmat* experts, int K, const moqe_qmat* se
   return MOQE_OK;
 }
 
-// Buckets of a few rows stream the weights once per launch; buckets of many rows are a dense
-// contraction and take the LDS-tiled kernel (more than 64 rows per expert on average).
-constexpr int TILE_MIN_ROWS_PER_EXPERT = 64;
-static bool use_tile_kernel(long long M, int K) { return M > (long long)TILE_MIN_ROWS_PER_EXPERT * K; }
+// Which kernel an expert's bucket takes.  Buckets of a few rows stream the weights once (bound by HBM);
+// buckets of many rows are a dense contraction and take the LDS-tiled kernel (bound by the matrix cores).
+// The host does not know the bucket sizes, only bounds: every non-empty bucket has a multiple of T rows
+// and at most M.  Where that decides, one kernel is launched; otherwise both are, and each takes, on the
+// device, the experts whose bucket is on its side of STREAM_MAX_ROWS.
+constexpr int STREAM_MAX_ROWS = 32;        // one pass of the streaming kernel
+constexpr int STREAM_ONLY_ROWS = 128;      // up to here even one bucket holding every row streams (4 passes at most)
+enum GemmPath { PATH_STREAM, PATH_TILE, PATH_BOTH };
+static GemmPath choose_path(long long M, int T) {
+  if (T > STREAM_MAX_ROWS) return PATH_TILE;
+  if (M <= STREAM_ONLY_ROWS) return PATH_STREAM;
+  return PATH_BOTH;
+}
 
 // Enqueues one grouped GEMM (plus the int8 row quantization its act_mode-1 experts need).
 static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t* a_perm, const int32_t* y_perm, int S, int T,
@@ -183,7 +183,6 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
   ga.a = a; ga.offsets = offsets; ga.a_perm = a_perm; ga.y_perm = y_perm; ga.y = y;
   ga.conv_h = conv_h; ga.conv_w = conv_w; ga.conv_c = conv_c;
   for (int e = 0; e < K; ++e) fill_expert(experts[e], second ? &second[e] : nullptr, gp.pi[e], &ga.ex[e]);
-  order_experts(&ga);
   const int M = S * T;
   if (gp.any_a8) {
     int8_t* aq = reinterpret_cast<int8_t*>(a8_ws);
@@ -195,11 +194,22 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
       if (rc) return rc;
     }
   }
-  // Buckets of a few rows stream the weights once per launch; buckets of many rows are a dense
-  // contraction and take the LDS-tiled kernel.
   // The 3x3 gather exists in the tiled kernel only: a convolution always goes there.
-  if (conv_c > 0 || use_tile_kernel(M, K)) return launch_qgemm_tile(ga, second != nullptr, st);
-  return launch_qgemm_stream(ga, second != nullptr, st);
+  const GemmPath path = conv_c > 0 ? PATH_TILE : choose_path(M, T);
+  const int32_t all_rows = 0x7fffffff;
+  if (path != PATH_TILE) {
+    ga.min_rows = 1;
+    ga.max_rows = path == PATH_STREAM ? all_rows : STREAM_MAX_ROWS;
+    int32_t rc = (ga.k / 128 <= STREAM_REG_MAX_KT) ? launch_qgemm_stream(ga, second != nullptr, st)
+                                                    : launch_qgemm_stream_lds(ga, second != nullptr, st);
+    if (rc) return rc;
+  }
+  if (path != PATH_STREAM) {
+    ga.min_rows = path == PATH_TILE ? 1 : STREAM_MAX_ROWS + 1;
+    ga.max_rows = all_rows;
+    return launch_qgemm_tile(ga, second != nullptr, st);
+  }
+  return MOQE_OK;
 }
 
 }  // namespace moqe

@@ -149,7 +149,6 @@ struct ExpertDev {
 
 struct GemmArgs {
   ExpertDev ex[MOQE_MAX_EXPERTS];
-  int32_t   order[MOQE_MAX_EXPERTS];   // expert visited by work-group block b (heaviest first)
   int32_t   n_experts;
   int32_t   n, k;                      // per-matrix output / input features
   int32_t   S, T;
@@ -162,8 +161,7 @@ struct GemmArgs {
   void*     y;               // float [M, n] (plain) or bf16 [M, n] (gate/up, bucket order)
   int32_t   conv_h, conv_w, conv_c;   // tiled kernel, 3x3 convolution: a is the NHWC image [S, h, w, c] and the
                              // k = (kh*3 + kw)*c + ch columns of a row are gathered from its pixel's neighbours
-  int32_t   wn, wk;          // work-group geometry: tasks per work-group, k-slices per task
-  int32_t   wg_per_expert;
+  int32_t   min_rows, max_rows;   // this launch handles the experts whose bucket has min_rows .. max_rows rows
 };
 
 // ---------------------------------------------------------------------------------------
@@ -203,7 +201,12 @@ int32_t launch_balance_stats(const float* logits, const int32_t* counts, int S, 
 int32_t launch_quantize(const float* w, float clip, const moqe_qmat& out, hipStream_t st);
 int32_t launch_pack(const moqe_qmat& c, const PackedInfo& pi, uint8_t* out, hipStream_t st);
 int32_t launch_unpack(const moqe_qmat& p, const PackedInfo& pi, int16_t* out, float* scale_out, hipStream_t st);
+// Two streaming kernels for buckets of a few rows: activations resident in registers (rows of up to
+// STREAM_REG_MAX_KT k-tiles of 128 columns, which one phase of that kernel covers), activations marching
+// through LDS (longer rows).
+constexpr int STREAM_REG_MAX_KT = 32;
 int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st);
+int32_t launch_qgemm_stream_lds(const GemmArgs& ga, bool gateup, hipStream_t st);
 int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st);
 int32_t launch_act_quant(const void* x_bf16, int kdim, int T, const int32_t* offsets, const int32_t* perm,
                          int expert, int max_rows, int8_t* out, float* scales, hipStream_t st);

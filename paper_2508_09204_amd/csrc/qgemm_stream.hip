@@ -1,443 +1,652 @@
-// Grouped dequantize-GEMM, weight-streaming kernel.
+// Grouped dequantize-GEMM, weight-streaming kernel for buckets of a few rows (decode).
 //
 // Each sample is processed by its selected expert only (MoQE Section 3.1), so for expert e the
-// rows of its bucket (a few rows in decode) meet the whole weight matrix of that expert: the
-// work is bound by reading packed weights once.  One wavefront owns two 16-row weight tiles
-// (gate and up tile of the same rows for the SiLU-gated pair, two neighbouring tiles
-// otherwise) and streams them along k with several tiles in flight; the lanes' packed codes
-// are already ordered as matrix-core operands, so a tile goes
-//     16-byte load -> a handful of bit operations -> bf16 MFMA
-// with no shuffles, and the weights never touch LDS (only the few activation rows are staged there,
-// once per work-group).  Integer codes enter the matrix cores exactly, as the bf16
-// value BASE + c/2 (or c for 8-bit codes), i.e. with a constant offset; a second MFMA against an all-ones operand
-// gives the row sums of the activations over the same columns, which removes offset and
-// zero-point exactly: sum_k x (off + c) - (off + z) sum_k x.  The fp32 scale multiplies the
-// fp32 partial sum of each group, so no weight is ever rounded.
+// few rows of its bucket meet the whole weight matrix of that expert: the work is bound by
+// reading the packed weights once, and everything else is arranged so that nothing but weights
+// moves in the inner loop.
+//
+//  * One work-group (8 waves) per compute unit, resident for the whole launch.  The work-groups
+//    are dealt to the experts in proportion to the bytes each expert has to stream (its tile size
+//    times the passes its bucket needs), and an expert's 16-row weight tiles are split evenly among
+//    its work-groups; every work-group computes this deal itself from the bucket offsets.
+//  * The activations stay in REGISTERS: the k range is cut across the 8 waves (4 k-tiles of 128
+//    columns per wave and phase; rows longer than 32 k-tiles take several phases), and a wave loads
+//    its slice of the bucket's rows once, already shaped as matrix-core operands.  It then streams
+//    the matching 4-tile piece of every weight tile row of the work-group (4 KiB contiguous for
+//    4-bit codes), a piece or two ahead, through 16-byte load -> a few bit operations -> bf16 MFMA.
+//    No LDS traffic and no barrier sits between a weight load and its MFMA.
+//  * Integer codes enter the matrix cores exactly as the bf16 value BASE + c/2 (or c for 8-bit
+//    codes).  The offset and the zero-point are removed exactly: for group formats by ONE fp32
+//    matrix-core operation per weight tile row, row sums of the activations (kept as its A operand,
+//    one register) times -scale*(BASE + z/2) (its B operand); for per-channel formats by the wave's
+//    row sum once per tile row.  The fp32 scale multiplies the fp32 partial sum of each group, so no
+//    weight is ever rounded.
+//  * The 8 partial sums of a tile row (one per k slice) are added in wave order through LDS, a
+//    batch of tile rows per barrier, by waves that take turns; with several phases the running sums
+//    wait in LDS.  Then the epilogue: fp32 rows scattered through the permutation, or
+//    bf16(silu(gate) * up).  Every sum has a fixed order: results do not depend on scheduling.
 #include "qgemm_device.h"
+
+#include <mutex>
 
 namespace moqe {
 
-constexpr int NS = 2;        // weight tiles (streams) per wave
-constexpr int MT = 2;        // 16-row activation tiles per pass (32 bucket rows)
+constexpr int SW = 8;                      // waves per work-group
+constexpr int KPW = 4;                     // k-tiles (128 columns) a wave keeps as register operands
+constexpr int PHASE_KT = SW * KPW;         // k-tiles a work-group covers per phase
+static_assert(PHASE_KT == STREAM_REG_MAX_KT, "rows of more k-tiles take several phases here and are sent to the other streaming kernel");
+constexpr int STREAM_ROWS = 32;            // bucket rows per pass (two 16-row blocks)
+constexpr int BMT = 4;                     // (tile rows per batch) x (16-row blocks): results exchanged per barrier
+constexpr int PART_BYTES = 2 * BMT * SW * 64 * 16;     // two buffers of per-wave partial sums
+constexpr int TOT_BATCHES = 8;             // batches whose running sums are kept between phases
+constexpr int TOT_BYTES = TOT_BATCHES * BMT * 64 * 16;
+constexpr int STREAM_LDS_BYTES = PART_BYTES + TOT_BYTES;
 
-// Work-group geometry: 8 waves = WN tasks x WK k-slices (WK = 2 or 4, chosen per launch).  A task is a pair
-// of weight tiles; slice ks of a task covers the k-tiles [ks*ceil(KT/WK), ...).  The activation
-// rows of the pass (at most 32) are staged in LDS in chunks of CH = 8/WK k-tiles per slice,
-// double-buffered, and shared by all waves, so activations cross the L2 once per work-group
-// instead of once per wave and the work-group meets at a barrier once per chunk only: while a
-// chunk is multiplied, each step copies one k-tile of the next chunk into the other buffer.
-// Inside the tile loop every global load is unconditional (addresses are clamped, unused data is
-// masked), which lets the compiler keep the whole prefetch ring in flight instead of draining
-// it at control-flow joins.
-constexpr int ROWS = 16 * MT;                 // bucket rows per pass
-constexpr int WAVES = 8;                      // waves per work-group
-constexpr int A_SLOT = 256;                   // LDS bytes per staged row and k-tile (int8 rows use half)
+// ---- which expert and which of its weight tiles a work-group streams ---------------------------------
+struct StreamSeg {
+  int e, u0, u1;          // expert and its weight tiles [u0, u1) for this work-group
+  int off_e, rows_e;      // first sample of the expert's bucket, rows in it
+  ExpertDev ex;           // the expert's descriptor, uniform over the work-group
+};
 
-// A staged row is 16 units of 16 bytes; unit u of row r is stored at position u ^ (r & 15), which
-// keeps the 16-byte-per-lane operand reads (16 rows x 4 units per instruction) free of bank conflicts.
-static __device__ __forceinline__ int a_unit_pos(int row, int unit) { return (unit ^ (row & 15)) * 16; }
+// Units are 16-row weight tiles (gate/up: the gate tile and the up tile of the same 16 features).  The cost of
+// an expert's unit is its tile bytes times the passes over its bucket; work-groups are dealt in proportion:
+// the floor of each expert's share, then the work-groups left over one at a time to the expert whose
+// work-groups carry the most.  Lane e of every 16-lane row holds expert e and the sums are cross-lane
+// reductions, so the deal costs a few dozen instructions; every work-group runs the same arithmetic on the
+// same inputs and gets the same deal.
+static __device__ __forceinline__ int row16_sum(int v) {
+#pragma unroll
+  for (int m = 1; m < 16; m <<= 1) v += __shfl_xor(v, m, 16);
+  return v;
+}
+static __device__ __forceinline__ int row16_max(int v) {
+#pragma unroll
+  for (int m = 1; m < 16; m <<= 1) v = max(v, __shfl_xor(v, m, 16));
+  return v;
+}
 
-// LDS bytes: two buffers of (WK slices x CH k-tiles = 8) x ROWS rows; the k-slice reduction reuses them.
-static constexpr int LDS_BYTES = 2 * 8 * ROWS * A_SLOT;
+static __device__ __forceinline__ uint32_t uni(uint32_t v) { return uint32_t(__builtin_amdgcn_readfirstlane(int(v))); }
 
-template <int FMT, int GM, bool GATEUP, int WK>
-static __device__ __forceinline__ void stream_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int wgi,
-                                                   uint8_t* lds) {
+// Lane e (of every 16-lane row) fetches bucket e's bounds and expert e's descriptor, all in one round trip:
+// the kernel arguments live in memory that is slow to touch for the first time, and a chain of dependent
+// reads there would cost microseconds before the first weight is requested.
+static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, const int wg, const int G) {
+  const int K = ga.n_experts, NU = ga.n >> 4;
+  const int e = threadIdx.x & 15;
+  const int el_safe = e < K ? e : 0;
+  const int o0 = ga.offsets[el_safe], o1 = ga.offsets[el_safe + 1];
+  const ExpertDev mine_ex = ga.ex[el_safe];                        // per-lane copy (vector loads from the argument block)
+  const int rows = e < K ? (o1 - o0) * ga.T : 0;
+  const bool mine = rows >= ga.min_rows && rows <= ga.max_rows && rows > 0;
+  // Relative time of one weight tile row: mostly its bytes, plus what unpacking costs (measured per format on
+  // MI355X), a little more when the bucket needs both 16-row blocks; times the passes over the bucket.
+  const int f = mine_ex.fmt;
+  const int per_tile = f == FMT_I8 ? 28 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 26 : (f == FMT_N4 ? 20 : 23)));
+  const int passes = (rows + STREAM_ROWS - 1) / STREAM_ROWS;
+  const int last = rows - (passes - 1) * STREAM_ROWS;              // rows of the last pass
+  const int eighths = (passes - 1) * 9 + (last > 16 ? 9 : 8);      // a pass with two blocks counts 9/8
+  const int cost = mine ? per_tile * eighths : 0;                  // small integers
+  const int total = row16_sum(cost);
+  StreamSeg sg;
+  sg.e = -1; sg.u0 = 0; sg.u1 = 0; sg.off_e = 0; sg.rows_e = 0;
+  if (total <= 0) return sg;
+  int g = cost > 0 ? max(1, min(NU, int((long long)cost * G / total))) : 0;
+  int sum = row16_sum(g);
+  // more than G (tiny shares rounded up to one): take from the largest
+  for (int it = 0; it < MOQE_MAX_EXPERTS && sum > G; ++it) {
+    const int top = row16_max((g << 4) | (15 - e));                // ties: the lowest expert index
+    const int cut = min(sum - G, (top >> 4) - 1);
+    if (cut <= 0) break;
+    if ((15 - (top & 15)) == e) g -= cut;
+    sum -= cut;
+  }
+  // work-groups left over go, one at a time, to the expert whose work-groups carry the most
+  for (int it = 0; it < MOQE_MAX_EXPERTS && sum < G; ++it) {
+    const float load = (g > 0 && g < NU) ? float(cost) / float(g) : 0.f;
+    const int key = (__float_as_int(load) & ~15) | (15 - e);       // positive floats order like their bit patterns
+    const int top = row16_max(key);
+    if ((top & ~15) == 0) break;                                   // nobody can take more
+    if ((15 - (top & 15)) == e) g += 1;
+    sum += 1;
+  }
+  // first work-group of each expert: exclusive prefix sum over the lanes of the row
+  int first = g;
+#pragma unroll
+  for (int m = 1; m < 16; m <<= 1) {
+    const int o = __shfl_up(first, m, 16);
+    if (e >= m) first += o;
+  }
+  first -= g;
+  const bool here = g > 0 && wg >= first && wg < first + g;
+  const unsigned long long who = __ballot(here) & 0xffffull;       // row 0 of the wave; at most one lane
+  if (who == 0ull) return sg;
+  const int el = __ffsll(who) - 1;
+  const int ge = __shfl(g, el, 64), fe = __shfl(first, el, 64);
+  const unsigned i = unsigned(wg - fe);
+  sg.e = el;
+  sg.u0 = int(i * unsigned(NU) / unsigned(ge));                    // i < G and NU < 2^20: the products fit 32 bits
+  sg.u1 = int((i + 1u) * unsigned(NU) / unsigned(ge));
+  sg.off_e = __shfl(o0, el, 64);
+  sg.rows_e = __shfl(rows, el, 64);
+  // the chosen expert's descriptor, broadcast from its lane and made uniform
+  const uint64_t w0 = reinterpret_cast<uint64_t>(mine_ex.w[0]), w1 = reinterpret_cast<uint64_t>(mine_ex.w[1]);
+  const uint64_t w0u = (uint64_t(uni(__shfl(uint32_t(w0 >> 32), el, 64))) << 32) | uni(__shfl(uint32_t(w0), el, 64));
+  const uint64_t w1u = (uint64_t(uni(__shfl(uint32_t(w1 >> 32), el, 64))) << 32) | uni(__shfl(uint32_t(w1), el, 64));
+  sg.ex.w[0] = reinterpret_cast<const uint8_t*>(w0u);
+  sg.ex.w[1] = reinterpret_cast<const uint8_t*>(w1u);
+  sg.ex.fmt = int(uni(__shfl(uint32_t(mine_ex.fmt), el, 64)));
+  sg.ex.gm = int(uni(__shfl(uint32_t(mine_ex.gm), el, 64)));
+  sg.ex.zc = int(uni(__shfl(uint32_t(mine_ex.zc), el, 64)));
+  sg.ex.asym = int(uni(__shfl(uint32_t(mine_ex.asym), el, 64)));
+  sg.ex.tile_bytes = uni(__shfl(mine_ex.tile_bytes, el, 64));
+  sg.ex.scale_off = uni(__shfl(mine_ex.scale_off, el, 64));
+  sg.ex.zero_off = uni(__shfl(mine_ex.zero_off, el, 64));
+  return sg;
+}
+
+static __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+static __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+static __device__ __forceinline__ float sum8(const u32x4& a) {
+  return ((bf16_lo(a.x) + bf16_hi(a.x)) + (bf16_lo(a.y) + bf16_hi(a.y))) +
+         ((bf16_lo(a.z) + bf16_hi(a.z)) + (bf16_lo(a.w) + bf16_hi(a.w)));
+}
+template <typename V> static __device__ __forceinline__ V pick4(int q, V a, V b, V c, V d) {
+  return q == 0 ? a : (q == 1 ? b : (q == 2 ? c : d));
+}
+
+// One pass (at most 32 bucket rows, MT blocks of 16) of one expert's weight tiles [u0, u1).
+template <int FMT, int GM, bool GATEUP, int MT>
+static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const ExpertDev& ex, const int off_e, const int u0,
+                                                   const int u1, const int pass0, const int rows_here, uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
-  // tiles in flight per stream (a deeper ring was measured and bought nothing)
-  constexpr int PF = 2;
-  constexpr int CH = 8 / WK;                  // k-tiles per staged chunk and slice
-  constexpr int U = PF > CH ? PF : CH;        // steps per loop iteration: ring slot and chunk position are static
-  static_assert(U % PF == 0 && U % CH == 0, "the unrolled loop indexes the prefetch ring and the chunk statically");
   constexpr int NR = Raw<FMT>::N;
   constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
-  constexpr int EB = A8 ? 1 : 2;              // bytes per activation element
-  constexpr int nthreads = WAVES * 64;
-  const int tid = threadIdx.x;
-  // the wave index is uniform over the wave: telling the compiler so keeps everything derived
-  // from it (task, k-slice, tile addresses) in scalar registers
-  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int lr = lane & 15, lq = lane >> 4;
-  const int KT = ga.k >> 7, NT = ga.n >> 4;
-  const int T = ga.T;
-  constexpr int wk = WK;
-  constexpr int WN = WAVES / WK;                // tasks per work-group
-  const int off_e = ga.offsets[e];
-  const int M_e = (ga.offsets[e + 1] - off_e) * T;
-  if (M_e <= 0) return;                       // uniform over the work-group (one expert per work-group)
-
-  const int ks = wave % wk;
-  const int task = wgi * WN + wave / wk;
-  const int ntasks = GATEUP ? NT : (NT + 1) / 2;
-  const bool active_task = task < ntasks;
-
-  int nt[NS];
-  bool sv[NS];
-  const uint8_t* blob[NS];
-  if constexpr (GATEUP) {
-    nt[0] = nt[1] = task; sv[0] = sv[1] = active_task;
-    blob[0] = ex.w[0]; blob[1] = ex.w[1];
-  } else {
-    nt[0] = 2 * task; nt[1] = 2 * task + 1;
-    sv[0] = active_task && nt[0] < NT; sv[1] = active_task && nt[1] < NT;
-    blob[0] = blob[1] = ex.w[0];
-  }
-  const int slice_tiles = (KT + wk - 1) / wk;              // k-tiles per slice (last slice may be shorter)
-  const int kt0 = ks * slice_tiles, kt1 = min(KT, kt0 + slice_tiles);
-  constexpr int KC = 128;                                  // columns staged per slice and step
-  constexpr int buf_bytes = wk * CH * ROWS * A_SLOT;
-  // streams without a tile of their own (odd tile count, padding tasks) and waves whose slice is
-  // empty still run the loop on clamped addresses; their results are never stored
-  const int nt_ld[NS] = {sv[0] ? nt[0] : 0, sv[1] ? nt[1] : 0};
-  const int kt_last = max(kt0, kt1 - 1) < KT ? max(kt0, kt1 - 1) : KT - 1;
-
-  // sum_k x (c - z) = (1/CM) * (sum_k x (BASE + CM c) - (BASE + CM z) sum_k x)
+  constexpr int GP1 = GPT ? GPT : 1;
+  constexpr int B = BMT / MT;                          // tile rows per batch
+  // Tile rows in flight (the one being multiplied and those behind it): as many as the registers allow, a
+  // budget of 24 registers of codes and group parameters per k-tile for one 16-row block, 12 for two.
+  constexpr int RING_REGS = NR + (GM == GM_PC ? 0 : (GM == GM_G128 ? 2 : 3));
+  constexpr int D_FIT = (MT == 1 ? 24 : 12) / RING_REGS;
+  constexpr int D = D_FIT >= 4 && B % 4 == 0 ? 4 : (D_FIT >= 2 ? 2 : 1);
+  constexpr int AJ = A8 ? 2 : 4;                        // matrix-core steps per k-tile
   constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
+  static_assert(B % D == 0 && (!GATEUP || B % 2 == 0), "ring slot and gate/up pairing are static inside a batch");
+  static_assert(KPW == 4, "a wave's k-tiles map onto the four k positions of the fp32 matrix-core operation");
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lr = lane & 15, lq = lane >> 4;
+  const int KT = ga.k >> 7, T = ga.T;
+  const int P = (KT + PHASE_KT - 1) / PHASE_KT;         // phases
+  const int ntr_all = (u1 - u0) * (GATEUP ? 2 : 1);     // weight tile rows of this work-group
+  const int sb_rows = P > 1 ? TOT_BATCHES * B : ntr_all;        // tile rows whose running sums fit in LDS
   const float off_sym = BASE + CM * float(ex.zc);
   const FragK<FMT> fk = frag_constants<FMT>();
-  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-  const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-  // ---- staging plan: which 16-byte units of a chunk this thread copies -----------------------
-  constexpr int upr = KC * EB / 16;                        // units per row
-  constexpr int n_units = wk * ROWS * upr;
-  constexpr int AU_MAX = n_units >= nthreads ? n_units / nthreads : 1;   // 16-byte units per thread and step
-  static_assert(n_units % nthreads == 0 || n_units * 2 == nthreads, "whole units per thread, or half the threads idle");
-  constexpr bool ALL_STAGE = n_units >= nthreads;          // false: only the lower half of the threads stages
+  const uint32_t zp_shift = 8u * uint32_t((lr * GPT) & 3);      // position of the lane's zero-point(s) in their dword
 
-  for (int pass0 = 0; pass0 < M_e; pass0 += ROWS) {
-    const int rows_here = min(ROWS, M_e - pass0);
-    // Per staged unit: byte offset of its step-0 source from the activation base, and the largest
-    // step offset that stays inside the unit's slice.  Nothing is zero-filled: rows past the end of
-    // the bucket repeat its last row (their products land in result rows that are never stored), and
-    // steps past the end of a slice re-read its last tile and are not multiplied.
-    const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
-    uint32_t uoff[AU_MAX];
-    int ukend[AU_MAX];
+  uint8_t* part = lds;                                  // [2][B][SW][MT][64] x 16 bytes
+  uint8_t* totl = lds + PART_BYTES;                     // [TOT_BATCHES][BMT][64] x 16 bytes
+
+  // ---- rows of this pass ---------------------------------------------------------------------------------
+  // operand rows: lane (lr, lq) feeds row mt*16 + lr of the pass; result rows: register r of lane (lr, lq) is
+  // row mt*16 + 4 lq + r.  Rows past the end repeat the last one and are never stored.
+  // The rows' gather / scatter indices and activation scales.
+  const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
+  int a_src[MT];                // sample of operand row mt*16 + lr (its gather index), before the row offset inside the sample
+  int a_m[MT];
 #pragma unroll
-    for (int i = 0; i < AU_MAX; ++i) {
-      const int u = tid + i * nthreads;
-      uoff[i] = 0u; ukend[i] = 0;
-      if (ALL_STAGE || u < n_units) {
-        const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
-        const int sk0 = min(sl * slice_tiles, KT - 1), sk1 = min(KT, sl * slice_tiles + slice_tiles);
-        const int m = pass0 + min(row, rows_here - 1);
-        size_t src;
-        if constexpr (A8) src = size_t(off_e) * T + m;
-        else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
-        else src = size_t(off_e) * T + m;
-        uoff[i] = uint32_t((src * size_t(ga.k) + size_t(sk0) * 128) * EB + cu * 16);
-        ukend[i] = max(sk1 - sk0 - 1, 0) * 128 * EB;      // offset of the slice's last tile
-      }
+  for (int mt = 0; mt < MT; ++mt) {
+    a_m[mt] = pass0 + min(mt * 16 + lr, rows_here - 1);
+    a_src[mt] = off_e + a_m[mt] / T;
+    if (!A8 && ga.a_perm) a_src[mt] = ga.a_perm[a_src[mt]];
+  }
+  int out_row[MT][4];           // destination row of each result register
+  float sx[MT][4];              // W8A8: activation scale of each result row
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int m = pass0 + min(mt * 16 + lq * 4 + r, rows_here - 1);
+      const int brow = off_e * T + m;
+      int dsmp = off_e + m / T;
+      if (!GATEUP && ga.y_perm) dsmp = ga.y_perm[dsmp];
+      out_row[mt][r] = dsmp;                                       // turned into a row index after the ring's first row
+      sx[mt][r] = 1.f;
+      if constexpr (A8) sx[mt][r] = ga.a_scale[brow];
     }
-    u32x4 areg[AU_MAX];
-    auto a_fetch = [&](int c) {       // global -> registers, k-tile c of every slice
-      const int koff = c * KC * EB;
-#pragma unroll
-      for (int i = 0; i < AU_MAX; ++i)
-        areg[i] = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + min(koff, ukend[i]));
-    };
-    auto a_store = [&](uint8_t* dst) {     // registers -> LDS; dst = buffer + k-tile position inside the chunk
-#pragma unroll
-      for (int i = 0; i < AU_MAX; ++i) {
-        const int u = tid + i * nthreads;
-        const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
-        if (ALL_STAGE || u < n_units)
-          *reinterpret_cast<u32x4*>(dst + (sl * CH * ROWS + row) * A_SLOT + a_unit_pos(row, cu)) = areg[i];
-      }
-    };
+  size_t a_row_off[MT];
 
-    f32x4 tot[NS][MT];     // bf16 path: fp32 results; int8 path: int32 bit patterns
-    f32x4 xs_tot[MT];      // per-channel formats: running row sums of the activations
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      xs_tot[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int s = 0; s < NS; ++s) tot[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // ---- weight ring -----------------------------------------------------------------------------------------
+  // The work-group walks its tile rows in one fixed sequence: for each super-batch, for each phase, the rows of
+  // the super-batch padded to whole batches (a padding row repeats the last row's tiles and is not multiplied).
+  // The ring holds D consecutive rows of that sequence, KPW tiles each; tile (row, t) is requested again, for
+  // the row D places further on, right after its matrix-core operations, so KPW * D - 1 tiles are in flight
+  // behind the one being multiplied, across batch and phase boundaries alike.  `cur` is the next row to request.
+  uint32_t raw[D][KPW][NR];
+  float sc[D][KPW][GP1];                                // group scales; per-channel formats: [0] of tile 0 is the row's scale
+  uint32_t zp[D][KPW];
+  const uint32_t tile_bytes = ex.tile_bytes, scale_off = ex.scale_off, zero_off = ex.zero_off;
+  const uint8_t* const blob0 = ex.w[0];
+  const uint8_t* const blob1 = ex.w[GATEUP ? 1 : 0];
+  int cur_sb0 = 0, cur_ph = 0, cur_i = 0;               // position in the sequence
+  int cur_ntr = min(sb_rows, ntr_all);
+  // derived from the position: which blob, first tile index of the row's KPW tiles, last valid tile offset, tile row
+  const uint8_t* cur_blob = blob0;
+  uint32_t cur_t0 = 0u;
+  int cur_tmax = 0, cur_nt = u0;
+  auto cur_derive = [&]() {
+    const int i = cur_sb0 + min(cur_i, cur_ntr - 1);
+    cur_nt = GATEUP ? u0 + (i >> 1) : u0 + i;
+    cur_blob = (GATEUP && (i & 1)) ? blob1 : blob0;
+    const int ktw0 = cur_ph * PHASE_KT + wave * KPW;
+    cur_tmax = max(min(KPW, KT - ktw0) - 1, 0);          // tiles the wave does not have repeat its last one (or the row's last)
+    cur_t0 = uint32_t(cur_nt) * uint32_t(KT) + uint32_t(min(ktw0, KT - 1));
+  };
+  auto cur_advance = [&]() {
+    const int padded = (cur_ntr + B - 1) / B * B;
+    if (cur_i + 1 < padded) {
+      cur_i += 1;
+    } else if (cur_ph + 1 < P) {
+      cur_i = 0; cur_ph += 1;
+    } else if (cur_sb0 + sb_rows < ntr_all) {
+      cur_i = 0; cur_ph = 0; cur_sb0 += sb_rows; cur_ntr = min(sb_rows, ntr_all - cur_sb0);
+    }                                                    // else: past the end, the last row is requested again
+    cur_derive();
+  };
+  auto issue_tile = [&](int d, int t) {                  // d, t are compile-time constants at every call
+    const uint32_t tl = cur_t0 + uint32_t(min(t, cur_tmax));
+    load_raw<FMT>(raw[d][t], cur_blob + size_t(tl) * tile_bytes, lane);
+    if constexpr (GPT > 0) {
+      const uint8_t* sp = cur_blob + scale_off + size_t(tl) * (16 * GPT * 4) + lr * (GPT * 4);
+      // zero-points: the aligned dword that holds the lane's byte(s); shifted down where it is used (a
+      // narrower load would get its zero-extension placed right behind the load, which waits for the ring)
+      const uint8_t* zq = cur_blob + zero_off + size_t(tl) * (16 * GPT) + ((lr * GPT) & ~3);
+      zp[d][t] = *reinterpret_cast<const uint32_t*>(zq);
+      if constexpr (GPT == 1) {
+        sc[d][t][0] = *reinterpret_cast<const float*>(sp);
+      } else {
+        const float2 v = *reinterpret_cast<const float2*>(sp);
+        sc[d][t][0] = v.x; sc[d][t][GP1 - 1] = v.y;
+      }
+    } else {
+      zp[d][t] = 0u;
+      sc[d][t][0] = 1.f;
+      if (t == 0) sc[d][t][0] = reinterpret_cast<const float*>(cur_blob + scale_off)[cur_nt * 16 + lr];
     }
-
-    uint32_t raw[PF][NS][NR];
-    float sc[PF][NS][GPT ? GPT : 1];
-    uint32_t zp[PF][NS];
-
-    auto issue_w = [&](int p, int kt_want) {
-      const int kt = min(kt_want, kt_last);
+  };
+  // ---- this wave's slice of the activations, as matrix-core operands ---------------------------------------------
+  u32x4 areg[KPW][AJ][MT];
+  auto load_a = [&](int ph) {
+    const int ktw0 = ph * PHASE_KT + wave * KPW;
+    const int nkt = max(0, min(KPW, KT - ktw0));
 #pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        const size_t t = size_t(nt_ld[s]) * KT + kt;
-        load_raw<FMT>(raw[p][s], blob[s] + t * ex.tile_bytes, lane);
-        if constexpr (GPT > 0) {          // group formats are asymmetric: scale and zero-point per group
-          const float* sp = reinterpret_cast<const float*>(blob[s] + ex.scale_off) + (t * 16 + lr) * GPT;
-          const uint8_t* zq = blob[s] + ex.zero_off + (t * 16 + lr) * GPT;
-          if constexpr (GPT == 1) {
-            sc[p][s][0] = sp[0];
-            zp[p][s] = uint32_t(zq[0]);
-          } else {
-            float2 v = *reinterpret_cast<const float2*>(sp);
-            sc[p][s][0] = v.x; sc[p][s][1] = v.y;
-            zp[p][s] = uint32_t(*reinterpret_cast<const uint16_t*>(zq));
-          }
-        }
-      }
-    };
-
-    // One k-tile: activation operands come from LDS (tile `tl` of the current chunk buffer).
-    auto consume = [&](int p, const uint8_t* abuf) {
-      const uint8_t* arow0 = abuf + (ks * CH * ROWS + lr) * A_SLOT;      // row lr: unit u sits at (u ^ lr) * 16
-      if constexpr (A8) {
+    for (int t = 0; t < KPW; ++t)
+#pragma unroll
+      for (int j = 0; j < AJ; ++j)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          if (mt * 16 < rows_here) {
-            i32x4 a0 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * A_SLOT + ((lq ^ lr) * 16));
-            i32x4 a1 = *reinterpret_cast<const i32x4*>(arow0 + mt * 16 * A_SLOT + (((4 + lq) ^ lr) * 16));
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-              i32x4 acc = __builtin_bit_cast(i32x4, tot[s][mt]);
-              i32x4 b0 = {int(raw[p][s][0]), int(raw[p][s][1]), int(raw[p][s][2]), int(raw[p][s][3])};
-              i32x4 b1 = {int(raw[p][s][4]), int(raw[p][s][5]), int(raw[p][s][6]), int(raw[p][s][7])};
-              acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, acc, 0, 0, 0);
-              acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, acc, 0, 0, 0);
-              tot[s][mt] = __builtin_bit_cast(f32x4, acc);
-            }
+          areg[t][j][mt] = u32x4{0u, 0u, 0u, 0u};
+          if (t < nkt) {                                         // uniform over the wave
+            const size_t col = A8 ? size_t(ktw0 + t) * 128 + j * 64 + lq * 16 : (size_t(ktw0 + t) * 128 + j * 32 + lq * 8) * 2;
+            areg[t][j][mt] = *reinterpret_cast<const u32x4*>(abase + a_row_off[mt] + col);
           }
         }
-      } else {
-        // Operands of the activations are read from LDS where they are used (once per weight
-        // stream) instead of being held for the whole tile: LDS has bandwidth to spare, registers
-        // are what limits the depth of the weight prefetch.
-        auto a_op = [&](int mt, int j) {
-          return *reinterpret_cast<const u32x4*>(arow0 + mt * 16 * A_SLOT + (((j * 4 + lq) ^ lr) * 16));
-        };
-        f32x4 xs[MT][GPT ? GPT : 1];
+  };
+
+  // The activations of the first phase are requested before any weight: a compute unit serves its requests
+  // in order, and once the 8 waves have filled its queues with ring loads (misses to HBM), a load that hits
+  // in L2 issued behind them would still wait for them all.
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-          const bf16x8 b0 = frag<FMT, 0>(raw[p][s], fk);
-          const bf16x8 b1 = frag<FMT, 1>(raw[p][s], fk);
-          const bf16x8 b2 = frag<FMT, 2>(raw[p][s], fk);
-          const bf16x8 b3 = frag<FMT, 3>(raw[p][s], fk);
+  for (int mt = 0; mt < MT; ++mt) {
+    a_row_off[mt] = (size_t(a_src[mt]) * T + size_t(a_m[mt] % T)) * size_t(ga.k) * (A8 ? 1 : 2);
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            if (mt * 16 < rows_here) {
-              const u32x4 a0 = a_op(mt, 0), a1 = a_op(mt, 1), a2 = a_op(mt, 2), a3 = a_op(mt, 3);
-              const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-              if (s == 0) {                 // row sums of the activations over the tile's groups, once per tile
-                if constexpr (GM == GM_PC) {
-                  xs_tot[mt] = mfma_bf16(a0, ones_b, xs_tot[mt]);
-                  xs_tot[mt] = mfma_bf16(a1, ones_b, xs_tot[mt]);
-                  xs_tot[mt] = mfma_bf16(a2, ones_b, xs_tot[mt]);
-                  xs_tot[mt] = mfma_bf16(a3, ones_b, xs_tot[mt]);
-                } else if constexpr (GM == GM_G128) {
-                  f32x4 v = mfma_bf16(a0, ones_b, zero);
-                  v = mfma_bf16(a1, ones_b, v);
-                  v = mfma_bf16(a2, ones_b, v);
-                  xs[mt][0] = mfma_bf16(a3, ones_b, v);
-                } else {
-                  xs[mt][0] = mfma_bf16(a1, ones_b, mfma_bf16(a0, ones_b, zero));
-                  xs[mt][GPT == 2 ? 1 : 0] = mfma_bf16(a3, ones_b, mfma_bf16(a2, ones_b, zero));
-                }
-              }
-              if constexpr (GM == GM_PC) {
-                f32x4 v = tot[s][mt];
-                v = mfma_bf16(a0, b0, v);
-                v = mfma_bf16(a1, b1, v);
-                v = mfma_bf16(a2, b2, v);
-                v = mfma_bf16(a3, b3, v);
-                tot[s][mt] = v;
-              } else if constexpr (GM == GM_G128) {
-                f32x4 v = mfma_bf16(a0, b0, zero);
-                v = mfma_bf16(a1, b1, v);
-                v = mfma_bf16(a2, b2, v);
-                v = mfma_bf16(a3, b3, v);
-                const float o = BASE + CM * float(zp[p][s] & 0xffu);
-                const float scv = sc[p][s][0] * INV_CM;
+    for (int r = 0; r < 4; ++r) {
+      const int m = pass0 + min(mt * 16 + lq * 4 + r, rows_here - 1);
+      out_row[mt][r] = out_row[mt][r] * T + (m % T);
+    }
+  }
+  load_a(0);
+  cur_derive();
 #pragma unroll
-                for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
-              } else {
-                f32x4 v0 = mfma_bf16(a1, b1, mfma_bf16(a0, b0, zero));
-                f32x4 v1 = mfma_bf16(a3, b3, mfma_bf16(a2, b2, zero));
-                const float o0 = BASE + CM * float(zp[p][s] & 0xffu);
-                const float o1 = BASE + CM * float((zp[p][s] >> 8) & 0xffu);
-                const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
+  for (int d = 0; d < D; ++d) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                  tot[s][mt][r] += s0 * (v0[r] - o0 * xs[mt][0][r]);
-                  tot[s][mt][r] += s1 * (v1[r] - o1 * xs[mt][GPT == 2 ? 1 : 0][r]);
-                }
-              }
-            }
-          }
-        }
+    for (int t = 0; t < KPW; ++t) issue_tile(d, t);
+    cur_advance();
+  }
+
+  for (int sb0 = 0; sb0 < ntr_all; sb0 += sb_rows) {
+    const int ntr = min(sb_rows, ntr_all - sb0);
+    for (int ph = 0; ph < P; ++ph) {
+      const int ktw0 = ph * PHASE_KT + wave * KPW;                 // first k-tile of this wave in this phase
+      const int nkt = max(0, min(KPW, KT - ktw0));                 // its k-tiles (0 .. KPW)
+
+      // ---- the activations of this phase (the first phase's are already on their way) and their row sums ----
+      if (sb0 > 0 || ph > 0) load_a(ph);
+      // group formats: xs_op[mt][g], lane (lr, lq) = sum of row lr over group g of k-tile lq: the A operand of
+      //   the fp32 matrix-core operation that removes offset and zero-point;
+      // per-channel formats: xs_c[mt], register r of lane (lr, lq) = sum of row 4 lq + r over the wave's k-tiles.
+      float xs_op[MT][GP1];
+      f32x4 xs_c[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        xs_c[mt] = zero4;
+#pragma unroll
+        for (int g = 0; g < GP1; ++g) xs_op[mt][g] = 0.f;
       }
-    };
-
-    // ---- prologue: first weight tiles in flight, the first chunk of the activations into LDS ----
-#pragma unroll
-    for (int p = 0; p < PF; ++p) issue_w(p, kt0 + p);
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      a_fetch(c);
-      a_store(lds + c * ROWS * A_SLOT);
-    }
-    __syncthreads();
-
-    // ---- main loop over the slice's k-tiles: while tile ti is multiplied, the activations of
-    // tile ti+CH (the same position in the next chunk) travel global -> registers -> the other
-    // LDS buffer, and weight tile ti+PF is requested.  U tiles per iteration so that the ring slot
-    // and the position inside the chunk are static; the work-group meets once per chunk.
-    // Tiles past the end of a shorter slice are skipped (uniform over the wave).
-    auto step = [&](int ti, int i) {                        // i = ti % U, known at compile time where it matters
-      const int cur = (ti / CH) & 1;
-      uint8_t* const rd = lds + cur * buf_bytes + (i % CH) * ROWS * A_SLOT;
-      uint8_t* const wr = lds + (cur ^ 1) * buf_bytes + (i % CH) * ROWS * A_SLOT;
-      a_fetch(ti + CH);
-      if (kt0 + ti < kt1) consume(i % PF, rd);
-      issue_w(i % PF, kt0 + ti + PF);
-      a_store(wr);
-      if ((i + 1) % CH == 0) __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);                    // keep the steps apart: their temporaries must not pile up
-    };
-    int tb = 0;
-#pragma unroll 1
-    for (; tb + U <= slice_tiles; tb += U) {
-#pragma unroll
-      for (int i = 0; i < U; ++i) step(tb + i, i);
-    }
-#pragma unroll
-    for (int i = 0; i < U - 1; ++i)
-      if (tb + i < slice_tiles) step(tb + i, i);            // uniform over the work-group
-    __syncthreads();                                        // all reads of the staged rows are done
-
-    // ---- combine the k-slices of a task (fixed order), then the epilogue -------------------
-    if (wk > 1) {
-      float* red = reinterpret_cast<float*>(lds);
-      constexpr int SLOT = (NS * MT + MT) * 4 * 64;
-      float* mine = red + size_t(wave) * SLOT;
-      if (ks > 0) {
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) mine[((s * MT + mt) * 4 + r) * 64 + lane] = tot[s][mt][r];
+      if constexpr (!A8 && GPT > 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) mine[((NS * MT + mt) * 4 + r) * 64 + lane] = xs_tot[mt][r];
+          for (int g = 0; g < GPT; ++g) {
+            float pt[KPW];
+#pragma unroll
+            for (int t = 0; t < KPW; ++t) {
+              float v;
+              if constexpr (GPT == 1) v = (sum8(areg[t][0][mt]) + sum8(areg[t][1][mt])) + (sum8(areg[t][2][mt]) + sum8(areg[t][3][mt]));
+              else v = sum8(areg[t][2 * g][mt]) + sum8(areg[t][2 * g + 1][mt]);
+              v += __shfl_xor(v, 16, 64);
+              v += __shfl_xor(v, 32, 64);
+              pt[t] = v;                                           // zero for k-tiles the wave does not have
+            }
+            xs_op[mt][g] = pick4(lq, pt[0], pt[1], pt[2], pt[3]);
+          }
       }
-      __syncthreads();
-      if (ks == 0) {
-        for (int o = 1; o < wk; ++o) {
-          const float* other = red + size_t(wave + o) * SLOT;
+      if constexpr (!A8 && GPT == 0) {
+        const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+        const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
 #pragma unroll
-          for (int s = 0; s < NS; ++s)
+        for (int mt = 0; mt < MT; ++mt) {
+          f32x4 v = zero4;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+          for (int t = 0; t < KPW; ++t)
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                const float v = other[((s * MT + mt) * 4 + r) * 64 + lane];
-                if constexpr (A8) tot[s][mt][r] = __int_as_float(__float_as_int(tot[s][mt][r]) + __float_as_int(v));
-                else tot[s][mt][r] += v;
+            for (int j = 0; j < 4; ++j) v = mfma_bf16(areg[t][j][mt], ones_b, v);
+          xs_c[mt] = v;
+        }
+      }
+
+      // The ring values arrive through the loop's back edge.  Pinning a tile's registers where the tile is
+      // used keeps the optimizer from moving arithmetic on them (a mask, a conversion) up to the end of the
+      // previous iteration, right behind their loads, where it would wait for the whole ring.
+      auto pin_tile = [&](int d, int t) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) asm volatile("" : "+v"(raw[d][t][i]));
+        asm volatile("" : "+v"(zp[d][t]));
+#pragma unroll
+        for (int g = 0; g < GP1; ++g) asm volatile("" : "+v"(sc[d][t][g]));
+      };
+      // ---- one tile row from ring slot d: the wave's partial result, ready to be added across waves.  Straight-
+      // line code: a k-tile the wave does not have is multiplied by all-zero activation operands, a padding row
+      // is multiplied like any other and never added up.  With no branch around a load the waits can be exact,
+      // and the compiler may overlap one tile's unpacking with the matrix-core operations of another. -------
+      auto multiply = [&](int d, bool row_live, f32x4 (&res)[MT], float& row_scale) {
+        pin_tile(d, 0);
+        row_scale = sc[d][0][0];                                   // per-channel formats: kept for the epilogue
+        if constexpr (A8) {
+          i32x4 acc[MT];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt] = i32x4{0, 0, 0, 0};
+#pragma unroll
+          for (int t = 0; t < KPW; ++t) {
+            if (t > 0) pin_tile(d, t);
+            {
+              const i32x4 b0 = {int(raw[d][t][0]), int(raw[d][t][1]), int(raw[d][t][2]), int(raw[d][t][3])};
+              const i32x4 b1 = {int(raw[d][t][4]), int(raw[d][t][5]), int(raw[d][t][6]), int(raw[d][t][7])};
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) {
+                acc[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, areg[t][0][mt]), b0, acc[mt], 0, 0, 0);
+                acc[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, areg[t][1][mt]), b1, acc[mt], 0, 0, 0);
               }
+            }
+            issue_tile(d, t);
+          }
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) res[mt] = __builtin_bit_cast(f32x4, acc[mt]);
+        } else if constexpr (GPT == 0) {
+          f32x4 acc[MT];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt] = zero4;
+#pragma unroll
+          for (int t = 0; t < KPW; ++t) {
+            if (t > 0) pin_tile(d, t);
+            {
+              const bf16x8 b0 = frag<FMT, 0>(raw[d][t], fk), b1 = frag<FMT, 1>(raw[d][t], fk);
+              const bf16x8 b2 = frag<FMT, 2>(raw[d][t], fk), b3 = frag<FMT, 3>(raw[d][t], fk);
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) {
+                f32x4 v = acc[mt];
+                v = mfma_bf16(areg[t][0][mt], b0, v);
+                v = mfma_bf16(areg[t][1][mt], b1, v);
+                v = mfma_bf16(areg[t][2][mt], b2, v);
+                v = mfma_bf16(areg[t][3][mt], b3, v);
+                acc[mt] = v;
+              }
+            }
+            issue_tile(d, t);
+          }
+          const float s = row_scale * INV_CM;
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) xs_tot[mt][r] += other[((NS * MT + mt) * 4 + r) * 64 + lane];
-        }
-      }
-    }
-
-    if (ks == 0 && (sv[0] || sv[1])) {
-      float pcs[NS] = {1.f, 1.f};
-      if constexpr (GM == GM_PC) {
+            for (int r = 0; r < 4; ++r) res[mt][r] = s * (acc[mt][r] - off_sym * xs_c[mt][r]);
+        } else {
+          f32x4 acc[MT];
+          float so[GP1];                                           // lane (n = lr, g = lq): -scale * (BASE + CM z) / CM of k-tile lq
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
-          if (sv[s]) pcs[s] = reinterpret_cast<const float*>(blob[s] + ex.scale_off)[nt[s] * 16 + lr];
-      }
+          for (int mt = 0; mt < MT; ++mt) acc[mt] = zero4;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
+          for (int g = 0; g < GP1; ++g) so[g] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int m = pass0 + mt * 16 + lq * 4 + r;
-          if (m < M_e) {
-            float val[NS];
+          for (int t = 0; t < KPW; ++t) {
+            if (t > 0) pin_tile(d, t);
+            const float s0 = sc[d][t][0] * INV_CM, s1 = sc[d][t][GP1 - 1] * INV_CM;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-              if constexpr (A8) {
-                const float sx = ga.a_scale[size_t(off_e) * T + m];
-                val[s] = float(__float_as_int(tot[s][mt][r])) * sx * pcs[s];
-              } else if constexpr (GM == GM_PC) {
-                val[s] = (pcs[s] * INV_CM) * (tot[s][mt][r] - off_sym * xs_tot[mt][r]);
-              } else {
-                val[s] = tot[s][mt][r];
+            for (int g = 0; g < GPT; ++g) {
+              const float z = float((zp[d][t] >> (zp_shift + 8 * g)) & 0xffu);
+              const float v = -(g == 0 ? s0 : s1) * (BASE + CM * z);
+              so[g] = lq == t ? v : so[g];
+            }
+            {
+              const bf16x8 b0 = frag<FMT, 0>(raw[d][t], fk), b1 = frag<FMT, 1>(raw[d][t], fk);
+              const bf16x8 b2 = frag<FMT, 2>(raw[d][t], fk), b3 = frag<FMT, 3>(raw[d][t], fk);
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) {
+                if constexpr (GPT == 1) {
+                  f32x4 v = mfma_bf16(areg[t][0][mt], b0, zero4);
+                  v = mfma_bf16(areg[t][1][mt], b1, v);
+                  v = mfma_bf16(areg[t][2][mt], b2, v);
+                  v = mfma_bf16(areg[t][3][mt], b3, v);
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) acc[mt][r] += s0 * v[r];
+                } else {
+                  const f32x4 v0 = mfma_bf16(areg[t][1][mt], b1, mfma_bf16(areg[t][0][mt], b0, zero4));
+                  const f32x4 v1 = mfma_bf16(areg[t][3][mt], b3, mfma_bf16(areg[t][2][mt], b2, zero4));
+#pragma unroll
+                  for (int r = 0; r < 4; ++r) acc[mt][r] += s0 * v0[r] + s1 * v1[r];
+                }
               }
             }
-            const size_t brow = size_t(off_e) * T + m;
-            if constexpr (GATEUP) {
-              if (sv[0]) {
-                uint16_t* h = static_cast<uint16_t*>(ga.y);
-                h[brow * size_t(ga.n) + nt[0] * 16 + lr] = float_to_bf16_rne(silu_mul(val[0], val[1]));
+            issue_tile(d, t);
+          }
+          // offset and zero-point of all the wave's groups in one fp32 matrix-core operation per 4 groups:
+          //   acc[m][n] += sum_g xs[m][g] * so[g][n]
+#pragma unroll
+          for (int g = 0; g < GPT; ++g)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xs_op[mt][g], so[g], acc[mt], 0, 0, 0);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) res[mt] = acc[mt];
+        }
+        cur_advance();
+      };
+
+      // ---- the tile rows, a batch per barrier ---------------------------------------------------------------
+      int bi = 0;
+#pragma unroll 1
+      for (int i0 = 0; i0 < ntr; i0 += B, ++bi) {
+        uint8_t* pbuf = part + (bi & 1) * (PART_BYTES / 2);
+        float pcs_b[B];                                            // the per-channel scales of this batch's tile rows
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+          const bool row_live = i0 + b < ntr;                      // uniform over the work-group
+          f32x4 res[MT];
+          multiply(b % D, row_live, res, pcs_b[b]);
+          if (row_live) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              *reinterpret_cast<f32x4*>(pbuf + (((b * SW + wave) * MT + mt) * 64 + lane) * 16) = res[mt];
+          }
+        }
+        __syncthreads();
+
+        // All waves share the additions evenly: a result (64 lanes x 4 registers of one tile row and 16-row block;
+        // gate/up: of the gate row and of the up row) belongs to SW / ITEMS waves, RPW registers each.  A thread adds
+        // the 8 partial sums of its registers in wave order and stores them.
+        constexpr int NV = GATEUP ? 2 : 1;                         // gate and up results meet in one thread
+        constexpr int ITEMS = B * MT / NV;                         // results per batch
+        constexpr int WPI = SW / ITEMS;                            // waves per result
+        constexpr int RPW = 4 / WPI;                               // registers per wave
+        static_assert(ITEMS * WPI == SW && RPW * WPI == 4, "the results of a batch divide evenly among the waves");
+        {
+          const int item = wave / WPI, r0 = (wave % WPI) * RPW;    // uniform over the wave
+          const int ib = item / MT, mt_dyn = item % MT;            // tile row (or pair) inside the batch, 16-row block
+          const int i_first = i0 + ib * NV;                        // tile row index inside the super-batch
+          if (i_first < ntr) {
+            float v[NV][RPW];
+#pragma unroll
+            for (int s = 0; s < NV; ++s) {
+              const uint8_t* src = pbuf + (((ib * NV + s) * SW * MT + mt_dyn) * 64 + lane) * 16 + r0 * 4;
+#pragma unroll
+              for (int rr = 0; rr < RPW; ++rr) v[s][rr] = reinterpret_cast<const float*>(src)[rr];
+#pragma unroll
+              for (int w = 1; w < SW; ++w) {
+#pragma unroll
+                for (int rr = 0; rr < RPW; ++rr) {
+                  const float o = reinterpret_cast<const float*>(src + w * (MT * 64 * 16))[rr];
+                  if constexpr (A8) v[s][rr] = __int_as_float(__float_as_int(v[s][rr]) + __float_as_int(o));
+                  else v[s][rr] += o;
+                }
               }
-            } else {
-              size_t drow = brow;
-              if (ga.y_perm) drow = size_t(ga.y_perm[off_e + m / T]) * T + (m % T);
-              float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
-              if (sv[0]) y[nt[0] * 16 + lr] = val[0];
-              if (sv[1]) y[nt[1] * 16 + lr] = val[1];
+            }
+            if (P > 1) {                                           // running sums between phases (same thread every phase)
+              uint8_t* tp = totl + (((bi % TOT_BATCHES) * BMT + item * NV) * 64 + lane) * 16 + r0 * 4;
+#pragma unroll
+              for (int s = 0; s < NV; ++s)
+#pragma unroll
+                for (int rr = 0; rr < RPW; ++rr) {
+                  float* t = reinterpret_cast<float*>(tp + s * 64 * 16) + rr;
+                  if (ph > 0) {
+                    if constexpr (A8) v[s][rr] = __int_as_float(__float_as_int(v[s][rr]) + __float_as_int(*t));
+                    else v[s][rr] += *t;
+                  }
+                  if (ph + 1 < P) *t = v[s][rr];
+                }
+            }
+            if (ph + 1 == P) {
+              const int i_glob = sb0 + i_first;
+              const int nt = GATEUP ? u0 + (i_glob >> 1) : u0 + i_glob;
+              const int ncol = nt * 16 + lr;
+#pragma unroll
+              for (int rr = 0; rr < RPW; ++rr) {
+                const int r = r0 + rr;
+                // this register's result row, picked without dynamic register indexing
+                int orow = out_row[0][0];
+                float osx = sx[0][0];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                  for (int q = 0; q < 4; ++q)
+                    if (mt_dyn == mt && r == q) { orow = out_row[mt][q]; osx = sx[mt][q]; }
+                float val[NV];
+#pragma unroll
+                for (int s = 0; s < NV; ++s) {
+                  val[s] = v[s][rr];
+                  if constexpr (A8) {
+                    float ps = pcs_b[0];
+#pragma unroll
+                    for (int b = 1; b < B; ++b) if (ib * NV + s == b) ps = pcs_b[b];
+                    val[s] = float(__float_as_int(val[s])) * osx * ps;
+                  }
+                }
+                if (mt_dyn * 16 + lq * 4 + r < rows_here) {
+                  const size_t o = size_t(orow) * size_t(ga.n) + ncol;
+                  if constexpr (GATEUP) static_cast<uint16_t*>(ga.y)[o] = float_to_bf16_rne(silu_mul(val[0], val[NV - 1]));
+                  else static_cast<float*>(ga.y)[o] = val[0];
+                }
+              }
             }
           }
         }
       }
+      __syncthreads();          // the partial-sum buffers are free again before the next phase writes them
     }
-    __syncthreads();                             // LDS is reused by the next pass
   }
 }
 
-template <bool GATEUP, int WK>
-__global__ __launch_bounds__(WAVES * 64, 2) void k_qgemm_stream(const GemmArgs ga) {
+template <int FMT, int GM, bool GATEUP>
+static __device__ __forceinline__ void stream_expert(const GemmArgs& ga, const StreamSeg& sg, uint8_t* lds) {
+  for (int pass0 = 0; pass0 < sg.rows_e; pass0 += STREAM_ROWS) {
+    const int rows_here = min(STREAM_ROWS, sg.rows_e - pass0);
+    if (rows_here <= 16) stream_pass<FMT, GM, GATEUP, 1>(ga, sg.ex, sg.off_e, sg.u0, sg.u1, pass0, rows_here, lds);
+    else stream_pass<FMT, GM, GATEUP, 2>(ga, sg.ex, sg.off_e, sg.u0, sg.u1, pass0, rows_here, lds);
+  }
+}
+
+template <bool GATEUP>
+__global__ __launch_bounds__(SW * 64, 2) void k_qgemm_stream(const GemmArgs ga) {
   extern __shared__ __align__(16) uint8_t lds[];
-  const int wg = blockIdx.x;
-  const int e = ga.order[wg / ga.wg_per_expert];
-  const int wgi = wg % ga.wg_per_expert;
-  const ExpertDev& ex = ga.ex[e];
-  switch (ex.fmt * 4 + ex.gm) {
-    case FMT_I8 * 4 + GM_PC:     stream_task<FMT_I8, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_I8A8 * 4 + GM_PC:   stream_task<FMT_I8A8, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N6 * 4 + GM_PC:     stream_task<FMT_N6, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_PC:     stream_task<FMT_N4, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_G128:   stream_task<FMT_N4, GM_G128, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_G64:    stream_task<FMT_N4, GM_G64, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N3 * 4 + GM_G128:   stream_task<FMT_N3, GM_G128, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N3 * 4 + GM_G64:    stream_task<FMT_N3, GM_G64, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+  StreamSeg sg = stream_schedule(ga, int(blockIdx.x), int(gridDim.x));
+  if (sg.e < 0 || sg.u1 <= sg.u0) return;             // uniform over the work-group
+  sg.u0 = __builtin_amdgcn_readfirstlane(sg.u0); sg.u1 = __builtin_amdgcn_readfirstlane(sg.u1);
+  sg.off_e = __builtin_amdgcn_readfirstlane(sg.off_e); sg.rows_e = __builtin_amdgcn_readfirstlane(sg.rows_e);
+  switch (sg.ex.fmt * 4 + sg.ex.gm) {
+    case FMT_I8 * 4 + GM_PC:     stream_expert<FMT_I8, GM_PC, GATEUP>(ga, sg, lds); break;
+    case FMT_I8A8 * 4 + GM_PC:   stream_expert<FMT_I8A8, GM_PC, GATEUP>(ga, sg, lds); break;
+    case FMT_N6 * 4 + GM_PC:     stream_expert<FMT_N6, GM_PC, GATEUP>(ga, sg, lds); break;
+    case FMT_N4 * 4 + GM_PC:     stream_expert<FMT_N4, GM_PC, GATEUP>(ga, sg, lds); break;
+    case FMT_N4 * 4 + GM_G128:   stream_expert<FMT_N4, GM_G128, GATEUP>(ga, sg, lds); break;
+    case FMT_N4 * 4 + GM_G64:    stream_expert<FMT_N4, GM_G64, GATEUP>(ga, sg, lds); break;
+    case FMT_N3 * 4 + GM_G128:   stream_expert<FMT_N3, GM_G128, GATEUP>(ga, sg, lds); break;
+    case FMT_N3 * 4 + GM_G64:    stream_expert<FMT_N3, GM_G64, GATEUP>(ga, sg, lds); break;
     default: break;
   }
 }
 
-typedef void (*StreamKernel)(const GemmArgs);
+// One work-group per compute unit of the current device.
+static int32_t stream_grid(int* out) {
+  static std::mutex mu;
+  static int cus[64] = {};
+  int dev = 0;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return set_error(MOQE_E_HIP, "grouped_qgemm: hipGetDevice: %s", hipGetErrorString(err));
+  if (dev < 0 || dev >= 64) return set_error(MOQE_E_HIP, "grouped_qgemm: device %d", dev);
+  std::lock_guard<std::mutex> lk(mu);
+  if (cus[dev] == 0) {
+    int n = 0;
+    err = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (err != hipSuccess || n <= 0) return set_error(MOQE_E_HIP, "grouped_qgemm: compute unit count: %s", hipGetErrorString(err));
+    cus[dev] = n;
+  }
+  *out = cus[dev];
+  return MOQE_OK;
+}
 
 int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
   // this kernel reads `a` as a plain [rows, k] matrix; an image that still needs its 3x3 gather must not get here
   if (ga.conv_c != 0) return set_error(MOQE_E_SHAPE, "grouped_qgemm: the streaming kernel cannot gather a convolution's rows");
-  const int NT = ga.n / 16, KT = ga.k / 128;
-  const int ntasks = gateup ? NT : (NT + 1) / 2;
-  GemmArgs a = ga;
-  // Long rows are cut into four k-slices per task, short ones into two: a wave should keep a
-  // dozen or more tiles to amortise its set-up, and there should be a few work-groups per CU.
-  const int wk = KT >= 64 ? 4 : 2;
-  const int wn = WAVES / wk;
-  a.wk = wk;
-  a.wn = wn;
-  a.wg_per_expert = (ntasks + wn - 1) / wn;
-  const unsigned grid = unsigned(a.wg_per_expert) * unsigned(a.n_experts);
-  const int slot_bytes = (NS * MT + MT) * 4 * 64 * 4;
-  int lds_bytes = LDS_BYTES;
-  if (WAVES * slot_bytes > lds_bytes) lds_bytes = WAVES * slot_bytes;
-  const int ki = (gateup ? 2 : 0) + (wk == 4 ? 1 : 0);
-  static const StreamKernel kernels[4] = {k_qgemm_stream<false, 2>, k_qgemm_stream<false, 4>, k_qgemm_stream<true, 2>,
-                                          k_qgemm_stream<true, 4>};
-  int32_t rc = ensure_dynamic_lds(LDSK_STREAM0 + ki, reinterpret_cast<const void*>(kernels[ki]), LDS_BYTES, "grouped_qgemm");
+  int grid = 0;
+  int32_t rc = stream_grid(&grid);
+  if (rc) return rc;
+  const void* fn = gateup ? reinterpret_cast<const void*>(&k_qgemm_stream<true>) : reinterpret_cast<const void*>(&k_qgemm_stream<false>);
+  rc = ensure_dynamic_lds(LDSK_STREAM0 + (gateup ? 1 : 0), fn, STREAM_LDS_BYTES, "grouped_qgemm");
   if (rc) return rc;
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  hipLaunchKernelGGL(kernels[ki], dim3(grid), dim3(WAVES * 64), lds_bytes, st, a);
+  if (gateup) hipLaunchKernelGGL(k_qgemm_stream<true>, dim3(grid), dim3(SW * 64), STREAM_LDS_BYTES, st, ga);
+  else hipLaunchKernelGGL(k_qgemm_stream<false>, dim3(grid), dim3(SW * 64), STREAM_LDS_BYTES, st, ga);
   return check_launch("grouped_qgemm");
 }
 

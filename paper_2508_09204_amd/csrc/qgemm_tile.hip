@@ -368,7 +368,8 @@ __global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga
   // which expert and which row tile of its bucket: `slot` counts row tiles over all experts
   int slot = (patch / patches_n) * PATCH_M + q % PATCH_M, e = -1, m0 = 0;
   for (int i = 0; i < ga.n_experts; ++i) {
-    const int rows = (ga.offsets[i + 1] - ga.offsets[i]) * ga.T;
+    int rows = (ga.offsets[i + 1] - ga.offsets[i]) * ga.T;
+    if (rows < ga.min_rows || rows > ga.max_rows) rows = 0;       // that bucket belongs to the streaming kernel's launch
     const int tiles = (rows + TBM - 1) / TBM;
     if (slot < tiles) { e = i; m0 = slot * TBM; break; }
     slot -= tiles;

@@ -6,7 +6,9 @@ dequantize-GEMM gate/up with the fused SiLU gate -> grouped dequantize-GEMM down
 Default workload: the LLaMA-7B-shaped MLP block in decode (64 sequences x 1 token, 4 experts),
 synthetic seeded tensors.  Inputs are resident in HBM before the timed region.  Prints ONE JSON
 line with the throughput, the roofline of the dominant kernel (measured with HIP events on the
-launch stream during the timed steps) and the CPU oracle timed on the host cores.
+launch stream during the timed steps) and the CPU oracle timed on the host cores; a `workloads` array in
+the same line carries the prefill-shaped, skewed and convolution workloads (step time, dominant kernel,
+roofline), measured in the same run with fewer steps.
 """
 from __future__ import annotations
 
@@ -22,13 +24,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+MFMA_INT8_PEAK_TOPS = 5000.0    # dense int8, published
+
+# Kernel durations from the committed rocprofv3 --kernel-trace summaries (profiles/), per workload: the event
+# bracket above also sees the gap between the event records and the kernel, so it reads a few microseconds
+# long; `frac_rocprof` is the roofline fraction with the profiler's own average duration.  Tied to the kernel
+# sources like the traffic figure.
+ROCPROF_KERNEL_US = {}
 
 
 # HBM traffic of the dominant kernel from hardware counters (two rocprofv3 --pmc runs, FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB device copy; summary and
 # commands are kept with the profile summaries in the repository).  Valid only for the kernel sources it was taken with: the entry carries
 # their hash and is ignored (traffic = null) once they have changed.
-KERNEL_SOURCES = ("qgemm_stream.hip", "qgemm_device.h")       # the dominant kernel's own sources
+KERNEL_SOURCES = ("qgemm_stream.hip", "qgemm_stream_lds.hip", "qgemm_tile.hip", "qgemm_device.h")       # the GEMM kernels' own sources
 MEASURED_TRAFFIC = {
     "llama7b_mlp_decode": {"sources_sha256": "074a1d9b760c4f296c6253a6375bdd06ef7a0147b981a7e20205876777493018",
                            "bytes_per_launch": 232536084},   # fetch 231.1 MB + write 1.41 MB
@@ -126,6 +135,129 @@ def cpu_baseline(cfg, max_seconds_hint=30.0):
             "sample": sample + f"; {dt:.1f} s wall, dequantization of the routed experts included"}
 
 
+def rocprof_kernel_us(workload):
+    t = ROCPROF_KERNEL_US.get(workload)
+    if not t or t["sources_sha256"] != kernel_sources_hash():
+        return None
+    return t["kernel_us"]
+
+
+def measure(name, steps, warmup, copies=0, with_graph=False, experts=None):
+    """Builds the workload on the GPU, times `steps` forwards after `warmup` untimed ones, and returns the
+    step metrics and the roofline of its dominant kernel (HIP events on the launch stream, recorded by the
+    library during the timed steps)."""
+    import dataclasses
+    import torch
+    import workloads as wl
+    from paper_2508_09204_amd import binding as mq
+
+    dev = "cuda:0"
+    cfg = wl.get_config(name)
+    if experts is not None:
+        cfg = dataclasses.replace(cfg, experts=tuple(experts))
+    is_mlp = cfg.kind == wl.configs.KIND_SILU_MLP
+    is_conv = cfg.kind == wl.configs.KIND_CONV3X3
+    mats = cfg.matrices()
+    per_expert_bytes = [sum(algorithmic_weight_bytes(n, k, e) for (n, k) in mats.values()) for e in cfg.experts]
+    n_copies = copies or max(2, min(8, -(-(1 << 30) // sum(per_expert_bytes))))
+    blocks = build_device_block(cfg, n_copies)
+    dominant = mq.PK_GEMM_GATEUP if is_mlp else mq.PK_GEMM_PLAIN
+
+    bits = wl.make_activations(cfg)
+    x = torch.from_numpy(bits.view("int16").reshape(cfg.M, cfg.D)).to(dev).view(torch.bfloat16)
+    n_out = cfg.D if is_mlp else cfg.F
+    y = torch.empty((cfg.M, n_out), dtype=torch.float32, device=dev)
+    counts = torch.zeros(cfg.K, dtype=torch.int32, device=dev)
+    aux = mq.Aux(counts=counts)
+    calls = [mq.ForwardCall(b, x, cfg.S, cfg.T, y, aux) for b in blocks]
+    stream = torch.cuda.current_stream().cuda_stream
+    mq.moqe_profile_enable(1 << dominant)          # warm the event pool before the timed region
+    for i in range(warmup):
+        calls[i % len(calls)](stream)
+    torch.cuda.synchronize()
+    mq.moqe_profile_enable(1 << dominant)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        calls[i % len(calls)](stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    launches, kern_ms = mq.moqe_profile_read(dominant)
+    mq.moqe_profile_enable(0)
+    hist = counts.cpu().tolist()
+
+    graph_ms = None
+    if with_graph:
+        # the same steps replayed from captured graphs (one per weight copy): launch gaps of the eager loop removed
+        graphs = []
+        for c in calls:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                c(torch.cuda.current_stream().cuda_stream)
+            graphs.append(g)
+        for i in range(min(warmup, 10)):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / steps
+        del graphs
+
+    ms_per_step = dt * 1e3 / steps
+    units = cfg.M if cfg.unit == "tokens" else cfg.S
+    kern_us = kern_ms * 1e3 / max(launches, 1)
+    launches_per_step = max(1, round(launches / steps))       # a bucket-size split may launch both GEMM kernels
+    kern_us *= launches_per_step
+
+    # algorithmic bytes / flops of the dominant launch: each non-empty expert's matrices once
+    dom_mats = [mats["gate"], mats["up"]] if is_mlp else list(mats.values())
+    dom_bytes = sum(sum(algorithmic_weight_bytes(n, k, e) for (n, k) in dom_mats)
+                    for e, c in zip(cfg.experts, hist) if c > 0)
+    flops_per_expert = [2.0 * c * cfg.T * sum(n * k for (n, k) in dom_mats) for c in hist]
+    dom_flops = sum(flops_per_expert)
+    # every non-empty bucket has a multiple of T rows: few rows stream the weights (bound by HBM), many rows
+    # are a dense contraction on the matrix cores
+    hbm_bound = (not is_conv) and cfg.T <= 32 and cfg.M <= 128
+    rp_us = rocprof_kernel_us(cfg.name) if experts is None else None
+    if hbm_bound:
+        achieved = dom_bytes / (kern_us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(cfg.name) if experts is None else None}
+        if rp_us:
+            roof["frac_rocprof"] = dom_bytes / (rp_us * 1e-6) / 1e9 / HBM_PEAK_GBS
+    else:
+        # experts with int8 activations run on the int8 matrix cores: the launch's fraction of peak is the time the
+        # flops would take at each expert's own peak over the measured time
+        ideal_s = sum(f / ((MFMA_INT8_PEAK_TOPS if e.act_mode else MFMA_BF16_PEAK_TFLOPS) * 1e12)
+                      for f, e in zip(flops_per_expert, cfg.experts))
+        achieved = dom_flops / (kern_us * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ideal_s / (kern_us * 1e-6), "traffic": None}
+        if any(e.act_mode for e in cfg.experts):
+            roof["peak_note"] = "frac = sum over experts of flops / own peak (int8 5000 TOP/s for the W8A8 expert) over the kernel time"
+        if rp_us:
+            roof["frac_rocprof"] = ideal_s / (rp_us * 1e-6)
+        # the same launch against the HBM roofline: weights once, activations in (bf16), results out
+        k_in = cfg.D if is_conv else dom_mats[0][1]          # conv: the kernel gathers from the image
+        io_bytes = cfg.M * k_in * 2 + cfg.M * dom_mats[0][0] * (2 if is_mlp else 4)
+        roof["hbm_view"] = {"algorithmic_bytes_per_launch": dom_bytes + io_bytes,
+                            "achieved_gbs": (dom_bytes + io_bytes) / (kern_us * 1e-6) / 1e9,
+                            "frac_of_8tbs": (dom_bytes + io_bytes) / (kern_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+    roof["kernel"] = ("k_qgemm_stream" if hbm_bound else "k_qgemm_tile") + ("<gate/up + SiLU>" if is_mlp else "<plain>")
+    roof["kernel_us"] = kern_us
+    if rp_us:
+        roof["kernel_us_rocprof"] = rp_us
+    roof["launches_timed"] = launches
+    roof["algorithmic_bytes_per_launch"] = dom_bytes
+    roof["algorithmic_flops_per_launch"] = dom_flops
+    res = {"cfg": cfg, "n_copies": n_copies, "hist": hist, "ms_per_step": ms_per_step, "value": units / (dt / steps),
+           "graph_ms_per_step": graph_ms, "roofline": roof, "steps": steps}
+    del blocks, calls
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,6 +267,7 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="rotating weight copies (0 = pick so that they exceed 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-int4-only", action="store_true", help="skip the extra all-int4 measurement of the decode launch")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the prefill / skew / conv entries of `workloads`")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the warm-up, run a plain device copy of 1 GiB five times (a kernel of known "
                          "traffic, for scaling hardware counters of a profiler run)")
@@ -146,44 +279,9 @@ def main():
 
     import torch
     import workloads as wl
-    from paper_2508_09204_amd import binding as mq
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
-    cfg = wl.get_config(args.workload)
-    is_mlp = cfg.kind == wl.configs.KIND_SILU_MLP
-    mats = cfg.matrices()
-    per_expert_bytes = [sum(algorithmic_weight_bytes(n, k, e) for (n, k) in mats.values()) for e in cfg.experts]
-    n_copies = args.copies or max(2, min(8, -(-(1 << 30) // sum(per_expert_bytes))))
-    blocks = build_device_block(cfg, n_copies)
-
     dev = "cuda:0"
-
-    def run_timed(cfg_run, blocks_run, steps, warmup):
-        """Times `steps` forwards (rotating over the weight copies); returns seconds, the routing
-        histogram, and the dominant kernel's launch count and summed duration from the library's
-        HIP events on the launch stream."""
-        bits = wl.make_activations(cfg_run)
-        x = torch.from_numpy(bits.view("int16").reshape(cfg_run.M, cfg_run.D)).to(dev).view(torch.bfloat16)
-        n_out = cfg_run.D if is_mlp else cfg_run.F
-        y = torch.empty((cfg_run.M, n_out), dtype=torch.float32, device=dev)
-        counts = torch.zeros(cfg_run.K, dtype=torch.int32, device=dev)
-        aux = mq.Aux(counts=counts)
-        calls = [mq.ForwardCall(b, x, cfg_run.S, cfg_run.T, y, aux) for b in blocks_run]
-        stream = torch.cuda.current_stream().cuda_stream
-        mq.moqe_profile_enable(1 << dominant)          # warm the event pool before the timed region
-        for i in range(warmup):
-            calls[i % len(calls)](stream)
-        torch.cuda.synchronize()
-        mq.moqe_profile_enable(1 << dominant)
-        t0 = time.perf_counter()
-        for i in range(steps):
-            calls[i % len(calls)](stream)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        launches, kern_ms = mq.moqe_profile_read(dominant)
-        mq.moqe_profile_enable(0)
-        return dt, counts.cpu().tolist(), launches, kern_ms
-
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -192,76 +290,42 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    dominant = mq.PK_GEMM_GATEUP if is_mlp else mq.PK_GEMM_PLAIN
-    dt, hist, launches, kern_ms = run_timed(cfg, blocks, args.steps, args.warmup)
-
-    ms_per_step = dt * 1e3 / args.steps
-    units = cfg.M if cfg.unit == "tokens" else cfg.S
-    value = units / (dt / args.steps)
-    kern_us = kern_ms * 1e3 / max(launches, 1)
-
-    # algorithmic bytes / flops of the dominant kernel per launch: each non-empty expert's matrices once
-    if is_mlp:
-        dom_mats = [mats["gate"], mats["up"]]
-    else:
-        dom_mats = list(mats.values())
-    dom_bytes = sum(sum(algorithmic_weight_bytes(n, k, e) for (n, k) in dom_mats)
-                    for e, c in zip(cfg.experts, hist) if c > 0)
-    dom_flops = sum(2.0 * c * cfg.T * sum(n * k for (n, k) in dom_mats) for c in hist)
-    # the library streams the weights for buckets of a few rows and tiles the contraction for larger
-    # ones (more than 64 rows per expert on average): the first is bound by HBM, the second by MFMA
-    tiled = cfg.M > 64 * cfg.K
-    hbm_bound = not tiled
-    if hbm_bound:
-        achieved = dom_bytes / (kern_us * 1e-6) / 1e9
-        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(cfg.name)}
-    else:
-        achieved = dom_flops / (kern_us * 1e-6) / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
-        # the same launch against the HBM roofline: weights once, activations in (bf16), results out
-        k_in = cfg.D if cfg.kind == wl.configs.KIND_CONV3X3 else dom_mats[0][1]     # conv: the kernel gathers from the image
-        n_out_dom = dom_mats[0][0]
-        io_bytes = cfg.M * k_in * 2 + cfg.M * n_out_dom * (2 if is_mlp else 4)
-        roof["hbm_view"] = {"algorithmic_bytes_per_launch": dom_bytes + io_bytes,
-                            "achieved_gbs": (dom_bytes + io_bytes) / (kern_us * 1e-6) / 1e9,
-                            "frac_of_8tbs": (dom_bytes + io_bytes) / (kern_us * 1e-6) / 1e9 / HBM_PEAK_GBS}
-    roof["kernel"] = ("k_qgemm_tile" if tiled else "k_qgemm_stream") + ("<gate/up + SiLU>" if is_mlp else "<plain>")
-    roof["kernel_us"] = kern_us
-    roof["launches_timed"] = launches
-    roof["algorithmic_bytes_per_launch"] = dom_bytes
-    roof["algorithmic_flops_per_launch"] = dom_flops
+    head = measure(args.workload, args.steps, args.warmup, args.copies, with_graph=True)
+    cfg, roof = head["cfg"], head["roofline"]
 
     # The decode target is stated for a grouped int4 GEMM: the same launch with all experts int4 g128.
-    if hbm_bound and is_mlp and not args.no_int4_only:
-        import dataclasses
-        del blocks
-        torch.cuda.empty_cache()
+    if roof["bound"] == "hbm" and cfg.kind == wl.configs.KIND_SILU_MLP and not args.no_int4_only:
         int4 = wl.configs.ExpertSpec(4, 128, False)
-        cfg4 = dataclasses.replace(cfg, experts=tuple([int4] * cfg.K))
-        per4 = sum(algorithmic_weight_bytes(n, k, int4) for (n, k) in mats.values()) * cfg.K
-        blocks4 = build_device_block(cfg4, max(2, min(8, -(-(1 << 30) // per4))))
-        steps4 = max(20, args.steps // 2)
-        _, hist4, launches4, kern_ms4 = run_timed(cfg4, blocks4, steps4, min(args.warmup, 10))
-        us4 = kern_ms4 * 1e3 / max(launches4, 1)
-        bytes4 = sum(sum(algorithmic_weight_bytes(n, k, int4) for (n, k) in dom_mats) for c in hist4 if c > 0)
-        roof["int4_only"] = {"experts": [int4.label()] * cfg.K, "kernel_us": us4, "launches_timed": launches4,
-                             "algorithmic_bytes_per_launch": bytes4, "achieved": bytes4 / (us4 * 1e-6) / 1e9,
-                             "frac": bytes4 / (us4 * 1e-6) / 1e9 / HBM_PEAK_GBS}
-        del blocks4
+        r4 = measure(args.workload, max(20, args.steps // 2), min(args.warmup, 10), 0, experts=[int4] * cfg.K)
+        q = r4["roofline"]
+        roof["int4_only"] = {"experts": [int4.label()] * cfg.K, "kernel_us": q["kernel_us"], "launches_timed": q["launches_timed"],
+                             "algorithmic_bytes_per_launch": q["algorithmic_bytes_per_launch"], "achieved": q["achieved"],
+                             "frac": q["frac"]}
+
+    def entry(r):
+        c = r["cfg"]
+        return {"workload": c.name, "samples": c.S, "rows_per_sample": c.T, "experts": [e.label() for e in c.experts],
+                "routing_histogram": r["hist"], "steps": r["steps"], "ms_per_step": r["ms_per_step"],
+                "value": r["value"], "unit": f"{c.unit}/s", "roofline": r["roofline"]}
+
+    others = []
+    if not args.no_other_workloads and args.workload == "llama7b_mlp_decode":
+        for name, st, wu in (("llama7b_mlp_prefill", 20, 3), ("qwen_mlp_skew", 5, 2), ("resnet50_conv", 100, 10)):
+            others.append(entry(measure(name, st, wu, 2)))
 
     out = {
         "metric": "routed qGEMM throughput (whole routed block: route + bucket + grouped qGEMMs + scatter)",
-        "value": value, "unit": f"{cfg.unit}/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["value"], "unit": f"{cfg.unit}/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic (seeded N(0,1) activations, N(0,0.02) weights quantized by round-to-nearest on the GPU)",
         "config": {"workload": cfg.name, "samples": cfg.S, "rows_per_sample": cfg.T, "d": cfg.D, "f": cfg.F,
-                   "experts": [e.label() for e in cfg.experts], "routing_histogram": hist,
+                   "experts": [e.label() for e in cfg.experts], "routing_histogram": head["hist"],
                    "arithmetic": "bf16 activations x exact integer weight codes on bf16 MFMA, fp32 accumulate and scales",
-                   "rotating_weight_copies": n_copies},
+                   "rotating_weight_copies": head["n_copies"],
+                   "ms_per_step_graph_replay": head["graph_ms_per_step"]},
         "roofline": roof,
+        "workloads": others,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)

@@ -9,8 +9,8 @@
 //    are dealt to the experts in proportion to the bytes each expert has to stream (its tile size
 //    times the passes its bucket needs), and an expert's 16-row weight tiles are split evenly among
 //    its work-groups; every work-group computes this deal itself from the bucket offsets.
-//  * The activations stay in REGISTERS: the k range is cut across the 8 waves (4 k-tiles of 128
-//    columns per wave and phase; rows longer than 32 k-tiles take several phases), and a wave loads
+//  * The activations stay in REGISTERS: the k range (at most 32 k-tiles of 128 columns; longer rows
+//    take the other streaming kernel) is cut across the 8 waves, 4 k-tiles per wave, and a wave loads
 //    its slice of the bucket's rows once, already shaped as matrix-core operands.  It then streams
 //    the matching 4-tile piece of every weight tile row of the work-group (4 KiB contiguous for
 //    4-bit codes), a piece or two ahead, through 16-byte load -> a few bit operations -> bf16 MFMA.
@@ -22,8 +22,7 @@
 //    row sum once per tile row.  The fp32 scale multiplies the fp32 partial sum of each group, so no
 //    weight is ever rounded.
 //  * The 8 partial sums of a tile row (one per k slice) are added in wave order through LDS, a
-//    batch of tile rows per barrier, by waves that take turns; with several phases the running sums
-//    wait in LDS.  Then the epilogue: fp32 rows scattered through the permutation, or
+//    batch of tile rows per barrier, every wave adding its share.  Then the epilogue: fp32 rows scattered through the permutation, or
 //    bf16(silu(gate) * up).  Every sum has a fixed order: results do not depend on scheduling.
 #include "qgemm_device.h"
 
@@ -33,14 +32,12 @@ namespace moqe {
 
 constexpr int SW = 8;                      // waves per work-group
 constexpr int KPW = 4;                     // k-tiles (128 columns) a wave keeps as register operands
-constexpr int PHASE_KT = SW * KPW;         // k-tiles a work-group covers per phase
-static_assert(PHASE_KT == STREAM_REG_MAX_KT, "rows of more k-tiles take several phases here and are sent to the other streaming kernel");
+constexpr int MAX_KT = SW * KPW;           // k-tiles a work-group covers: longer rows go to the other streaming kernel
+static_assert(MAX_KT == STREAM_REG_MAX_KT, "the launcher's limit is what the waves' register operands cover");
 constexpr int STREAM_ROWS = 32;            // bucket rows per pass (two 16-row blocks)
 constexpr int BMT = 4;                     // (tile rows per batch) x (16-row blocks): results exchanged per barrier
 constexpr int PART_BYTES = 2 * BMT * SW * 64 * 16;     // two buffers of per-wave partial sums
-constexpr int TOT_BATCHES = 8;             // batches whose running sums are kept between phases
-constexpr int TOT_BYTES = TOT_BATCHES * BMT * 64 * 16;
-constexpr int STREAM_LDS_BYTES = PART_BYTES + TOT_BYTES;
+constexpr int STREAM_LDS_BYTES = PART_BYTES;
 
 // ---- which expert and which of its weight tiles a work-group streams ---------------------------------
 struct StreamSeg {
@@ -168,7 +165,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   // budget of 24 registers of codes and group parameters per k-tile for one 16-row block, 12 for two.
   constexpr int RING_REGS = NR + (GM == GM_PC ? 0 : (GM == GM_G128 ? 2 : 3));
   constexpr int D_FIT = (MT == 1 ? 24 : 12) / RING_REGS;
-  constexpr int D = D_FIT >= 4 && B % 4 == 0 ? 4 : (D_FIT >= 2 ? 2 : 1);
+  constexpr int D = D_FIT >= 4 && B % 4 == 0 ? 4 : ((D_FIT >= 2 && !(MT == 2 && GM == GM_G64)) ? 2 : 1);      // two blocks and two groups per k-tile: no room
   constexpr int AJ = A8 ? 2 : 4;                        // matrix-core steps per k-tile
   constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
   static_assert(B % D == 0 && (!GATEUP || B % 2 == 0), "ring slot and gate/up pairing are static inside a batch");
@@ -178,9 +175,9 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lq = lane >> 4;
   const int KT = ga.k >> 7, T = ga.T;
-  const int P = (KT + PHASE_KT - 1) / PHASE_KT;         // phases
-  const int ntr_all = (u1 - u0) * (GATEUP ? 2 : 1);     // weight tile rows of this work-group
-  const int sb_rows = P > 1 ? TOT_BATCHES * B : ntr_all;        // tile rows whose running sums fit in LDS
+  const int ntr = (u1 - u0) * (GATEUP ? 2 : 1);         // weight tile rows of this work-group
+  const int ktw0 = wave * KPW;                          // first k-tile of this wave
+  const int nkt = max(0, min(KPW, KT - ktw0));          // its k-tiles (0 .. KPW)
   const float off_sym = BASE + CM * float(ex.zc);
   const FragK<FMT> fk = frag_constants<FMT>();
   const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
@@ -188,7 +185,6 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   const uint32_t zp_shift = 8u * uint32_t((lr * GPT) & 3);      // position of the lane's zero-point(s) in their dword
 
   uint8_t* part = lds;                                  // [2][B][SW][MT][64] x 16 bytes
-  uint8_t* totl = lds + PART_BYTES;                     // [TOT_BATCHES][BMT][64] x 16 bytes
 
   // ---- rows of this pass ---------------------------------------------------------------------------------
   // operand rows: lane (lr, lq) feeds row mt*16 + lr of the pass; result rows: register r of lane (lr, lq) is
@@ -220,40 +216,30 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   size_t a_row_off[MT];
 
   // ---- weight ring -----------------------------------------------------------------------------------------
-  // The work-group walks its tile rows in one fixed sequence: for each super-batch, for each phase, the rows of
-  // the super-batch padded to whole batches (a padding row repeats the last row's tiles and is not multiplied).
-  // The ring holds D consecutive rows of that sequence, KPW tiles each; tile (row, t) is requested again, for
-  // the row D places further on, right after its matrix-core operations, so KPW * D - 1 tiles are in flight
-  // behind the one being multiplied, across batch and phase boundaries alike.  `cur` is the next row to request.
+  // The work-group walks its tile rows in order, padded to whole batches (a padding row repeats the last row's
+  // tiles and is never added up).  The ring holds D consecutive rows, KPW tiles each; tile (row, t) is requested
+  // again, for the row D places further on, right after its matrix-core operations, so KPW * D - 1 tiles are in
+  // flight behind the one being multiplied, across batch boundaries alike.  `cur_i` is the next row to request.
   uint32_t raw[D][KPW][NR];
   float sc[D][KPW][GP1];                                // group scales; per-channel formats: [0] of tile 0 is the row's scale
   uint32_t zp[D][KPW];
   const uint32_t tile_bytes = ex.tile_bytes, scale_off = ex.scale_off, zero_off = ex.zero_off;
   const uint8_t* const blob0 = ex.w[0];
   const uint8_t* const blob1 = ex.w[GATEUP ? 1 : 0];
-  int cur_sb0 = 0, cur_ph = 0, cur_i = 0;               // position in the sequence
-  int cur_ntr = min(sb_rows, ntr_all);
-  // derived from the position: which blob, first tile index of the row's KPW tiles, last valid tile offset, tile row
+  int cur_i = 0;
+  // derived from the position: which blob, first tile index of the row's KPW tiles, tile row
   const uint8_t* cur_blob = blob0;
   uint32_t cur_t0 = 0u;
-  int cur_tmax = 0, cur_nt = u0;
+  int cur_nt = u0;
+  const int cur_tmax = max(nkt - 1, 0);                  // tiles the wave does not have repeat its last one (or the row's last)
   auto cur_derive = [&]() {
-    const int i = cur_sb0 + min(cur_i, cur_ntr - 1);
+    const int i = min(cur_i, ntr - 1);                   // padding rows and rows past the end: the last row again
     cur_nt = GATEUP ? u0 + (i >> 1) : u0 + i;
     cur_blob = (GATEUP && (i & 1)) ? blob1 : blob0;
-    const int ktw0 = cur_ph * PHASE_KT + wave * KPW;
-    cur_tmax = max(min(KPW, KT - ktw0) - 1, 0);          // tiles the wave does not have repeat its last one (or the row's last)
     cur_t0 = uint32_t(cur_nt) * uint32_t(KT) + uint32_t(min(ktw0, KT - 1));
   };
   auto cur_advance = [&]() {
-    const int padded = (cur_ntr + B - 1) / B * B;
-    if (cur_i + 1 < padded) {
-      cur_i += 1;
-    } else if (cur_ph + 1 < P) {
-      cur_i = 0; cur_ph += 1;
-    } else if (cur_sb0 + sb_rows < ntr_all) {
-      cur_i = 0; cur_ph = 0; cur_sb0 += sb_rows; cur_ntr = min(sb_rows, ntr_all - cur_sb0);
-    }                                                    // else: past the end, the last row is requested again
+    cur_i += 1;
     cur_derive();
   };
   auto issue_tile = [&](int d, int t) {                  // d, t are compile-time constants at every call
@@ -279,9 +265,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   };
   // ---- this wave's slice of the activations, as matrix-core operands ---------------------------------------------
   u32x4 areg[KPW][AJ][MT];
-  auto load_a = [&](int ph) {
-    const int ktw0 = ph * PHASE_KT + wave * KPW;
-    const int nkt = max(0, min(KPW, KT - ktw0));
+  auto load_a = [&]() {
 #pragma unroll
     for (int t = 0; t < KPW; ++t)
 #pragma unroll
@@ -296,7 +280,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
         }
   };
 
-  // The activations of the first phase are requested before any weight: a compute unit serves its requests
+  // The activations are requested before any weight: a compute unit serves its requests
   // in order, and once the 8 waves have filled its queues with ring loads (misses to HBM), a load that hits
   // in L2 issued behind them would still wait for them all.
 #pragma unroll
@@ -308,7 +292,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
       out_row[mt][r] = out_row[mt][r] * T + (m % T);
     }
   }
-  load_a(0);
+  load_a();
   cur_derive();
 #pragma unroll
   for (int d = 0; d < D; ++d) {
@@ -317,14 +301,9 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
     cur_advance();
   }
 
-  for (int sb0 = 0; sb0 < ntr_all; sb0 += sb_rows) {
-    const int ntr = min(sb_rows, ntr_all - sb0);
-    for (int ph = 0; ph < P; ++ph) {
-      const int ktw0 = ph * PHASE_KT + wave * KPW;                 // first k-tile of this wave in this phase
-      const int nkt = max(0, min(KPW, KT - ktw0));                 // its k-tiles (0 .. KPW)
-
-      // ---- the activations of this phase (the first phase's are already on their way) and their row sums ----
-      if (sb0 > 0 || ph > 0) load_a(ph);
+  {
+    {
+      // ---- row sums of this wave's slice of the activations ------------------------------------------------
       // group formats: xs_op[mt][g], lane (lr, lq) = sum of row lr over group g of k-tile lq: the A operand of
       //   the fp32 matrix-core operation that removes offset and zero-point;
       // per-channel formats: xs_c[mt], register r of lane (lr, lq) = sum of row 4 lq + r over the wave's k-tiles.
@@ -514,7 +493,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
         {
           const int item = wave / WPI, r0 = (wave % WPI) * RPW;    // uniform over the wave
           const int ib = item / MT, mt_dyn = item % MT;            // tile row (or pair) inside the batch, 16-row block
-          const int i_first = i0 + ib * NV;                        // tile row index inside the super-batch
+          const int i_first = i0 + ib * NV;                        // tile row index
           if (i_first < ntr) {
             float v[NV][RPW];
 #pragma unroll
@@ -532,22 +511,8 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
                 }
               }
             }
-            if (P > 1) {                                           // running sums between phases (same thread every phase)
-              uint8_t* tp = totl + (((bi % TOT_BATCHES) * BMT + item * NV) * 64 + lane) * 16 + r0 * 4;
-#pragma unroll
-              for (int s = 0; s < NV; ++s)
-#pragma unroll
-                for (int rr = 0; rr < RPW; ++rr) {
-                  float* t = reinterpret_cast<float*>(tp + s * 64 * 16) + rr;
-                  if (ph > 0) {
-                    if constexpr (A8) v[s][rr] = __int_as_float(__float_as_int(v[s][rr]) + __float_as_int(*t));
-                    else v[s][rr] += *t;
-                  }
-                  if (ph + 1 < P) *t = v[s][rr];
-                }
-            }
-            if (ph + 1 == P) {
-              const int i_glob = sb0 + i_first;
+            {
+              const int i_glob = i_first;
               const int nt = GATEUP ? u0 + (i_glob >> 1) : u0 + i_glob;
               const int ncol = nt * 16 + lr;
 #pragma unroll
@@ -582,7 +547,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
           }
         }
       }
-      __syncthreads();          // the partial-sum buffers are free again before the next phase writes them
+      __syncthreads();          // the partial-sum buffers are free again before the next pass writes them
     }
   }
 }

@@ -194,18 +194,22 @@ int32_t moqe_unpack_qmat(const moqe_qmat* packed, int16_t* q_minus_z, float* sca
  *           load), or already in bucket order when perm == NULL.
  *   offsets device int32 [K+1] in samples;  perm device int32 [S] or NULL.
  *   experts host array of K packed matrices with equal n and k.
- *   y       device float [S*T, n]; scatter = 1 writes each row at its caller-order position
- *           (needs perm), scatter = 0 writes bucket order.
+ *   y       device float [S*T, n] (bfloat16 with MOQE_OUTPUT_BF16); scatter = 1 writes each row at
+ *           its caller-order position (needs perm), scatter = 0 writes bucket order.
  *   scatter is a bit set: MOQE_SCATTER_OUTPUT (1) as above; MOQE_INPUT_IN_BUCKET_ORDER (2) says
- *           that a is already in bucket order although perm is given.  A stack of layers that is
- *           routed and bucketed once (the router selects the expert for the whole model, Section
- *           3.1) runs its first layer with perm and scatter 0, the inner layers with perm NULL, and
- *           its last layer with perm and scatter 3; activations stay in bucket order in between.
+ *           that a is already in bucket order although perm is given; MOQE_OUTPUT_BF16 (4) rounds
+ *           each result once to bfloat16 (nearest even) and stores y as 16-bit rows, which is the
+ *           input type of the next layer.  A stack of layers that is routed and bucketed once (the
+ *           router selects the expert for the whole model, Section 3.1) runs its first layer with
+ *           perm and scatter 4, the inner layers with perm NULL and scatter 4, and its last layer with
+ *           perm and scatter 3: activations stay in bucket order and in bfloat16 in between, and
+ *           nothing but this library touches them.
  * The integer codes enter bf16 matrix cores exactly and the fp32 scale is applied to fp32
  * partial sums per group, so no weight is rounded.  act_mode 1 experts quantize their rows
  * to int8 first (workspace). */
 #define MOQE_SCATTER_OUTPUT          1
 #define MOQE_INPUT_IN_BUCKET_ORDER   2
+#define MOQE_OUTPUT_BF16             4
 size_t  moqe_grouped_qgemm_workspace_bytes(const moqe_qmat* experts, int32_t K, int32_t S, int32_t T);
 int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t* perm,
                            int32_t S, int32_t T, const moqe_qmat* experts, int32_t K,

@@ -95,6 +95,7 @@ def _load() -> C.CDLL:
 lib = _load()
 SCATTER_OUTPUT = 1
 INPUT_IN_BUCKET_ORDER = 2
+OUTPUT_BF16 = 4
 
 EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
             "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",

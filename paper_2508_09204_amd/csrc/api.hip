@@ -173,7 +173,7 @@ static GemmPath choose_path(long long M, int T) {
 // Enqueues one grouped GEMM (plus the int8 row quantization its act_mode-1 experts need).
 static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t* a_perm, const int32_t* y_perm, int S, int T,
                            const moqe_qmat* experts, const moqe_qmat* second, int K, const GroupedPlan& gp, void* y,
-                           uint8_t* a8_ws, hipStream_t st, int conv_h = 0, int conv_w = 0, int conv_c = 0) {
+                           uint8_t* a8_ws, hipStream_t st, int conv_h = 0, int conv_w = 0, int conv_c = 0, bool y_bf16 = false) {
   // conv_c > 0: a is the NHWC image and the tiled kernel gathers the 3x3 neighbourhoods itself
   GemmArgs ga;
   memset(&ga, 0, sizeof(ga));
@@ -182,6 +182,7 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
   ga.S = S; ga.T = T;
   ga.a = a; ga.offsets = offsets; ga.a_perm = a_perm; ga.y_perm = y_perm; ga.y = y;
   ga.conv_h = conv_h; ga.conv_w = conv_w; ga.conv_c = conv_c;
+  ga.y_bf16 = (y_bf16 && !second) ? 1 : 0;
   for (int e = 0; e < K; ++e) fill_expert(experts[e], second ? &second[e] : nullptr, gp.pi[e], &ga.ex[e]);
   const int M = S * T;
   if (gp.any_a8) {
@@ -359,7 +360,7 @@ int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t*
   if (S == 0) return MOQE_OK;
   if (!a || !offsets || !y) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: a, offsets or y is NULL");
   if (!aligned(a, 16) || !aligned(y, 16)) return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: a and y must be 16-byte aligned");
-  if (scatter & ~(MOQE_SCATTER_OUTPUT | MOQE_INPUT_IN_BUCKET_ORDER))
+  if (scatter & ~(MOQE_SCATTER_OUTPUT | MOQE_INPUT_IN_BUCKET_ORDER | MOQE_OUTPUT_BF16))
     return set_error(MOQE_E_SHAPE, "moqe_grouped_qgemm: unknown bits in scatter=%d", scatter);
   if ((scatter & MOQE_SCATTER_OUTPUT) && !perm) return set_error(MOQE_E_NULL, "moqe_grouped_qgemm: scatter needs perm");
   const size_t need = a8_bytes(gp.any_a8, S * T, experts[0].k);
@@ -368,7 +369,8 @@ int32_t moqe_grouped_qgemm(const void* a, const int32_t* offsets, const int32_t*
   if (dry_run()) return MOQE_OK;
   return run_grouped(a, offsets, (scatter & MOQE_INPUT_IN_BUCKET_ORDER) ? nullptr : perm,
                      (scatter & MOQE_SCATTER_OUTPUT) ? perm : nullptr, S, T, experts, nullptr, K, gp, y,
-                     static_cast<uint8_t*>(workspace), static_cast<hipStream_t>(stream));
+                     static_cast<uint8_t*>(workspace), static_cast<hipStream_t>(stream), 0, 0, 0,
+                     (scatter & MOQE_OUTPUT_BF16) != 0);
 }
 
 // ---- the whole block -----------------------------------------------------------------------

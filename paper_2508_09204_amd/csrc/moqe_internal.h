@@ -158,7 +158,8 @@ struct GemmArgs {
   const int32_t* offsets;    // [K+1] samples
   const int32_t* a_perm;     // bucket slot -> sample for reading a; NULL: a is in bucket order
   const int32_t* y_perm;     // bucket slot -> sample for writing y; NULL: bucket order
-  void*     y;               // float [M, n] (plain) or bf16 [M, n] (gate/up, bucket order)
+  void*     y;               // float [M, n] (plain) or bf16 [M, n] (gate/up, bucket order; plain with y_bf16)
+  int32_t   y_bf16;          // plain launch: results are rounded to bf16 (nearest even) and stored as 16-bit rows
   int32_t   conv_h, conv_w, conv_c;   // tiled kernel, 3x3 convolution: a is the NHWC image [S, h, w, c] and the
                              // k = (kh*3 + kw)*c + ch columns of a row are gathered from its pixel's neighbours
   int32_t   min_rows, max_rows;   // this launch handles the experts whose bucket has min_rows .. max_rows rows

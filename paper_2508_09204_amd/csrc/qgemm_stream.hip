@@ -540,6 +540,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
                 if (mt_dyn * 16 + lq * 4 + r < rows_here) {
                   const size_t o = size_t(orow) * size_t(ga.n) + ncol;
                   if constexpr (GATEUP) static_cast<uint16_t*>(ga.y)[o] = float_to_bf16_rne(silu_mul(val[0], val[NV - 1]));
+                  else if (ga.y_bf16) static_cast<uint16_t*>(ga.y)[o] = float_to_bf16_rne(val[0]);
                   else static_cast<float*>(ga.y)[o] = val[0];
                 }
               }

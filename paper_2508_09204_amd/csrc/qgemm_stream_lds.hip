@@ -387,9 +387,15 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
             } else {
               size_t drow = brow;
               if (ga.y_perm) drow = size_t(ga.y_perm[off_e + m / T]) * T + (m % T);
-              float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
-              if (sv[0]) y[nt[0] * 16 + lr] = val[0];
-              if (sv[1]) y[nt[1] * 16 + lr] = val[1];
+              if (ga.y_bf16) {
+                uint16_t* y = static_cast<uint16_t*>(ga.y) + drow * size_t(ga.n);
+                if (sv[0]) y[nt[0] * 16 + lr] = float_to_bf16_rne(val[0]);
+                if (sv[1]) y[nt[1] * 16 + lr] = float_to_bf16_rne(val[1]);
+              } else {
+                float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
+                if (sv[0]) y[nt[0] * 16 + lr] = val[0];
+                if (sv[1]) y[nt[1] * 16 + lr] = val[1];
+              }
             }
           }
         }

@@ -340,10 +340,17 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
         } else {
           size_t drow = brow;
           if (ga.y_perm) drow = size_t(ga.y_perm[off_e + m / T]) * T + (m % T);
-          float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
+          if (ga.y_bf16) {
+            uint16_t* y = static_cast<uint16_t*>(ga.y) + drow * size_t(ga.n);
 #pragma unroll
-          for (int b = 0; b < TNB; ++b)
-            if (nok[b]) y[ncol[b]] = val[b];
+            for (int b = 0; b < TNB; ++b)
+              if (nok[b]) y[ncol[b]] = float_to_bf16_rne(val[b]);
+          } else {
+            float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
+#pragma unroll
+            for (int b = 0; b < TNB; ++b)
+              if (nok[b]) y[ncol[b]] = val[b];
+          }
         }
       }
     }

@@ -124,7 +124,8 @@ def test_grouped_qgemm_argument_errors(mq):
     assert call(FAKE, FAKE, None, 4, 1, ex, 2, FAKE, 1, None, 0) == -1          # scatter without perm
     assert call(FAKE, FAKE, FAKE, 4, 1, ex, 2, FAKE, 3, None, 0) == 0           # bucket-order input, scattered output
     assert call(FAKE, FAKE, None, 4, 1, ex, 2, FAKE, 3, None, 0) == -1
-    assert call(FAKE, FAKE, FAKE, 4, 1, ex, 2, FAKE, 4, None, 0) == -2          # unknown flag bit
+    assert call(FAKE, FAKE, FAKE, 4, 1, ex, 2, FAKE, 4, None, 0) == 0           # bf16 output
+    assert call(FAKE, FAKE, FAKE, 4, 1, ex, 2, FAKE, 8, None, 0) == -2          # unknown flag bit
     assert call(FAKE, FAKE, FAKE, 4, 0, ex, 2, FAKE, 1, None, 0) == -2
     assert call(FAKE, FAKE, FAKE, 4, 1, ex, 0, FAKE, 1, None, 0) == -2
     assert call(FAKE + 2, FAKE, FAKE, 4, 1, ex, 2, FAKE, 1, None, 0) == -2      # misaligned activations

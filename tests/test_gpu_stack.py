@@ -36,29 +36,34 @@ def test_three_layer_stack_bucketed_once(S, T):
 
     packed = [[gb.packed_dev(q) for q in L] for L in layers]
     x0 = gb.bf16_dev(a_bits.reshape(S * T, dims[0]))
-    y1 = torch.empty((S * T, dims[1]), dtype=torch.float32, device=gb.DEV)
-    mq.moqe_grouped_qgemm(x0, offs_d, perm_d, S, T, packed[0], y1, 0)                          # gather, bucket order out
-    x1 = y1.to(torch.bfloat16)
-    y2 = torch.empty((S * T, dims[2]), dtype=torch.float32, device=gb.DEV)
-    mq.moqe_grouped_qgemm(x1, offs_d, None, S, T, packed[1], y2, 0)                            # bucket order in and out
-    x2 = y2.to(torch.bfloat16)
+    # every tensor between the layers is written and read by the library alone: bf16, bucket order
+    x1 = torch.full((S * T, dims[1]), float("nan"), dtype=torch.bfloat16, device=gb.DEV)
+    mq.moqe_grouped_qgemm(x0, offs_d, perm_d, S, T, packed[0], x1, mq.OUTPUT_BF16)             # gather, bucket order out
+    x2 = torch.full((S * T, dims[2]), float("nan"), dtype=torch.bfloat16, device=gb.DEV)
+    mq.moqe_grouped_qgemm(x1, offs_d, None, S, T, packed[1], x2, mq.OUTPUT_BF16)               # bucket order in and out
     y3 = torch.full((S * T, dims[3]), float("nan"), dtype=torch.float32, device=gb.DEV)
     mq.moqe_grouped_qgemm(x2, offs_d, perm_d, S, T, packed[2], y3,
                           mq.SCATTER_OUTPUT | mq.INPUT_IN_BUCKET_ORDER)                        # scatter only here
     torch.cuda.synchronize()
 
-    # stage-wise against the oracle: each layer on the bfloat16 input the GPU actually fed it
+    # stage-wise against the oracle: each layer on the bfloat16 input the GPU actually fed it; a bf16 output
+    # must be the oracle's fp64 result rounded once, give or take one bf16 step where fp32 accumulation lands
+    # on the other side of a rounding boundary
     x0_f = oc.bf16_bits_to_f64(a_bits).reshape(S, T, dims[0])
-    y1_g = y1.cpu().numpy().reshape(S, T, dims[1])[inv]       # bucket order -> caller order
-    x1_f = gb.bf16_tensor_to_f64(x1).reshape(S, T, dims[1])[inv]
-    y2_g = y2.cpu().numpy().reshape(S, T, dims[2])[inv]
+    x1_f = gb.bf16_tensor_to_f64(x1).reshape(S, T, dims[1])[inv]      # bucket order -> caller order
     x2_f = gb.bf16_tensor_to_f64(x2).reshape(S, T, dims[2])[inv]
-    y3_g = y3.cpu().numpy().reshape(S, T, dims[3])            # already in caller order
-    assert np.all(np.isfinite(y3_g))
+    y3_g = y3.cpu().numpy().reshape(S, T, dims[3])                    # already in caller order
+    assert np.all(np.isfinite(x1_f)) and np.all(np.isfinite(x2_f)) and np.all(np.isfinite(y3_g))
+    flips = 0
     for s in range(S):
         k = int(e[s])
-        for (xin, yout, L) in ((x0_f, y1_g, layers[0]), (x1_f, y2_g, layers[1]), (x2_f, y3_g, layers[2])):
-            ok, worst = ob.tolerance_ok(yout[s], oc.qlinear(xin[s], L[k]))
-            assert ok, (s, k, worst)
-    # and the intermediate roundings are those of the values the GPU produced (round to nearest even)
-    assert np.array_equal(gb.bf16_tensor_to_f64(x1).reshape(-1), oc.bf16_round(y1.cpu().numpy().astype(np.float64)).reshape(-1))
+        for (xin, xout, L) in ((x0_f, x1_f, layers[0]), (x1_f, x2_f, layers[1])):
+            ref = oc.qlinear(xin[s], L[k])
+            ref16 = oc.bf16_round(ref)
+            rms = float(np.sqrt(np.mean(ref * ref)))
+            step = np.maximum(np.abs(ref) * 2.0 ** -7, 1e-4 * rms)
+            assert np.all(np.abs(xout[s] - ref16) <= step), (s, k)
+            flips += int(np.sum(xout[s] != ref16))
+        ok, worst = ob.tolerance_ok(y3_g[s], oc.qlinear(x2_f[s], layers[2][k]))
+        assert ok, (s, k, worst)
+    assert flips < 0.02 * S * T * (dims[1] + dims[2])

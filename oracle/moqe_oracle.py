@@ -14,7 +14,9 @@ What it computes follows MoQE (arXiv 2508.09204):
   logit per expert.  Appendix "number of quantization experts": every input
   activates exactly one expert.
 * Section 3.3, Eq. (1)-(2): n_i is the number of samples of the batch
-  dispatched to expert i and F_i = n_i / B.
+  dispatched to expert i and F_i = n_i / B.  Section 3.3, first paragraph:
+  the router's training label of a sample is the expert with the lowest
+  prediction loss among all experts run on it (label_pass).
 
 The paper prints no quantizer, no rounding rule and no batching scheme.  The
 readings used here (round-to-nearest quantizers, tie rule, stable bucketing,
@@ -397,6 +399,42 @@ def expert_forward(blk: Block, e: int, xs: np.ndarray) -> np.ndarray:
         img = xs.reshape(blk.img_h, blk.img_w, blk.cin)
         return conv3x3(img, blk.w0[e], blk.cin).reshape(blk.img_h * blk.img_w, -1)
     raise ValueError("unknown block kind")
+
+
+def cross_entropy_rows(y: np.ndarray, targets: Sequence[int]) -> np.ndarray:
+    """Prediction loss of rows of logits y [m, n] against class indices targets [m]:
+    CE_r = log(sum_c exp(y[r, c])) - y[r, targets[r]]  (the negative log of the softmax probability of the target)."""
+    y = np.asarray(y, dtype=np.float64)
+    t = np.asarray(targets, dtype=np.int64)
+    mx = y.max(axis=1)
+    lse = mx + np.log(np.exp(y - mx[:, None]).sum(axis=1))
+    return lse - y[np.arange(y.shape[0]), t]
+
+
+def label_pass(blk: Block, x: np.ndarray, targets: np.ndarray):
+    """The router's training labels (Section 3.3, first paragraph): every sample goes through ALL experts,
+    each expert's prediction loss on the sample is computed, and the expert with the lowest loss is the
+    sample's label (ties: the lowest index).  The prediction loss of a sample is the mean cross-entropy of
+    its rows' logits f_j(x_s) [T, n] against the rows' target classes (the loss of both of the paper's task
+    families: next-token prediction and classification).  x fp64 [S, T, D] holding bfloat16 values, targets
+    int [S, T].  Returns (losses fp64 [S, K], labels int32 [S]).  LINEAR and SILU_MLP blocks."""
+    if blk.kind == KIND_CONV3X3:
+        raise ValueError("the label pass is defined for blocks whose rows are logits")
+    x = np.asarray(x, dtype=np.float64)
+    S, K = x.shape[0], blk.n_experts
+    losses = np.zeros((S, K), dtype=np.float64)
+    for s in range(S):
+        for j in range(K):
+            y = expert_forward(blk, j, x[s])
+            losses[s, j] = cross_entropy_rows(y, targets[s]).sum() / y.shape[0]
+    labels = np.zeros(S, dtype=np.int32)
+    for s in range(S):
+        best = 0
+        for j in range(1, K):
+            if losses[s, j] < losses[s, best]:
+                best = j
+        labels[s] = best
+    return losses, labels
 
 
 def forward_ragged(blk: Block, xs: Sequence[np.ndarray]):

@@ -8,6 +8,7 @@ yields the same bits no matter which consumer asks or in which order:
     child m      : router first layer
     child m+1    : router second layer
     child m+2    : activations
+    child m+3    : target classes of the label pass
 
 Activations are stored at the library boundary as bfloat16.  The only
 arithmetic here is the storage conversion fp32 -> bf16 bits (round to
@@ -82,3 +83,10 @@ def make_activations(cfg: WorkloadConfig, S: Optional[int] = None) -> np.ndarray
     S = cfg.S if S is None else S
     x = ss[m + 2].standard_normal((S, cfg.T, cfg.D), dtype=np.float32)
     return f32_to_bf16_bits(x)
+
+
+def make_targets(cfg: WorkloadConfig, n_classes: int) -> np.ndarray:
+    """Target class per row for the label pass, int32 [S, T], uniform in [0, n_classes) (child stream m+3)."""
+    ss = _streams(cfg)
+    m = len(cfg.matrices())
+    return ss[m + 3].integers(0, n_classes, size=(cfg.S, cfg.T), dtype=np.int64).astype(np.int32)

@@ -151,6 +151,22 @@ int32_t moqe_bucket(const int32_t* expert_idx, int32_t S, int32_t K,
                     int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                     void* stream);
 
+/* The router's training labels (Section 3.3, first paragraph).  Every sample is run through ALL K experts
+ * of the block, the prediction loss of each expert on the sample is computed, and the expert with the
+ * lowest loss becomes the sample's label (ties: the lowest index).  The prediction loss of expert j on
+ * sample s is the mean over the sample's T rows of the cross-entropy of the row's logits f_j(x_s)[t, :]
+ * against targets[s, t]:  log(sum_c exp(logit_c)) - logit_target.  The router of the block is not used.
+ *   blk     : LINEAR or SILU_MLP block (n = width of the logits); CONV3X3 is MOQE_E_FORMAT
+ *   x       : device bf16 [S, T, d], 16-byte aligned;  targets: device int32 [S, T], values in [0, n)
+ *             (a value outside is clamped into the range)
+ *   losses  : device float [S, K] out;  labels: device int32 [S] out
+ * The K forward passes are one grouped launch over K*S virtual samples in bucket order; logits fp32 in
+ * the workspace, loss arithmetic fp32 with a fixed summation order (deterministic).  S*T*K rows must fit
+ * int32 and the MLP's intermediate [S*T*K, F] bf16 must stay below 4 GiB.  S == 0 is a no-op. */
+size_t moqe_label_pass_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T);
+int32_t moqe_label_pass(const moqe_block* blk, const void* x, const int32_t* targets, int32_t S, int32_t T,
+                        float* losses, int32_t* labels, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Load-balance statistics of one routed batch (Section 3.2, Eq. 1-2), from the logits that
  * moqe_route wrote and the counts of moqe_bucket:
  *   P_i = mean over the S samples of softmax(logits[s, :])_i,   F_i = counts[i] / S,

@@ -78,6 +78,8 @@ def _load() -> C.CDLL:
         "moqe_workspace_bytes": (sz, [C.POINTER(_Block), i32, i32]),
         "moqe_forward": (i32, [C.POINTER(_Block), vp, i32, i32, vp, C.POINTER(_Aux), vp, sz, vp]),
         "moqe_forward_static": (i32, [C.POINTER(_Block), vp, i32, i32, vp, C.POINTER(_Aux), vp]),
+        "moqe_label_pass_workspace_bytes": (sz, [C.POINTER(_Block), i32, i32]),
+        "moqe_label_pass": (i32, [C.POINTER(_Block), vp, vp, i32, i32, vp, vp, vp, sz, vp]),
         "moqe_cache_create": (i32, [C.POINTER(vp), C.POINTER(vp), C.POINTER(sz), i32, i32]),
         "moqe_cache_destroy": (i32, [vp]),
         "moqe_cache_acquire": (i32, [vp, C.POINTER(i32), i32, C.POINTER(vp), C.POINTER(i32), vp]),
@@ -101,7 +103,7 @@ EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_
             "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",
             "moqe_expand_rows", "moqe_workspace_bytes_ragged", "moqe_forward_ragged", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
-            "moqe_workspace_bytes", "moqe_forward", "moqe_forward_static", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
+            "moqe_workspace_bytes", "moqe_forward", "moqe_forward_static", "moqe_label_pass_workspace_bytes", "moqe_label_pass", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
             "moqe_cache_stats", "moqe_profile_enable", "moqe_profile_read"]
 
 
@@ -315,6 +317,20 @@ def moqe_forward(blk: Block, x: torch.Tensor, S: int, T: int, y: torch.Tensor, a
     a = aux.c() if aux is not None else None
     _check(lib.moqe_forward(C.byref(b), _ptr(x), S, T, _ptr(y), C.byref(a) if a is not None else None,
                             _ptr(workspace), workspace.numel(), _stream()))
+
+
+def moqe_label_pass_workspace_bytes(blk: Block, S: int, T: int) -> int:
+    b = blk.c()
+    return lib.moqe_label_pass_workspace_bytes(C.byref(b), S, T)
+
+
+def moqe_label_pass(blk: Block, x: torch.Tensor, targets: torch.Tensor, S: int, T: int, losses: torch.Tensor,
+                    labels: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:
+    b = blk.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_label_pass_workspace_bytes(C.byref(b), S, T), x.device)
+    _check(lib.moqe_label_pass(C.byref(b), _ptr(x), _ptr(targets), S, T, _ptr(losses), _ptr(labels),
+                               _ptr(workspace), workspace.numel(), _stream()))
 
 
 STATIC_SCRATCH_BYTES = 16 << 20

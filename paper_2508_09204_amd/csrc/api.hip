@@ -553,6 +553,96 @@ int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T,
 }
 }  // namespace
 
+// ---- the router's training labels ------------------------------------------------------------
+namespace {
+struct LabelLayout {
+  size_t offsets, perm, y, h, a8, total;
+  int n_out;
+};
+
+int32_t label_layout(const moqe_block* b, int S, int T, LabelLayout* L, GroupedPlan* gp0, GroupedPlan* gp2) {
+  const char* who = "moqe_label_pass";
+  if (!b) return set_error(MOQE_E_NULL, "%s: block is NULL", who);
+  const int K = b->n_experts;
+  if (K < 1 || K > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "%s: n_experts=%d outside [1, %d]", who, K, MOQE_MAX_EXPERTS);
+  if (b->kind != MOQE_KIND_LINEAR && b->kind != MOQE_KIND_SILU_MLP)
+    return set_error(MOQE_E_FORMAT, "%s: kind %d (the rows of the block's output must be logits)", who, b->kind);
+  if (S < 0 || T <= 0 || (long long)S * T * K > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "%s: S=%d T=%d K=%d", who, S, T, K);
+  if (!b->w0) return set_error(MOQE_E_NULL, "%s: w0 is NULL", who);
+  const bool mlp = b->kind == MOQE_KIND_SILU_MLP;
+  int32_t rc = plan_experts(b->w0, K, mlp ? b->w1 : nullptr, gp0, who);
+  if (rc) return rc;
+  if (mlp) {
+    if (!b->w1 || !b->w2) return set_error(MOQE_E_NULL, "%s: SILU_MLP needs w1 and w2", who);
+    rc = plan_experts(b->w2, K, nullptr, gp2, who);
+    if (rc) return rc;
+    if (b->w2[0].k != b->w0[0].n) return set_error(MOQE_E_SHAPE, "%s: down takes %d features, gate/up give %d", who, b->w2[0].k, b->w0[0].n);
+  }
+  const long long MV = (long long)S * T * K;                 // rows of the K*S virtual samples
+  rc = check_activation_bytes((long long)S * T, b->w0[0].k, who);
+  if (rc) return rc;
+  if (mlp) {
+    rc = check_activation_bytes(MV, b->w0[0].n, who);
+    if (rc) return rc;
+  }
+  L->n_out = mlp ? b->w2[0].n : b->w0[0].n;
+  size_t o = 0;
+  L->offsets = o; o += align256(size_t(K + 1) * 4);
+  L->perm = o;    o += align256(size_t(K) * S * 4);
+  L->y = o;       o += align256(size_t(MV) * L->n_out * 4);
+  L->h = o;
+  if (mlp) o += align256(size_t(MV) * size_t(b->w0[0].n) * 2);
+  L->a8 = o;
+  {
+    bool any = gp0->any_a8 || (mlp && gp2->any_a8);
+    int kmax = b->w0[0].k;
+    if (mlp) kmax = std::max(kmax, b->w2[0].k);
+    o += a8_bytes(any, int(MV), kmax);
+  }
+  L->total = o;
+  return MOQE_OK;
+}
+}  // namespace
+
+size_t moqe_label_pass_workspace_bytes(const moqe_block* blk, int32_t S, int32_t T) {
+  LabelLayout L;
+  GroupedPlan g0, g2;
+  if (label_layout(blk, S, T, &L, &g0, &g2)) return 0;
+  return L.total;
+}
+
+int32_t moqe_label_pass(const moqe_block* blk, const void* x, const int32_t* targets, int32_t S, int32_t T, float* losses,
+                        int32_t* labels, void* workspace, size_t workspace_bytes, void* stream) {
+  LabelLayout L;
+  GroupedPlan g0, g2;
+  int32_t rc = label_layout(blk, S, T, &L, &g0, &g2);
+  if (rc) return rc;
+  if (S == 0) return MOQE_OK;
+  if (!x || !targets || !losses || !labels) return set_error(MOQE_E_NULL, "moqe_label_pass: x, targets, losses or labels is NULL");
+  if (!aligned(x, 16)) return set_error(MOQE_E_SHAPE, "moqe_label_pass: x must be 16-byte aligned");
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total)
+    return set_error(MOQE_E_WORKSPACE, "moqe_label_pass: workspace needs %zu bytes, 256-byte aligned", L.total);
+  if (dry_run()) return MOQE_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* ws = static_cast<uint8_t*>(workspace);
+  const int K = blk->n_experts;
+  int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
+  int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
+  float* yv = reinterpret_cast<float*>(ws + L.y);
+  rc = launch_label_dispatch(S, K, offsets, perm, st);
+  if (rc) return rc;
+  // K*S virtual samples, expert j's bucket = every sample; the logits stay in bucket order
+  if (blk->kind == MOQE_KIND_LINEAR) {
+    rc = run_grouped(x, offsets, perm, nullptr, K * S, T, blk->w0, nullptr, K, g0, yv, ws + L.a8, st);
+  } else {
+    rc = run_grouped(x, offsets, perm, nullptr, K * S, T, blk->w0, blk->w1, K, g0, ws + L.h, ws + L.a8, st);
+    if (rc) return rc;
+    rc = run_grouped(ws + L.h, offsets, nullptr, nullptr, K * S, T, blk->w2, nullptr, K, g2, yv, ws + L.a8, st);
+  }
+  if (rc) return rc;
+  return launch_label_loss(yv, targets, S, T, L.n_out, K, losses, labels, st);
+}
+
 // ---- the whole block, samples of different lengths -------------------------------------------
 namespace {
 struct RaggedLayout {

@@ -197,6 +197,9 @@ int32_t launch_route_bucket(const void* x, int S, int T, const moqe_router& r, i
                             int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t st);
 int32_t launch_bucket(const int32_t* idx, int S, int K, int32_t* counts, int32_t* offsets,
                       int32_t* perm, int32_t* inv_perm, hipStream_t st);
+int32_t launch_label_dispatch(int S, int K, int32_t* offsets, int32_t* perm, hipStream_t st);
+int32_t launch_label_loss(const float* y, const int32_t* targets, int S, int T, int n, int K, float* losses, int32_t* labels,
+                          hipStream_t st);
 int32_t launch_balance_stats(const float* logits, const int32_t* counts, int S, int K, float alpha, float* out,
                              hipStream_t st);
 int32_t launch_quantize(const float* w, float clip, const moqe_qmat& out, hipStream_t st);

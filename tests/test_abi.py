@@ -173,6 +173,18 @@ def test_route_and_forward_argument_errors(mq):
     assert lib.moqe_workspace_bytes(C.byref(blk), 4096, 8) > (16 << 20)
     assert lib.moqe_forward_static(C.byref(blk), FAKE, 4096, 8, FAKE, None, None) == -4
     assert b"built-in" in lib.moqe_last_error_string()
+    # the label pass: all K experts on every sample, so K times the rows of a routed forward
+    lneed = lib.moqe_label_pass_workspace_bytes(C.byref(blk), 4, 3)
+    assert lneed >= 2 * 4 * 3 * (256 * 4 + 512 * 2)
+    assert lib.moqe_label_pass(C.byref(blk), FAKE, FAKE, 4, 3, FAKE, FAKE, FAKE, lneed, None) == 0
+    assert lib.moqe_label_pass(C.byref(blk), FAKE, FAKE, 0, 3, None, None, None, 0, None) == 0
+    assert lib.moqe_label_pass(C.byref(blk), FAKE, FAKE, 4, 3, FAKE, FAKE, FAKE, lneed - 256, None) == -4
+    assert lib.moqe_label_pass(C.byref(blk), FAKE, None, 4, 3, FAKE, FAKE, FAKE, lneed, None) == -1
+    assert lib.moqe_label_pass(C.byref(blk), FAKE, FAKE, 4, 3, FAKE, None, FAKE, lneed, None) == -1
+    assert lib.moqe_label_pass(C.byref(blk), FAKE, FAKE, 1 << 20, 1 << 10, FAKE, FAKE, FAKE, lneed, None) == -2
+    conv = mq._Block(2, r, gate, None, None, 2, 2, 2, 256)
+    assert lib.moqe_label_pass(C.byref(conv), FAKE, FAKE, 4, 4, FAKE, FAKE, FAKE, lneed, None) == -3
+    assert lib.moqe_label_pass_workspace_bytes(C.byref(conv), 4, 4) == 0
     mixed = (mq._QMat * 2)(_qmat(mq, n=512, k=256, bits=3), _qmat(mq, n=512, k=256, bits=8, group=0, sym=1))
     blk2 = mq._Block(1, r, gate, mixed, down, 2, 0, 0, 0)
     assert lib.moqe_forward(C.byref(blk2), FAKE, 4, 3, FAKE, None, FAKE, need, None) == -3   # gate/up formats differ

@@ -23,6 +23,9 @@
 //    extra roundings are one fp32 multiply per group on the accumulator.
 #include "qgemm_device.h"
 
+#include <algorithm>
+#include <cstring>
+
 namespace moqe {
 
 constexpr int TBM = 64;                  // bucket rows per work-group tile
@@ -33,9 +36,16 @@ constexpr int TBN = TWN * TNB * 16;      // 256 weight rows per work-group tile
 constexpr int T_SLOT = 256;              // LDS bytes per staged row and k-step (int8 rows use half)
 constexpr int T_LDS_BYTES = 2 * TBM * T_SLOT;
 
+// What the launcher works out on the host for one launch.
+struct TileGeom {
+  uint64_t order_bits;                // 4 bits per position: experts in the order their row tiles are enumerated, dearest format first
+  int32_t  patch_n_log2;              // a patch is 2^patch_n_log2 weight tiles x PATCH_M row tiles
+  uint32_t conv_c_magic;              // ceil(2^32 / conv_c): column / conv_c = umulhi(column, magic) for every column < 9 * conv_c
+};
+
 template <int FMT, int GM, bool GATEUP, bool CONV>
-static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int m0,
-                                                 const int ntile, uint8_t* lds) {
+static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileGeom& tg, const ExpertDev& ex, const int off_e, const int M_e,
+                                                 const int m0, const int ntile, uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
   constexpr int NR = Raw<FMT>::N;
   constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
@@ -51,8 +61,6 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
   const int wm = wave / TWN, wn = wave % TWN;
   const int KT = ga.k >> 7, NT = ga.n >> 4;
   const int T = ga.T;
-  const int off_e = ga.offsets[e];
-  const int M_e = (ga.offsets[e + 1] - off_e) * T;
   const float off_sym = BASE + CM * float(ex.zc);
   const FragK<FMT> fk = frag_constants<FMT>();
 
@@ -80,7 +88,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
   const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
   uint32_t a_off[A_ITERS];
   const int a_unit = tid % A_UNITS, a_row0 = tid / A_UNITS;
-  int a_py[CONV ? A_ITERS : 1], a_px[CONV ? A_ITERS : 1];       // convolution: the row's pixel inside its image
+  uint32_t a_taps[CONV ? A_ITERS : 1];       // convolution: bit t set = filter tap t of the row's pixel lies inside its image
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
     const int m = min(m0 + a_row0 + i * A_ROWS_PER_IT, M_e - 1);      // rows past the bucket repeat its last row
@@ -89,37 +97,56 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
     else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
     else src = size_t(off_e) * T + m;
     if constexpr (CONV && !A8) {
-      a_off[i] = uint32_t(src);                                       // pixel index in the NHWC image
+      a_off[i] = uint32_t(src * size_t(ga.conv_c) * 2);              // byte offset of the pixel in the NHWC image
       const int p = int(src % size_t(T));
-      a_py[i] = p / ga.conv_w;
-      a_px[i] = p - a_py[i] * ga.conv_w;
+      const int py = p / ga.conv_w, px = p - py * ga.conv_w;
+      uint32_t taps = 0;
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const int yy = py + t / 3 - 1, xx = px + t % 3 - 1;
+        if (yy >= 0 && yy < ga.conv_h && xx >= 0 && xx < ga.conv_w) taps |= 1u << t;
+      }
+      a_taps[i] = taps;
     } else {
       a_off[i] = uint32_t(src * size_t(ga.k) * EB + a_unit * 16);
     }
   }
+  // Where each of the tile's rows goes (and, for int8 activations, its scale): worked out now by the
+  // first TBM threads, one row each, handed to every lane through LDS after the main loop.  -1: no such row.
+  int my_drow = -1;
+  float my_sx = 0.f;
+  if (tid < TBM) {
+    const int m = m0 + tid;
+    if (m < M_e) {
+      my_drow = off_e * T + m;
+      if constexpr (A8) my_sx = ga.a_scale[my_drow];
+      if constexpr (!GATEUP) {
+        if (ga.y_perm) my_drow = ga.y_perm[off_e + m / T] * T + (m % T);
+      }
+    }
+  }
   u32x4 a_reg[A_ITERS];
+  uint32_t a_ok = 0u;                          // convolution: bit i = the tap of a_reg[i] lies inside the image
   // Convolution: the 8 columns of this thread's unit are 8 neighbouring channels of ONE filter tap
   // (k = tap * C + channel), i.e. 16 contiguous bytes of the pixel at that tap's offset, or zeros
-  // outside the image.  a_fetch is called for k-steps 0, 1, 2, ... in order, so tap and channel of
-  // the unit advance by 128 columns per call.
-  int cv_tap = 0, cv_c = CONV ? a_unit * 8 : 0;
-  if constexpr (CONV && !A8) {
-    while (cv_c >= ga.conv_c) { cv_c -= ga.conv_c; ++cv_tap; }
-  }
+  // outside the image.  Tap and channel follow from the unit's first column by one multiply-high.
   auto a_fetch = [&](int kt) {
     if constexpr (CONV && !A8) {
-      const int dy = cv_tap / 3 - 1, dx = cv_tap - (cv_tap / 3) * 3 - 1;
-      const bool tap_ok = cv_tap < 9;                                  // k-steps past the end are never multiplied
+      const uint32_t col = uint32_t(kt) * 128u + uint32_t(a_unit) * 8u;
+      const uint32_t tap = __umulhi(col, tg.conv_c_magic);           // k-steps past the end give taps >= 9: never multiplied
+      const int ch = int(col - tap * uint32_t(ga.conv_c));
+      const int ty = int((tap * 11u) >> 5);                           // tap / 3 for tap < 12
+      const int dy = ty - 1, dx = int(tap) - ty * 3 - 1;
+      const int delta = ((dy * ga.conv_w + dx) * ga.conv_c + ch) * 2;  // bytes from the row's pixel to the tap's channels
+      const uint32_t bit = tap < 9u ? (1u << tap) : 0u;
+      a_ok = 0u;
 #pragma unroll
       for (int i = 0; i < A_ITERS; ++i) {
-        const int yy = a_py[i] + dy, xx = a_px[i] + dx;
-        const bool ok = tap_ok && yy >= 0 && yy < ga.conv_h && xx >= 0 && xx < ga.conv_w;
-        const int pix = ok ? int(a_off[i]) + dy * ga.conv_w + dx : int(a_off[i]);      // always a valid address
-        u32x4 v = *reinterpret_cast<const u32x4*>(abase + (size_t(uint32_t(pix)) * size_t(ga.conv_c) + size_t(cv_c)) * 2);
-        a_reg[i].x = ok ? v.x : 0u; a_reg[i].y = ok ? v.y : 0u; a_reg[i].z = ok ? v.z : 0u; a_reg[i].w = ok ? v.w : 0u;
+        const bool ok = (a_taps[i] & bit) != 0u;
+        const uint32_t off = a_off[i] + uint32_t(ok ? delta : 0);     // always a valid address
+        a_reg[i] = *reinterpret_cast<const u32x4*>(abase + off);
+        a_ok |= ok ? (1u << i) : 0u;                                   // taps outside the image become zeros when the row is stored
       }
-      cv_c += 128;
-      while (cv_c >= ga.conv_c) { cv_c -= ga.conv_c; ++cv_tap; }
     } else {
       const uint32_t koff = uint32_t(min(kt, KT - 1)) * (128 * EB);
 #pragma unroll
@@ -130,7 +157,13 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
 #pragma unroll
     for (int i = 0; i < A_ITERS; ++i) {
       const int row = a_row0 + i * A_ROWS_PER_IT;
-      *reinterpret_cast<u32x4*>(buf + row * T_SLOT + ((a_unit ^ (row & 15)) * 16)) = a_reg[i];
+      u32x4 v = a_reg[i];
+      if constexpr (CONV && !A8) {
+        // the loaded words are first touched here, a k-step after the load was issued
+        const bool ok = (a_ok >> i) & 1u;
+        v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+      }
+      *reinterpret_cast<u32x4*>(buf + row * T_SLOT + ((a_unit ^ (row & 15)) * 16)) = v;
     }
   };
 
@@ -314,85 +347,117 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const Exper
       fin[b] = s_cur[b] * INV_CM;
     }
   }
+  // every wave is past its last operand read (the loop ends with a barrier): the staging buffer is free
+  int32_t* row_tab = reinterpret_cast<int32_t*>(lds);
+  float* sx_tab = reinterpret_cast<float*>(lds + TBM * 4);
+  if (tid < TBM) {
+    row_tab[tid] = my_drow;
+    if constexpr (A8) sx_tab[tid] = my_sx;
+  }
+  __syncthreads();
 #pragma unroll
   for (int mb = 0; mb < TMB; ++mb) {
+    const i32x4 drow4 = *reinterpret_cast<const i32x4*>(row_tab + wm * 64 + mb * 16 + lq * 4);
+    f32x4 sx4 = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (A8) sx4 = *reinterpret_cast<const f32x4*>(sx_tab + wm * 64 + mb * 16 + lq * 4);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int m = m0 + wm * 64 + mb * 16 + lq * 4 + r;
-      if (m < M_e) {
+      if (drow4[r] >= 0) {
         float val[TNB];
 #pragma unroll
         for (int b = 0; b < TNB; ++b) {
           if constexpr (A8) {
-            const float sx = ga.a_scale[size_t(off_e) * T + m];
-            val[b] = float(__float_as_int(tot[mb][b][r])) * sx * fin[b];
+            val[b] = float(__float_as_int(tot[mb][b][r])) * sx4[r] * fin[b];
           } else if constexpr (GM == GM_PC) {
             val[b] = (fin[b] * INV_CM) * (tot[mb][b][r] - off_sym * xs_tot[mb][r]);
           } else {
             val[b] = tot[mb][b][r] * fin[b];
           }
         }
-        const size_t brow = size_t(off_e) * T + m;
+        const size_t drow = size_t(drow4[r]);
         if constexpr (GATEUP) {
-          uint16_t* h = static_cast<uint16_t*>(ga.y) + brow * size_t(ga.n);
+          uint16_t* h = static_cast<uint16_t*>(ga.y) + drow * size_t(ga.n);
           if (nok[0]) h[ncol[0]] = float_to_bf16_rne(silu_mul(val[0], val[2]));
           if (nok[1]) h[ncol[1]] = float_to_bf16_rne(silu_mul(val[1], val[3]));
+        } else if (ga.y_bf16) {
+          uint16_t* y = static_cast<uint16_t*>(ga.y) + drow * size_t(ga.n);
+#pragma unroll
+          for (int b = 0; b < TNB; ++b)
+            if (nok[b]) y[ncol[b]] = float_to_bf16_rne(val[b]);
         } else {
-          size_t drow = brow;
-          if (ga.y_perm) drow = size_t(ga.y_perm[off_e + m / T]) * T + (m % T);
-          if (ga.y_bf16) {
-            uint16_t* y = static_cast<uint16_t*>(ga.y) + drow * size_t(ga.n);
+          float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
 #pragma unroll
-            for (int b = 0; b < TNB; ++b)
-              if (nok[b]) y[ncol[b]] = float_to_bf16_rne(val[b]);
-          } else {
-            float* y = static_cast<float*>(ga.y) + drow * size_t(ga.n);
-#pragma unroll
-            for (int b = 0; b < TNB; ++b)
-              if (nok[b]) y[ncol[b]] = val[b];
-          }
+          for (int b = 0; b < TNB; ++b)
+            if (nok[b]) y[ncol[b]] = val[b];
         }
       }
     }
   }
 }
 
-// Work-group id -> tile.  The hardware deals consecutive work-group ids round-robin to the 8 XCDs,
-// each with its own L2, so the 64 work-groups that are resident on one XCD at a time are the ids
-// x, x + 8, x + 16, ...; they are made a patch of PATCH_M row tiles x PATCH_N weight tiles, which
-// run side by side over k and share their activation and weight tiles in that L2.  Consecutive
-// patches of an XCD, and the patches of the 8 XCDs at one time, walk along the weight rows first.
-constexpr int PATCH_M = 8, PATCH_N = 8;
+// A launch with fewer than 8 weight tiles makes the patch narrower (2^patch_n_log2 weight tiles), so no
+// work-group is launched for weight tiles that do not exist, and consecutive groups of PATCH_M row
+// tiles still go round the XCDs.  Row tiles are enumerated expert by expert in the order of
+// `TileGeom::order` (formats with the most arithmetic per tile first: what runs last, when the chip
+// drains, are the cheap tiles).
+constexpr int PATCH_M = 8;
 
 template <bool GATEUP, bool CONV>
-__global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga) {
+__global__ __launch_bounds__(TWAVES * 64, 2) void k_qgemm_tile(const GemmArgs ga, const TileGeom tg) {
   extern __shared__ __align__(16) uint8_t lds[];
   const int n_tiles = GATEUP ? (ga.n + TBN / 2 - 1) / (TBN / 2) : (ga.n + TBN - 1) / TBN;
-  const int patches_n = (n_tiles + PATCH_N - 1) / PATCH_N;
+  const int pn_log2 = tg.patch_n_log2, patch_wgs = PATCH_M << pn_log2;
+  const int patches_n = (n_tiles + (1 << pn_log2) - 1) >> pn_log2;
   const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
-  const int patch = (j / (PATCH_M * PATCH_N)) * 8 + xcd, q = j % (PATCH_M * PATCH_N);
-  const int ntile = (patch % patches_n) * PATCH_N + q / PATCH_M;
-  // which expert and which row tile of its bucket: `slot` counts row tiles over all experts
-  int slot = (patch / patches_n) * PATCH_M + q % PATCH_M, e = -1, m0 = 0;
-  for (int i = 0; i < ga.n_experts; ++i) {
-    int rows = (ga.offsets[i + 1] - ga.offsets[i]) * ga.T;
-    if (rows < ga.min_rows || rows > ga.max_rows) rows = 0;       // that bucket belongs to the streaming kernel's launch
-    const int tiles = (rows + TBM - 1) / TBM;
-    if (slot < tiles) { e = i; m0 = slot * TBM; break; }
-    slot -= tiles;
+  const int patch = (j / patch_wgs) * 8 + xcd, q = j % patch_wgs;
+  const int ntile = ((patch % patches_n) << pn_log2) + q / PATCH_M;
+  if (ntile >= n_tiles) return;               // uniform over the work-group
+  // Which expert and which row tile of its bucket: `slot` counts row tiles over all experts in the launch's
+  // order.  Lane i takes the expert at position i: one load of the offsets, a prefix sum over 16 lanes.
+  const int slot = (patch / patches_n) * PATCH_M + q % PATCH_M;
+  const int lane = threadIdx.x & 63;
+  const int mine = int((tg.order_bits >> (4 * (lane & 15))) & 15u);
+  int o0 = 0, o1 = 0;
+  if (lane < ga.n_experts) { o0 = ga.offsets[mine]; o1 = ga.offsets[mine + 1]; }
+  int rows = (o1 - o0) * ga.T;
+  if (rows < ga.min_rows || rows > ga.max_rows) rows = 0;         // that bucket belongs to the streaming kernel's launch
+  const int tiles = (rows + TBM - 1) / TBM;
+  int incl = tiles;
+#pragma unroll
+  for (int d = 1; d < MOQE_MAX_EXPERTS; d <<= 1) {
+    const int v = __shfl_up(incl, d);
+    if (lane >= d) incl += v;
   }
-  if (e < 0 || ntile >= n_tiles) return;      // uniform over the work-group
+  const unsigned long long hit = __ballot(lane < ga.n_experts && slot >= incl - tiles && slot < incl);
+  if (hit == 0ull) return;                    // uniform: a surplus work-group
+  const int src = __ffsll(hit) - 1;
+  const int e = __builtin_amdgcn_readfirstlane(__shfl(mine, src));
+  const int off_e = __builtin_amdgcn_readfirstlane(__shfl(o0, src));
+  const int M_e = __builtin_amdgcn_readfirstlane(__shfl((o1 - o0) * ga.T, src));
+  const int m0 = __builtin_amdgcn_readfirstlane(__shfl((slot - (incl - tiles)) * TBM, src));
   const ExpertDev& ex = ga.ex[e];
   switch (ex.fmt * 4 + ex.gm) {
-    case FMT_I8 * 4 + GM_PC:     tile_task<FMT_I8, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_I8A8 * 4 + GM_PC:   tile_task<FMT_I8A8, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N6 * 4 + GM_PC:     tile_task<FMT_N6, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N4 * 4 + GM_PC:     tile_task<FMT_N4, GM_PC, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N4 * 4 + GM_G128:   tile_task<FMT_N4, GM_G128, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N4 * 4 + GM_G64:    tile_task<FMT_N4, GM_G64, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N3 * 4 + GM_G128:   tile_task<FMT_N3, GM_G128, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
-    case FMT_N3 * 4 + GM_G64:    tile_task<FMT_N3, GM_G64, GATEUP, CONV>(ga, ex, e, m0, ntile, lds); break;
+    case FMT_I8 * 4 + GM_PC:     tile_task<FMT_I8, GM_PC, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
+    case FMT_I8A8 * 4 + GM_PC:   tile_task<FMT_I8A8, GM_PC, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
+    case FMT_N6 * 4 + GM_PC:     tile_task<FMT_N6, GM_PC, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
+    case FMT_N4 * 4 + GM_PC:     tile_task<FMT_N4, GM_PC, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
+    case FMT_N4 * 4 + GM_G128:   tile_task<FMT_N4, GM_G128, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
+    case FMT_N4 * 4 + GM_G64:    tile_task<FMT_N4, GM_G64, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
+    case FMT_N3 * 4 + GM_G128:   tile_task<FMT_N3, GM_G128, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
+    case FMT_N3 * 4 + GM_G64:    tile_task<FMT_N3, GM_G64, GATEUP, CONV>(ga, tg, ex, off_e, M_e, m0, ntile, lds); break;
     default: break;
+  }
+}
+
+// Relative arithmetic per tile of a format (measured on one launch per format): only the order matters.
+static int tile_cost(const ExpertDev& ex) {
+  const bool g64 = ex.gm == GM_G64, grp = ex.gm != GM_PC;
+  switch (ex.fmt) {
+    case FMT_I8A8: return 60;
+    case FMT_I8:   return 119;
+    case FMT_N6:   return 134;
+    case FMT_N4:   return g64 ? 166 : (grp ? 125 : 108);
+    default:       return g64 ? 172 : (grp ? 131 : 114);      // FMT_N3
   }
 }
 
@@ -400,19 +465,33 @@ int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
   const int M = ga.S * ga.T;
   const int row_tiles = (M + TBM - 1) / TBM + ga.n_experts;      // upper bound on sum_e ceil(M_e / TBM)
   const int n_tiles = gateup ? (ga.n + TBN / 2 - 1) / (TBN / 2) : (ga.n + TBN - 1) / TBN;
-  const long patches = long((row_tiles + PATCH_M - 1) / PATCH_M) * ((n_tiles + PATCH_N - 1) / PATCH_N);
-  const long grid = (patches + 7) / 8 * 8 * (PATCH_M * PATCH_N);
+  TileGeom tg;
+  memset(&tg, 0, sizeof(tg));
+  while ((1 << tg.patch_n_log2) < n_tiles && tg.patch_n_log2 < 3) ++tg.patch_n_log2;
+  const int pn = 1 << tg.patch_n_log2;
+  const long patches = long((row_tiles + PATCH_M - 1) / PATCH_M) * ((n_tiles + pn - 1) / pn);
+  const long grid = (patches + 7) / 8 * 8 * (PATCH_M * pn);
   if (grid > 0x7fffffffL) return set_error(MOQE_E_SHAPE, "grouped_qgemm: %d rows exceed the tile kernel's grid", M);
+  static_assert(MOQE_MAX_EXPERTS <= 16, "the order is packed in 4-bit fields");
+  int order[MOQE_MAX_EXPERTS];
+  for (int e = 0; e < ga.n_experts; ++e) order[e] = e;
+  std::stable_sort(order, order + ga.n_experts, [&](int a, int b) { return tile_cost(ga.ex[a]) > tile_cost(ga.ex[b]); });
+  for (int e = 0; e < ga.n_experts; ++e) tg.order_bits |= uint64_t(order[e]) << (4 * e);
   const bool conv = ga.conv_c > 0;
+  if (conv) {
+    // column / conv_c by multiply-high is exact while column * conv_c < 2^32; columns stay below 10 * conv_c
+    if (ga.conv_c > 16384) return set_error(MOQE_E_SHAPE, "grouped_qgemm: %d input channels exceed the convolution gather's 16384", ga.conv_c);
+    tg.conv_c_magic = uint32_t(((1ull << 32) + uint32_t(ga.conv_c) - 1) / uint32_t(ga.conv_c));
+  }
   const int ki = gateup ? 1 : (conv ? 2 : 0);
   const void* fns[3] = {reinterpret_cast<const void*>(&k_qgemm_tile<false, false>), reinterpret_cast<const void*>(&k_qgemm_tile<true, false>),
                         reinterpret_cast<const void*>(&k_qgemm_tile<false, true>)};
   int32_t rc = ensure_dynamic_lds(LDSK_TILE0 + ki, fns[ki], T_LDS_BYTES, "grouped_qgemm(tile)");
   if (rc) return rc;
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL((k_qgemm_tile<true, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
-  else if (conv) hipLaunchKernelGGL((k_qgemm_tile<false, true>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
-  else hipLaunchKernelGGL((k_qgemm_tile<false, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga);
+  if (gateup) hipLaunchKernelGGL((k_qgemm_tile<true, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga, tg);
+  else if (conv) hipLaunchKernelGGL((k_qgemm_tile<false, true>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga, tg);
+  else hipLaunchKernelGGL((k_qgemm_tile<false, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga, tg);
   return check_launch("grouped_qgemm(tile)");
 }
 

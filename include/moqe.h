@@ -315,6 +315,10 @@ int32_t moqe_cache_stats(const moqe_expert_cache* cache, uint64_t* copies, uint6
  * kernel kind k has bit (1 << k) set in mask (MOQE_PK_*; at most MOQE_PROFILE_MAX_LAUNCHES
  * launches are kept; mask 0 stops).  moqe_profile_read synchronises the recorded events of one
  * kind and returns the number of launches seen and their summed duration in milliseconds.
+ * The two GEMM kinds hand their event pair to the launch itself, so that the pair carries the
+ * kernel's own begin and end time stamps (the duration a kernel trace shows); the other kinds record
+ * one event before and one after their launches, which includes the dispatch gap between them.
+ * Do not enable profiling while a stream is being captured into a graph.
  * The record list is process-wide and unlocked: enable, run and read from one thread at a time. */
 #define MOQE_PK_ROUTE      0
 #define MOQE_PK_BUCKET     1

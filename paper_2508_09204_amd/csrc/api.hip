@@ -53,7 +53,7 @@ static uint32_t g_prof_mask = 0;
 static std::vector<ProfRec> g_prof;
 static std::vector<hipEvent_t> g_pool;     // events 2i, 2i+1 form pair i
 
-ProfileScope::ProfileScope(int kind, hipStream_t s) : slot(-1), stream(s) {
+ProfileScope::ProfileScope(int kind, hipStream_t s, bool exact_) : slot(-1), stream(s), exact(exact_), ev_begin(nullptr), ev_end(nullptr) {
   if (!((g_prof_mask >> kind) & 1u)) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   if (!((g_prof_mask >> kind) & 1u) || g_prof.size() >= MOQE_PROFILE_MAX_LAUNCHES) return;
@@ -63,15 +63,16 @@ ProfileScope::ProfileScope(int kind, hipStream_t s) : slot(-1), stream(s) {
     if (hipEventCreate(&e) != hipSuccess) return;
     g_pool.push_back(e);
   }
-  (void)hipEventRecord(g_pool[2 * pair], s);
+  ev_begin = g_pool[2 * pair];
+  ev_end = g_pool[2 * pair + 1];
+  if (!exact) (void)hipEventRecord(ev_begin, s);
   g_prof.push_back(ProfRec{int(pair), kind});
   slot = int(pair);
 }
 
 ProfileScope::~ProfileScope() {
-  if (slot < 0) return;
-  std::lock_guard<std::mutex> lk(g_prof_mu);
-  if (size_t(2 * slot + 1) < g_pool.size()) (void)hipEventRecord(g_pool[2 * slot + 1], stream);
+  if (slot < 0 || exact) return;
+  (void)hipEventRecord(ev_end, stream);
 }
 
 // ---- validation helpers --------------------------------------------------------------------

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -171,11 +172,20 @@ struct GemmArgs {
 int32_t set_error(int32_t code, const char* fmt, ...);
 bool    dry_run();
 
-// Brackets a kernel launch with HIP events when profiling is on.
+// Times kernel launches with HIP events when profiling is on.  The default scope records one event
+// before and one after whatever is launched inside it.  An `exact` scope records nothing itself: its one
+// kernel is launched through launch(), which hands the two events to the launch, so that they carry the
+// kernel's own begin and end time stamps (what a kernel trace reports) without the dispatch gap.
 struct ProfileScope {
-  ProfileScope(int kind, hipStream_t s);
+  ProfileScope(int kind, hipStream_t s, bool exact = false);
   ~ProfileScope();
-  int slot; hipStream_t stream;
+  template <typename F, typename... Args>
+  void launch(F kernel, dim3 grid, dim3 block, size_t lds_bytes, Args... args) {
+    if (slot >= 0 && exact) hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, ev_begin, ev_end, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args...);
+  }
+  int slot; hipStream_t stream; bool exact;
+  hipEvent_t ev_begin, ev_end;
 };
 
 int32_t check_launch(const char* what);

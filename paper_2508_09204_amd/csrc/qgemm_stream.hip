@@ -610,9 +610,9 @@ int32_t launch_qgemm_stream(const GemmArgs& ga, bool gateup, hipStream_t st) {
   const void* fn = gateup ? reinterpret_cast<const void*>(&k_qgemm_stream<true>) : reinterpret_cast<const void*>(&k_qgemm_stream<false>);
   rc = ensure_dynamic_lds(LDSK_STREAM0 + (gateup ? 1 : 0), fn, STREAM_LDS_BYTES, "grouped_qgemm");
   if (rc) return rc;
-  ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL(k_qgemm_stream<true>, dim3(grid), dim3(SW * 64), STREAM_LDS_BYTES, st, ga);
-  else hipLaunchKernelGGL(k_qgemm_stream<false>, dim3(grid), dim3(SW * 64), STREAM_LDS_BYTES, st, ga);
+  ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st, true);
+  if (gateup) ps.launch(k_qgemm_stream<true>, dim3(grid), dim3(SW * 64), STREAM_LDS_BYTES, ga);
+  else ps.launch(k_qgemm_stream<false>, dim3(grid), dim3(SW * 64), STREAM_LDS_BYTES, ga);
   return check_launch("grouped_qgemm");
 }
 

@@ -455,8 +455,8 @@ int32_t launch_qgemm_stream_lds(const GemmArgs& ga, bool gateup, hipStream_t st)
                                              k_qgemm_stream_lds<true, 4>};
   int32_t rc = ensure_dynamic_lds(LDSK_STREAM0 + 2 + ki, reinterpret_cast<const void*>(kernels[ki]), LDS_BYTES, "grouped_qgemm");
   if (rc) return rc;
-  ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  hipLaunchKernelGGL(kernels[ki], dim3(grid), dim3(WAVES * 64), lds_bytes, st, ga, geo);
+  ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st, true);
+  ps.launch(kernels[ki], dim3(grid), dim3(WAVES * 64), lds_bytes, ga, geo);
   return check_launch("grouped_qgemm");
 }
 

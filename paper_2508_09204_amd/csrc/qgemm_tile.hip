@@ -488,10 +488,10 @@ int32_t launch_qgemm_tile(const GemmArgs& ga, bool gateup, hipStream_t st) {
                         reinterpret_cast<const void*>(&k_qgemm_tile<false, true>)};
   int32_t rc = ensure_dynamic_lds(LDSK_TILE0 + ki, fns[ki], T_LDS_BYTES, "grouped_qgemm(tile)");
   if (rc) return rc;
-  ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st);
-  if (gateup) hipLaunchKernelGGL((k_qgemm_tile<true, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga, tg);
-  else if (conv) hipLaunchKernelGGL((k_qgemm_tile<false, true>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga, tg);
-  else hipLaunchKernelGGL((k_qgemm_tile<false, false>), dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, st, ga, tg);
+  ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st, true);
+  if (gateup) ps.launch(k_qgemm_tile<true, false>, dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, ga, tg);
+  else if (conv) ps.launch(k_qgemm_tile<false, true>, dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, ga, tg);
+  else ps.launch(k_qgemm_tile<false, false>, dim3(unsigned(grid)), dim3(TWAVES * 64), T_LDS_BYTES, ga, tg);
   return check_launch("grouped_qgemm(tile)");
 }
 

@@ -90,3 +90,42 @@ def make_targets(cfg: WorkloadConfig, n_classes: int) -> np.ndarray:
     ss = _streams(cfg)
     m = len(cfg.matrices())
     return ss[m + 3].integers(0, n_classes, size=(cfg.S, cfg.T), dtype=np.int64).astype(np.int32)
+
+
+def make_nlp_router(d: int, dm: int, n_heads: int, d_ff: int, head_hidden: int, K: int, seed: int) -> Dict[str, np.ndarray]:
+    """Random fp32 parameters of the NLP router model (projection, encoder layer, attention module, MLP head).
+    Matrices are [out, in] with N(0, 1/in) entries, biases N(0, 0.02), LayerNorm gains 1 + N(0, 0.05);
+    the rows of the last layer are zero-sum (see make_router)."""
+    ss = [np.random.default_rng(s) for s in np.random.SeedSequence(seed).spawn(32)]
+    it = iter(ss)
+
+    def mat(n, k):
+        return (next(it).standard_normal((n, k), dtype=np.float32) * np.float32(1.0 / np.sqrt(k)))
+
+    def vec(n, std=0.02, mean=0.0):
+        return (next(it).standard_normal(n, dtype=np.float32) * np.float32(std) + np.float32(mean))
+
+    p = {"w_in": mat(dm, d), "b_in": vec(dm)}
+    for tag in ("1", "2"):
+        p["wqkv" + tag] = mat(3 * dm, dm)
+        p["bqkv" + tag] = vec(3 * dm)
+        p["wo" + tag] = mat(dm, dm)
+        p["bo" + tag] = vec(dm)
+    p["w_ff1"], p["b_ff1"] = mat(d_ff, dm), vec(d_ff)
+    p["w_ff2"], p["b_ff2"] = mat(dm, d_ff), vec(dm)
+    for tag in ("1", "2", "3"):
+        p["ln%s_g" % tag] = vec(dm, 0.05, 1.0)
+        p["ln%s_b" % tag] = vec(dm)
+    p["head_w1"], p["head_b1"] = mat(head_hidden, dm), vec(head_hidden)
+    w2 = mat(K, head_hidden)
+    w2 -= w2.mean(axis=1, keepdims=True, dtype=np.float32)
+    p["head_w2"], p["head_b2"] = w2, vec(K)
+    return p
+
+
+def make_token_activations(S: int, T: int, D: int, seed: int, topic_std: float = 1.0) -> np.ndarray:
+    """bf16 token vectors [S, T, D] as uint16 bit patterns: every sequence has its own N(0, topic_std) offset
+    vector (sequences differ in content) plus N(0, 1) noise per token."""
+    a, b = [np.random.default_rng(s) for s in np.random.SeedSequence(seed).spawn(2)]
+    x = a.standard_normal((S, 1, D), dtype=np.float32) * np.float32(topic_std) + b.standard_normal((S, T, D), dtype=np.float32)
+    return f32_to_bf16_bits(x)

@@ -96,6 +96,30 @@ typedef struct moqe_router {
   int32_t d, h, n_experts;
 } moqe_router;
 
+/* The NLP router model (Section 3.2, "NLP Router Model"): a Transformer encoder makes every token vector
+ * context-aware, a dedicated self-attention module re-weights these representations, and an MLP maps the
+ * refined features to one logit per expert.  The paper fixes the order of the stages, not their sizes; here
+ *   u = x W_in^T + b_in                                         token vectors [T, d] -> width dm
+ *   v = LN1(u + MHA1(u));  w = LN2(v + W_ff2 relu(W_ff1 v + b_ff1) + b_ff2)       one post-norm encoder layer
+ *   z = LN3(w + MHA2(w))                                        the attention module
+ *   logits = head(mean over the T tokens of z)                  head: Linear(dm -> h) -> ReLU -> Linear(h -> K)
+ * MHA(u): n_heads heads of width dm / n_heads; [Q K V] = u Wqkv^T + bqkv (rows of Wqkv: queries, keys,
+ * values); head h uses columns h*dh .. (h+1)*dh; softmax(Q K^T / sqrt(dh)) V, heads concatenated, then
+ * Wo and bo.  No mask, no positional term.  LayerNorm: biased variance, eps 1e-5, gain g and offset b.
+ * All parameters device fp32, matrices row-major [out, in].  d a multiple of 64; dm and d_ff multiples of
+ * 128, dm <= 2048; dm / n_heads in {16, 32, 64, 128}; head.d == dm. */
+typedef struct moqe_nlp_router {
+  const float *w_in, *b_in;                              /* [dm, d], [dm] */
+  const float *wqkv1, *bqkv1, *wo1, *bo1;                /* [3dm, dm], [3dm], [dm, dm], [dm] */
+  const float *ln1_g, *ln1_b;                            /* [dm] */
+  const float *w_ff1, *b_ff1, *w_ff2, *b_ff2;            /* [d_ff, dm], [d_ff], [dm, d_ff], [dm] */
+  const float *ln2_g, *ln2_b;
+  const float *wqkv2, *bqkv2, *wo2, *bo2;
+  const float *ln3_g, *ln3_b;
+  moqe_router head;
+  int32_t d, dm, n_heads, d_ff;
+} moqe_nlp_router;
+
 /* One routed block.  w0/w1/w2 are host arrays of n_experts PACKED matrices.
  *   LINEAR   : y = x W0^T.                         x [S*T, d], y [S*T, n]
  *   SILU_MLP : h = bf16(silu(x Wg^T) * (x Wu^T)), y = h Wd^T with w0 = gate, w1 = up,
@@ -177,6 +201,19 @@ int32_t moqe_label_pass(const moqe_block* blk, const void* x, const int32_t* tar
  * (deterministic).  S >= 1, 1 <= K <= MOQE_MAX_EXPERTS.  One small kernel on `stream`. */
 int32_t moqe_balance_stats(const float* logits, const int32_t* counts, int32_t S, int32_t K,
                            float alpha, float* out, void* stream);
+
+/* Routing with the NLP router model (Section 3.2; the stages are listed at moqe_nlp_router).
+ *   x          : device bf16 [S, T, d], 16-byte aligned (the token vectors the router model sees)
+ *   expert_idx : device int32 [S] out (top-1, ties to the lowest index);  logits: device float [S, K] out or NULL
+ * Arithmetic: the matrix products of the token stages multiply bf16 operands (x as given; parameters and the
+ * activations between stages rounded to bf16, nearest even) on the matrix cores with fp32 accumulation;
+ * softmax, LayerNorm, residual sums, the mean over the tokens and the MLP head are fp32.  All sums run in a
+ * fixed order (deterministic).  About 16 launches on `stream`; workspace as the query says, 256-byte aligned.
+ * S == 0 is a no-op. */
+size_t moqe_route_nlp_workspace_bytes(int32_t S, int32_t T, const moqe_nlp_router* r);
+int32_t moqe_route_nlp(const void* x, int32_t S, int32_t T, const moqe_nlp_router* r,
+                       int32_t* expert_idx, float* logits,
+                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- expert weights ----------------------------------------------------------------- */
 

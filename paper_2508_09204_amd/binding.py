@@ -39,6 +39,15 @@ class _Router(C.Structure):
                 ("d", C.c_int32), ("h", C.c_int32), ("n_experts", C.c_int32)]
 
 
+_NLP_PTRS = ("w_in", "b_in", "wqkv1", "bqkv1", "wo1", "bo1", "ln1_g", "ln1_b", "w_ff1", "b_ff1", "w_ff2", "b_ff2",
+             "ln2_g", "ln2_b", "wqkv2", "bqkv2", "wo2", "bo2", "ln3_g", "ln3_b")
+
+
+class _NlpRouter(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _NLP_PTRS] + [("head", _Router), ("d", C.c_int32), ("dm", C.c_int32),
+                                                         ("n_heads", C.c_int32), ("d_ff", C.c_int32)]
+
+
 class _Block(C.Structure):
     _fields_ = [("kind", C.c_int32), ("router", _Router),
                 ("w0", C.POINTER(_QMat)), ("w1", C.POINTER(_QMat)), ("w2", C.POINTER(_QMat)),
@@ -64,6 +73,8 @@ def _load() -> C.CDLL:
         "moqe_route": (i32, [vp, i32, i32, C.POINTER(_Router), vp, vp, vp, sz, vp]),
         "moqe_bucket": (i32, [vp, i32, i32, vp, vp, vp, vp, vp]),
         "moqe_balance_stats": (i32, [vp, vp, i32, i32, C.c_float, vp, vp]),
+        "moqe_route_nlp_workspace_bytes": (sz, [i32, i32, C.POINTER(_NlpRouter)]),
+        "moqe_route_nlp": (i32, [vp, i32, i32, C.POINTER(_NlpRouter), vp, vp, vp, sz, vp]),
         "moqe_route_ragged_workspace_bytes": (sz, [i32, C.POINTER(_Router)]),
         "moqe_route_ragged": (i32, [vp, vp, i32, C.POINTER(_Router), vp, vp, vp, sz, vp]),
         "moqe_expand_rows": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
@@ -100,7 +111,7 @@ INPUT_IN_BUCKET_ORDER = 2
 OUTPUT_BF16 = 4
 
 EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
-            "moqe_route", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",
+            "moqe_route", "moqe_route_nlp_workspace_bytes", "moqe_route_nlp", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",
             "moqe_expand_rows", "moqe_workspace_bytes_ragged", "moqe_forward_ragged", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
             "moqe_workspace_bytes", "moqe_forward", "moqe_forward_static", "moqe_label_pass_workspace_bytes", "moqe_label_pass", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
@@ -159,6 +170,25 @@ class Router:
 
     def c(self) -> _Router:
         return _Router(_ptr(self.w1), _ptr(self.b1), _ptr(self.w2), _ptr(self.b2), self.d, self.h, self.n_experts)
+
+
+@dataclass
+class NlpRouter:
+    """The NLP router model: `params` maps the names of moqe_nlp_router's pointers to fp32 device tensors."""
+    params: dict
+    head: Router
+    d: int
+    dm: int
+    n_heads: int
+    d_ff: int
+
+    def c(self) -> _NlpRouter:
+        r = _NlpRouter()
+        for n in _NLP_PTRS:
+            setattr(r, n, _ptr(self.params[n]))
+        r.head = self.head.c()
+        r.d, r.dm, r.n_heads, r.d_ff = self.d, self.dm, self.n_heads, self.d_ff
+        return r
 
 
 @dataclass
@@ -232,6 +262,20 @@ def moqe_route(x: torch.Tensor, S: int, T: int, router: Router, expert_idx: torc
 def moqe_bucket(expert_idx: torch.Tensor, S: int, K: int, counts: Optional[torch.Tensor], offsets: torch.Tensor,
                 perm: Optional[torch.Tensor], inv_perm: Optional[torch.Tensor]) -> None:
     _check(lib.moqe_bucket(_ptr(expert_idx), S, K, _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _stream()))
+
+
+def moqe_route_nlp_workspace_bytes(S: int, T: int, r: NlpRouter) -> int:
+    rc = r.c()
+    return lib.moqe_route_nlp_workspace_bytes(S, T, C.byref(rc))
+
+
+def moqe_route_nlp(x: torch.Tensor, S: int, T: int, r: NlpRouter, expert_idx: torch.Tensor,
+                   logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    rc = r.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_route_nlp_workspace_bytes(S, T, C.byref(rc)), x.device)
+    _check(lib.moqe_route_nlp(_ptr(x), S, T, C.byref(rc), _ptr(expert_idx), _ptr(logits), _ptr(workspace),
+                              workspace.numel(), _stream()))
 
 
 def moqe_balance_stats(logits: torch.Tensor, counts: torch.Tensor, S: int, K: int, alpha: float,

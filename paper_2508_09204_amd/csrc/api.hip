@@ -255,6 +255,30 @@ int32_t moqe_bucket(const int32_t* expert_idx, int32_t S, int32_t K, int32_t* co
   return launch_bucket(expert_idx, S, K, counts, offsets, perm, inv_perm, static_cast<hipStream_t>(stream));
 }
 
+size_t moqe_route_nlp_workspace_bytes(int32_t S, int32_t T, const moqe_nlp_router* r) {
+  if (S < 0 || T <= 0 || (long long)S * T > 0x7fffffffLL) return 0;
+  if (check_nlp_router(r, "moqe_route_nlp_workspace_bytes") || check_router(&r->head, "moqe_route_nlp_workspace_bytes")) return 0;
+  return route_nlp_ws_bytes(S, T, *r);
+}
+
+int32_t moqe_route_nlp(const void* x, int32_t S, int32_t T, const moqe_nlp_router* r, int32_t* expert_idx, float* logits,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t rc = check_nlp_router(r, "moqe_route_nlp");
+  if (rc) return rc;
+  rc = check_router(&r->head, "moqe_route_nlp");
+  if (rc) return rc;
+  if (S < 0 || T <= 0 || (long long)S * T > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_route_nlp: S=%d T=%d", S, T);
+  if (S == 0) return MOQE_OK;
+  if (!x || !expert_idx) return set_error(MOQE_E_NULL, "moqe_route_nlp: x or expert_idx is NULL");
+  if (!aligned(x, 16)) return set_error(MOQE_E_SHAPE, "moqe_route_nlp: x must be 16-byte aligned");
+  if (S > 65535) return set_error(MOQE_E_SHAPE, "moqe_route_nlp: at most 65535 samples per call");
+  const size_t need = route_nlp_ws_bytes(S, T, *r);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < need)
+    return set_error(MOQE_E_WORKSPACE, "moqe_route_nlp: workspace needs %zu bytes, 256-byte aligned", need);
+  if (dry_run()) return MOQE_OK;
+  return launch_route_nlp(x, S, T, *r, expert_idx, logits, workspace, static_cast<hipStream_t>(stream));
+}
+
 size_t moqe_route_ragged_workspace_bytes(int32_t S, const moqe_router* r) {
   if (!r || S < 0 || r->d <= 0) return 0;
   return route_ws_bytes(S, 2, *r);

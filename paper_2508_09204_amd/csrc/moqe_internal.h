@@ -193,12 +193,16 @@ int32_t check_launch(const char* what);
 // Kernels that need more than 64 KiB of dynamic LDS must ask for it once per kernel: `slot` is a
 // process-wide id of the kernel (LdsKernel); the request is made by the first caller only, under a
 // lock, and every caller gets its outcome.
-enum LdsKernel : int { LDSK_STREAM0 = 0, LDSK_TILE0 = 8, LDSK_ROUTER_TAIL = 12, LDSK_COUNT = 16 };
+enum LdsKernel : int { LDSK_STREAM0 = 0, LDSK_TILE0 = 8, LDSK_ROUTER_TAIL = 12, LDSK_NLP_LIN = 13, LDSK_COUNT = 16 };
 int32_t ensure_dynamic_lds(int slot, const void* kernel, int bytes, const char* what);
 
 int32_t launch_route(const void* x, int S, int T, const moqe_router& r, int32_t* idx, float* logits,
                      void* ws, hipStream_t st);
 size_t  route_ws_bytes(int S, int T, const moqe_router& r);
+int32_t launch_route_features(const float* feat, int S, const moqe_router& r, int32_t* idx, float* logits, void* ws, hipStream_t st);
+int32_t check_nlp_router(const moqe_nlp_router* r, const char* who);
+size_t  route_nlp_ws_bytes(int S, int T, const moqe_nlp_router& r);
+int32_t launch_route_nlp(const void* x, int S, int T, const moqe_nlp_router& r, int32_t* idx, float* logits, void* ws, hipStream_t st);
 int32_t launch_route_ragged(const void* x, const int32_t* cu_rows, int S, const moqe_router& r, int32_t* idx, float* logits,
                             void* ws, hipStream_t st);
 int32_t launch_expand_rows(const int32_t* cu_rows, const int32_t* offsets, const int32_t* perm, int S, int K,

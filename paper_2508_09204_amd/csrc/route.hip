@@ -403,6 +403,24 @@ int32_t launch_route(const void* x, int S, int T, const moqe_router& r, int32_t*
   return check_launch("route");
 }
 
+// The router's MLP on feature vectors that are already there (feat: fp32 [S, r.d]); workspace route_ws_bytes(S, 1, r).
+int32_t launch_route_features(const float* feat, int S, const moqe_router& r, int32_t* idx, float* logits, void* ws, hipStream_t st) {
+  RouteFeat rf{feat, 0, 0, r.d};
+  if (r.h > 0) {
+    int C, CT;
+    pool_shape(1, r.d, &C, &CT);
+    float* hidden = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + align256(size_t(S) * C * r.d * 4) + align256(size_t(S) * r.d * 4));
+    const int KS = hidden_slices(r.d);
+    ProfileScope ps(MOQE_PK_ROUTE, st);
+    hipLaunchKernelGGL(k_router_hidden<false>, dim3((r.h + 15) / 16, (S + 15) / 16, KS), dim3(256), 0, st,
+                       static_cast<const void*>(feat), r.w1, hidden, S, r.d, r.h);
+    rf = RouteFeat{hidden, KS, size_t(S) * r.h, r.h};
+  }
+  ProfileScope ps(MOQE_PK_ROUTE, st);
+  launch_logits_argmax(rf.feat, rf.nslices, rf.stride, r, S, rf.Dk, idx, logits, st);
+  return check_launch("route");
+}
+
 // Samples of different lengths (cu_rows: device int32 [S + 1], first row of every sample): the
 // workspace is that of route_ws_bytes(S, 2, r).
 int32_t launch_route_ragged(const void* x, const int32_t* cu_rows, int S, const moqe_router& r, int32_t* idx, float* logits,

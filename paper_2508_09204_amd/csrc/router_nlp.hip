@@ -1,0 +1,448 @@
+// The NLP router model (MoQE Section 3.2): token vectors -> projection -> one post-norm Transformer encoder
+// layer -> a second self-attention module (residual, LayerNorm) -> mean over the tokens -> MLP head -> top-1.
+// The paper fixes the order of the stages, not their sizes; widths come with the parameter struct.
+//
+// Kernels of this file:
+//   k_to_bf16      fp32 parameters -> bf16 copies (one launch for all matrices)
+//   k_lin          C = A W^T + bias [+ residual] [ReLU] on the bf16 matrix cores, fp32 accumulation; A and W
+//                  are bf16, C is written as fp32 and/or bf16
+//   k_attention    softmax(Q K^T / sqrt(dh)) V per (sample, head) in fp32 on the fp32 matrix cores, one wave per
+//                  16 queries, keys streamed in tiles of 16 with a running maximum and sum (no LDS, no barrier)
+//   k_layer_norm   per row, fp32, biased variance; writes fp32 and/or bf16
+//   k_pool_f32     mean over a sample's tokens, added in token order
+// The MLP head on the pooled vector is the small router of route.hip.
+#include "qgemm_device.h"
+
+#include <cstring>
+
+namespace moqe {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+static __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {   // round to nearest even, a in the low half
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// ---- parameters to bf16 ---------------------------------------------------------------------------------
+constexpr int CVT_MAX_SEG = 8;
+struct CvtSegs {
+  const float* src[CVT_MAX_SEG];
+  uint16_t* dst[CVT_MAX_SEG];
+  long long first[CVT_MAX_SEG + 1];      // first[i] = index (in units of 4 elements) where segment i starts
+  int n;
+};
+
+__global__ __launch_bounds__(256) void k_to_bf16(const CvtSegs sg) {
+  const long long total = sg.first[sg.n];
+  for (long long i = blockIdx.x * 256ll + threadIdx.x; i < total; i += gridDim.x * 256ll) {
+    int s = 0;
+#pragma unroll
+    for (int j = 1; j < CVT_MAX_SEG; ++j) s += (j < sg.n && i >= sg.first[j]) ? 1 : 0;
+    const long long e = (i - sg.first[s]) * 4;
+    const float4 v = *reinterpret_cast<const float4*>(sg.src[s] + e);
+    uint2 o;
+    o.x = pack_bf16x2(v.x, v.y);
+    o.y = pack_bf16x2(v.z, v.w);
+    *reinterpret_cast<uint2*>(sg.dst[s] + e) = o;
+  }
+}
+
+// ---- C = A W^T ---------------------------------------------------------------------------------------------
+// Work-group tile 128 rows x 128 columns, k-tiles of 64; 4 waves as 2 x 2, a wave owns 64 x 64 (4 x 4
+// matrix-core blocks).  Both operand tiles go through LDS (rows of 128 bytes, 16-byte units XOR-swizzled by
+// the row so that operand reads are conflict free), double-buffered, one barrier per k-tile.
+constexpr int LBM = 128, LBN = 128, LBK = 64;
+constexpr int L_TILE_BYTES = LBM * LBK * 2;                  // one operand tile
+constexpr int L_LDS_BYTES = 4 * L_TILE_BYTES;               // A and W, two buffers each
+
+struct LinArgs {
+  const uint16_t* a;      // bf16 [M, k]
+  const uint16_t* w;      // bf16 [n, k]
+  const float* bias;      // [n] or NULL
+  const float* residual;  // fp32 [M, n] or NULL, added after the bias
+  float* c32;             // fp32 [M, n] or NULL
+  uint16_t* c16;          // bf16 [M, n] or NULL
+  int M, n, k;
+  int relu;
+};
+
+__global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
+  extern __shared__ __align__(16) uint8_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lq = lane >> 4;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * LBM, n0 = blockIdx.x * LBN;
+  const int KT = la.k / LBK;
+  // staging: a tile is 128 rows x 8 units of 16 bytes = 1024 units, 4 per thread per operand
+  const int s_unit = tid & 7, s_row0 = tid >> 3;             // rows s_row0 + 32 i
+  const uint16_t* a_src[4];
+  const uint16_t* w_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = s_row0 + 32 * i;
+    a_src[i] = la.a + size_t(min(m0 + row, la.M - 1)) * la.k + s_unit * 8;    // rows past the end repeat the last row
+    w_src[i] = la.w + size_t(n0 + row) * la.k + s_unit * 8;                    // n is a multiple of the tile
+  }
+  u32x4 a_reg[4], w_reg[4];
+  auto fetch = [&](int kt) {
+    const int ko = min(kt, KT - 1) * LBK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a_reg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + ko);
+      w_reg[i] = *reinterpret_cast<const u32x4*>(w_src[i] + ko);
+    }
+  };
+  auto store = [&](int buf) {
+    uint8_t* ab = lds + buf * 2 * L_TILE_BYTES;
+    uint8_t* wb = ab + L_TILE_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = s_row0 + 32 * i;
+      const int off = row * 128 + ((s_unit ^ (row & 7)) * 16);
+      *reinterpret_cast<u32x4*>(ab + off) = a_reg[i];
+      *reinterpret_cast<u32x4*>(wb + off) = w_reg[i];
+    }
+  };
+  f32x4 acc[4][4];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  fetch(0);
+  store(0);
+  fetch(1);
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    const uint8_t* ab = lds + buf * 2 * L_TILE_BYTES + (wm * 64 + lr) * 128;
+    const uint8_t* wb = lds + buf * 2 * L_TILE_BYTES + L_TILE_BYTES + (wn * 64 + lr) * 128;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int uo = ((j * 4 + lq) ^ (lr & 7)) * 16;        // rows lr + 16 b share lr & 7
+      u32x4 af[4];
+      bf16x8 wf[4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        af[b] = *reinterpret_cast<const u32x4*>(ab + b * 16 * 128 + uo);
+        wf[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(wb + b * 16 * 128 + uo));
+      }
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = mfma_bf16(af[mb], wf[nb], acc[mb][nb]);
+    }
+    store(buf ^ 1);            // k-tile kt + 1; that buffer was last read in iteration kt - 1
+    fetch(kt + 2);
+    __syncthreads();
+  }
+  // ---- epilogue: lane holds column n0 + wn*64 + nb*16 + lr, rows m0 + wm*64 + mb*16 + 4 lq + r
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb) {
+    const int col = n0 + wn * 64 + nb * 16 + lr;
+    const float bv = la.bias ? la.bias[col] : 0.f;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = m0 + wm * 64 + mb * 16 + 4 * lq + r;
+        if (row < la.M) {
+          const size_t o = size_t(row) * la.n + col;
+          float v = acc[mb][nb][r] + bv;
+          if (la.residual) v += la.residual[o];
+          if (la.relu) v = fmaxf(v, 0.f);
+          if (la.c32) la.c32[o] = v;
+          if (la.c16) la.c16[o] = float_to_bf16_rne(v);
+        }
+      }
+  }
+}
+
+// ---- attention -----------------------------------------------------------------------------------------------
+// qkv: fp32 [S*T, 3*dm] (queries, keys, values); out: bf16 [S*T, dm].  One wave = 16 queries of one head.
+// Scores of a 16-key tile are computed TRANSPOSED (keys x queries), so that a lane's four accumulator values are
+// four keys of ITS query (lane % 16): the softmax of a query then needs its own lane's values and those of the three
+// lanes 16, 32, 48 further on, and the probabilities already sit where the second product wants them.
+// The sum over the head's dimensions and the sum over a tile's keys are order-free, which lets lane group q
+// (= lane / 16) take the contiguous quarter q of a row (dimensions) and the keys 4q .. 4q+3 of a tile.
+template <int DH>
+__global__ __launch_bounds__(256) void k_attention(const float* __restrict__ qkv, uint16_t* __restrict__ out, int S, int T, int dm,
+                                                    float scale) {
+  constexpr int QS = DH / 4;            // dimensions per lane group = matrix-core steps of the first product
+  constexpr int CB = DH / 16;           // 16-column blocks of the output
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lr = lane & 15, lq = lane >> 4;
+  const int q0 = (blockIdx.x * 4 + wave) * 16;
+  const int head = blockIdx.y, s = blockIdx.z;
+  if (q0 >= T) return;                                      // uniform over the wave; the kernel has no barrier
+  const size_t ld = size_t(3) * dm;
+  const float* base = qkv + size_t(s) * T * ld + head * DH;
+  // queries: lane (lr, lq) holds Q[q0 + lr][lq*QS .. +QS)
+  float qf[QS];
+  {
+    const float* qp = base + size_t(min(q0 + lr, T - 1)) * ld + lq * QS;
+#pragma unroll
+    for (int i = 0; i < QS; i += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(qp + i);
+      qf[i] = v.x * scale; qf[i + 1] = v.y * scale; qf[i + 2] = v.z * scale; qf[i + 3] = v.w * scale;
+    }
+  }
+  f32x4 o[CB];
+#pragma unroll
+  for (int cb = 0; cb < CB; ++cb) o[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+  for (int k0 = 0; k0 < T; k0 += 16) {
+    // ---- scores^T[key][query] for keys k0 .. k0+15
+    f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+    {
+      const float* kp = base + dm + size_t(min(k0 + lr, T - 1)) * ld + lq * QS;
+      float kf[QS];
+#pragma unroll
+      for (int i = 0; i < QS; i += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(kp + i);
+        kf[i] = v.x; kf[i + 1] = v.y; kf[i + 2] = v.z; kf[i + 3] = v.w;
+      }
+#pragma unroll
+      for (int i = 0; i < QS; ++i) sc = __builtin_amdgcn_mfma_f32_16x16x4f32(kf[i], qf[i], sc, 0, 0, 0);
+    }
+    // lane (lr, lq) now holds the scores of query q0 + lr against keys k0 + 4 lq + r
+    float p[4];
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const bool live = k0 + 4 * lq + r < T;
+      p[r] = live ? sc[r] : -INFINITY;
+      tmax = fmaxf(tmax, p[r]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float m_new = fmaxf(m_run, tmax);                 // finite: key k0 itself is live
+    const float alpha = __expf(m_run - m_new);              // exp(-inf) = 0 on the first tile
+    float tsum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      p[r] = __expf(p[r] - m_new);
+      tsum += p[r];
+    }
+    tsum += __shfl_xor(tsum, 16);
+    tsum += __shfl_xor(tsum, 32);
+    l_run = l_run * alpha + tsum;
+    m_run = m_new;
+    // ---- out^T[c][query] += V^T P^T: step r multiplies the keys k0 + 4 kk + r (kk = lane group) of the tile
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o[cb][r] *= alpha;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float* vp = base + 2 * dm + size_t(min(k0 + 4 * lq + r, T - 1)) * ld + lr;   // dead keys have p = 0
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) o[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(vp[cb * 16], p[r], o[cb], 0, 0, 0);
+    }
+  }
+  // lane (lr, lq) holds out[q0 + lr][16 cb + 4 lq + r]
+  if (q0 + lr < T) {
+    const float inv = 1.f / l_run;
+    uint16_t* op = out + (size_t(s) * T + q0 + lr) * dm + head * DH + 4 * lq;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      uint2 v;
+      v.x = pack_bf16x2(o[cb][0] * inv, o[cb][1] * inv);
+      v.y = pack_bf16x2(o[cb][2] * inv, o[cb][3] * inv);
+      *reinterpret_cast<uint2*>(op + cb * 16) = v;
+    }
+  }
+}
+
+// ---- LayerNorm -----------------------------------------------------------------------------------------------
+static __device__ __forceinline__ float wave_sum_f(float v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  return v;
+}
+
+constexpr int LN_MAX_PER_LANE = 32;      // rows of up to 2048 elements
+__global__ __launch_bounds__(256) void k_layer_norm(const float* __restrict__ x, const float* __restrict__ g, const float* __restrict__ b,
+                                                     int M, int n, float* __restrict__ y32, uint16_t* __restrict__ y16) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= M) return;
+  const float* xr = x + size_t(row) * n;
+  float v[LN_MAX_PER_LANE];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAX_PER_LANE; ++i) {
+    const int c = lane + 64 * i;
+    v[i] = c < n ? xr[c] : 0.f;
+    sum += v[i];
+  }
+  const float mu = wave_sum_f(sum) / float(n);
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAX_PER_LANE; ++i) {
+    const int c = lane + 64 * i;
+    const float d = c < n ? v[i] - mu : 0.f;
+    sq += d * d;
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum_f(sq) / float(n) + 1e-5f);
+#pragma unroll
+  for (int i = 0; i < LN_MAX_PER_LANE; ++i) {
+    const int c = lane + 64 * i;
+    if (c < n) {
+      const float r = (v[i] - mu) * rstd * g[c] + b[c];
+      if (y32) y32[size_t(row) * n + c] = r;
+      if (y16) y16[size_t(row) * n + c] = float_to_bf16_rne(r);
+    }
+  }
+}
+
+// pooled[s][c] = (sum over t in order of z[s][t][c]) / T
+__global__ __launch_bounds__(256) void k_pool_f32(const float* __restrict__ z, float* __restrict__ pooled, int S, int T, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= S * n) return;
+  const int s = i / n, c = i - s * n;
+  const float* p = z + size_t(s) * T * n + c;
+  float acc = 0.f;
+  for (int t = 0; t < T; ++t) acc += p[size_t(t) * n];
+  pooled[i] = __fdiv_rn(acc, float(T));
+}
+
+// ---- host side -------------------------------------------------------------------------------------------------
+namespace {
+struct NlpLayout {
+  size_t w_in, wqkv1, wo1, wff1, wff2, wqkv2, wo2;          // bf16 parameter copies
+  size_t t32a, t32b, t32c, t16a, t16b, qkv, hid, pooled, head, total;
+};
+
+NlpLayout nlp_layout(int S, int T, const moqe_nlp_router& r) {
+  NlpLayout L;
+  const size_t M = size_t(S) * T, dm = r.dm;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { const size_t at = o; o += align256(bytes); return at; };
+  L.w_in = take(dm * r.d * 2);
+  L.wqkv1 = take(3 * dm * dm * 2);
+  L.wo1 = take(dm * dm * 2);
+  L.wff1 = take(size_t(r.d_ff) * dm * 2);
+  L.wff2 = take(size_t(r.d_ff) * dm * 2);
+  L.wqkv2 = take(3 * dm * dm * 2);
+  L.wo2 = take(dm * dm * 2);
+  L.t32a = take(M * dm * 4);
+  L.t32b = take(M * dm * 4);
+  L.t32c = take(M * dm * 4);
+  L.t16a = take(M * dm * 2);
+  L.t16b = take(M * dm * 2);
+  L.qkv = take(M * 3 * dm * 4);
+  L.hid = take(M * size_t(r.d_ff) * 2);
+  L.pooled = take(size_t(S) * dm * 4);
+  L.head = take(route_ws_bytes(S, 1, r.head));
+  L.total = o;
+  return L;
+}
+
+int32_t lin(const uint16_t* a, const uint16_t* w, const float* bias, const float* residual, float* c32, uint16_t* c16, int M, int n,
+            int k, bool relu, hipStream_t st) {
+  LinArgs la{a, w, bias, residual, c32, c16, M, n, k, relu ? 1 : 0};
+  ProfileScope ps(MOQE_PK_ROUTE, st);
+  hipLaunchKernelGGL(k_lin, dim3(n / LBN, (M + LBM - 1) / LBM), dim3(256), L_LDS_BYTES, st, la);
+  return check_launch("route_nlp(linear)");
+}
+
+int32_t attention(const float* qkv, uint16_t* out, int S, int T, int dm, int heads, hipStream_t st) {
+  const int dh = dm / heads;
+  const float scale = 1.0f / sqrtf(float(dh));
+  const dim3 grid((T + 63) / 64, heads, S);
+  ProfileScope ps(MOQE_PK_ROUTE, st);
+  switch (dh) {
+    case 16:  hipLaunchKernelGGL(k_attention<16>, grid, dim3(256), 0, st, qkv, out, S, T, dm, scale); break;
+    case 32:  hipLaunchKernelGGL(k_attention<32>, grid, dim3(256), 0, st, qkv, out, S, T, dm, scale); break;
+    case 64:  hipLaunchKernelGGL(k_attention<64>, grid, dim3(256), 0, st, qkv, out, S, T, dm, scale); break;
+    default:  hipLaunchKernelGGL(k_attention<128>, grid, dim3(256), 0, st, qkv, out, S, T, dm, scale); break;
+  }
+  return check_launch("route_nlp(attention)");
+}
+
+int32_t layer_norm(const float* x, const float* g, const float* b, int M, int n, float* y32, uint16_t* y16, hipStream_t st) {
+  ProfileScope ps(MOQE_PK_ROUTE, st);
+  hipLaunchKernelGGL(k_layer_norm, dim3((M + 3) / 4), dim3(256), 0, st, x, g, b, M, n, y32, y16);
+  return check_launch("route_nlp(layer norm)");
+}
+}  // namespace
+
+int32_t check_nlp_router(const moqe_nlp_router* r, const char* who) {
+  if (!r) return set_error(MOQE_E_NULL, "%s: router is NULL", who);
+  const void* need[] = {r->w_in, r->b_in, r->wqkv1, r->bqkv1, r->wo1, r->bo1, r->ln1_g, r->ln1_b, r->w_ff1, r->b_ff1, r->w_ff2,
+                        r->b_ff2, r->ln2_g, r->ln2_b, r->wqkv2, r->bqkv2, r->wo2, r->bo2, r->ln3_g, r->ln3_b};
+  for (const void* p : need)
+    if (!p) return set_error(MOQE_E_NULL, "%s: a parameter pointer is NULL", who);
+  const void* mats[] = {r->w_in, r->wqkv1, r->wo1, r->w_ff1, r->w_ff2, r->wqkv2, r->wo2};
+  for (const void* p : mats)
+    if (reinterpret_cast<uintptr_t>(p) % 16) return set_error(MOQE_E_SHAPE, "%s: parameter matrices must be 16-byte aligned", who);
+  if (r->d <= 0 || r->d % 64 || r->dm <= 0 || r->dm % 128 || r->dm > 64 * LN_MAX_PER_LANE || r->d_ff <= 0 || r->d_ff % 128)
+    return set_error(MOQE_E_SHAPE, "%s: d=%d must be a multiple of 64, dm=%d and d_ff=%d multiples of 128, dm <= %d", who, r->d,
+                     r->dm, r->d_ff, 64 * LN_MAX_PER_LANE);
+  if (r->n_heads <= 0 || r->dm % r->n_heads) return set_error(MOQE_E_SHAPE, "%s: %d heads do not divide dm=%d", who, r->n_heads, r->dm);
+  const int dh = r->dm / r->n_heads;
+  if (dh != 16 && dh != 32 && dh != 64 && dh != 128)
+    return set_error(MOQE_E_SHAPE, "%s: head width %d must be 16, 32, 64 or 128", who, dh);
+  if (r->head.d != r->dm) return set_error(MOQE_E_SHAPE, "%s: the MLP head takes %d features, dm is %d", who, r->head.d, r->dm);
+  return MOQE_OK;
+}
+
+size_t route_nlp_ws_bytes(int S, int T, const moqe_nlp_router& r) { return nlp_layout(S, T, r).total; }
+
+int32_t launch_route_nlp(const void* x, int S, int T, const moqe_nlp_router& r, int32_t* idx, float* logits, void* ws, hipStream_t st) {
+  const NlpLayout L = nlp_layout(S, T, r);
+  uint8_t* p = static_cast<uint8_t*>(ws);
+  auto b16 = [&](size_t off) { return reinterpret_cast<uint16_t*>(p + off); };
+  auto f32 = [&](size_t off) { return reinterpret_cast<float*>(p + off); };
+  const int M = S * T, dm = r.dm, dff = r.d_ff;
+  int32_t rc;
+  {
+    CvtSegs sg;
+    memset(&sg, 0, sizeof(sg));
+    const float* src[7] = {r.w_in, r.wqkv1, r.wo1, r.w_ff1, r.w_ff2, r.wqkv2, r.wo2};
+    const size_t dst[7] = {L.w_in, L.wqkv1, L.wo1, L.wff1, L.wff2, L.wqkv2, L.wo2};
+    const long long cnt[7] = {(long long)dm * r.d, 3ll * dm * dm, (long long)dm * dm, (long long)dff * dm, (long long)dff * dm,
+                              3ll * dm * dm, (long long)dm * dm};
+    sg.n = 7;
+    for (int i = 0; i < 7; ++i) {
+      sg.src[i] = src[i];
+      sg.dst[i] = b16(dst[i]);
+      sg.first[i + 1] = sg.first[i] + cnt[i] / 4;          // every count is a multiple of 64
+    }
+    ProfileScope ps(MOQE_PK_ROUTE, st);
+    const long long blocks = (sg.first[7] + 255) / 256;
+    hipLaunchKernelGGL(k_to_bf16, dim3(unsigned(blocks < 2048 ? blocks : 2048)), dim3(256), 0, st, sg);
+    rc = check_launch("route_nlp(parameters)");
+    if (rc) return rc;
+  }
+  rc = ensure_dynamic_lds(LDSK_NLP_LIN, reinterpret_cast<const void*>(&k_lin), L_LDS_BYTES, "route_nlp");
+  if (rc) return rc;
+  const uint16_t* xb = static_cast<const uint16_t*>(x);
+  // u = x W_in^T + b_in                                             u: t32a / t16a
+  if ((rc = lin(xb, b16(L.w_in), r.b_in, nullptr, f32(L.t32a), b16(L.t16a), M, dm, r.d, false, st))) return rc;
+  // encoder layer: v = LN1(u + attention(u))                         v: t32c / t16a
+  if ((rc = lin(b16(L.t16a), b16(L.wqkv1), r.bqkv1, nullptr, f32(L.qkv), nullptr, M, 3 * dm, dm, false, st))) return rc;
+  if ((rc = attention(f32(L.qkv), b16(L.t16b), S, T, dm, r.n_heads, st))) return rc;
+  if ((rc = lin(b16(L.t16b), b16(L.wo1), r.bo1, f32(L.t32a), f32(L.t32b), nullptr, M, dm, dm, false, st))) return rc;
+  if ((rc = layer_norm(f32(L.t32b), r.ln1_g, r.ln1_b, M, dm, f32(L.t32c), b16(L.t16a), st))) return rc;
+  //                w = LN2(v + W2 relu(W1 v + b1) + b2)              w: t32a / t16a
+  if ((rc = lin(b16(L.t16a), b16(L.wff1), r.b_ff1, nullptr, nullptr, b16(L.hid), M, dff, dm, true, st))) return rc;
+  if ((rc = lin(b16(L.hid), b16(L.wff2), r.b_ff2, f32(L.t32c), f32(L.t32b), nullptr, M, dm, dff, false, st))) return rc;
+  if ((rc = layer_norm(f32(L.t32b), r.ln2_g, r.ln2_b, M, dm, f32(L.t32a), b16(L.t16a), st))) return rc;
+  // attention module: z = LN3(w + attention2(w))                     z: t32c
+  if ((rc = lin(b16(L.t16a), b16(L.wqkv2), r.bqkv2, nullptr, f32(L.qkv), nullptr, M, 3 * dm, dm, false, st))) return rc;
+  if ((rc = attention(f32(L.qkv), b16(L.t16b), S, T, dm, r.n_heads, st))) return rc;
+  if ((rc = lin(b16(L.t16b), b16(L.wo2), r.bo2, f32(L.t32a), f32(L.t32b), nullptr, M, dm, dm, false, st))) return rc;
+  if ((rc = layer_norm(f32(L.t32b), r.ln3_g, r.ln3_b, M, dm, f32(L.t32c), nullptr, st))) return rc;
+  {
+    ProfileScope ps(MOQE_PK_ROUTE, st);
+    hipLaunchKernelGGL(k_pool_f32, dim3((S * dm + 255) / 256), dim3(256), 0, st, f32(L.t32c), f32(L.pooled), S, T, dm);
+    if ((rc = check_launch("route_nlp(pool)"))) return rc;
+  }
+  return launch_route_features(f32(L.pooled), S, r.head, idx, logits, p + L.head, st);
+}
+
+}  // namespace moqe

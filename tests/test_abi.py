@@ -173,6 +173,25 @@ def test_route_and_forward_argument_errors(mq):
     assert lib.moqe_workspace_bytes(C.byref(blk), 4096, 8) > (16 << 20)
     assert lib.moqe_forward_static(C.byref(blk), FAKE, 4096, 8, FAKE, None, None) == -4
     assert b"built-in" in lib.moqe_last_error_string()
+    # the NLP router model: shape rules of the struct, workspace, NULL parameters
+    head = mq._Router(FAKE, None, FAKE, None, 384, 384, 4)
+    nr = mq._NlpRouter()
+    for n in mq._NLP_PTRS:
+        setattr(nr, n, FAKE)
+    nr.head, nr.d, nr.dm, nr.n_heads, nr.d_ff = head, 4096, 384, 6, 1536
+    wn = lib.moqe_route_nlp_workspace_bytes(4, 33, C.byref(nr))
+    assert wn > 2 * (384 * 4096 + 8 * 384 * 384 + 2 * 1536 * 384)          # at least the bf16 parameter copies
+    assert lib.moqe_route_nlp(FAKE, 4, 33, C.byref(nr), FAKE, None, FAKE, wn, None) == 0
+    assert lib.moqe_route_nlp(FAKE, 0, 33, C.byref(nr), None, None, None, 0, None) == 0
+    assert lib.moqe_route_nlp(FAKE, 4, 33, C.byref(nr), FAKE, None, FAKE, wn - 256, None) == -4
+    assert lib.moqe_route_nlp(FAKE, 4, 33, C.byref(nr), None, None, FAKE, wn, None) == -1
+    nr.n_heads = 5
+    assert lib.moqe_route_nlp(FAKE, 4, 33, C.byref(nr), FAKE, None, FAKE, wn, None) == -2     # heads do not divide dm
+    nr.n_heads, nr.dm = 6, 200
+    assert lib.moqe_route_nlp(FAKE, 4, 33, C.byref(nr), FAKE, None, FAKE, wn, None) == -2     # dm not a multiple of 128
+    nr.dm, nr.wo2 = 384, None
+    assert lib.moqe_route_nlp(FAKE, 4, 33, C.byref(nr), FAKE, None, FAKE, wn, None) == -1
+    assert lib.moqe_route_nlp_workspace_bytes(4, 33, C.byref(nr)) == 0
     # the label pass: all K experts on every sample, so K times the rows of a routed forward
     lneed = lib.moqe_label_pass_workspace_bytes(C.byref(blk), 4, 3)
     assert lneed >= 2 * 4 * 3 * (256 * 4 + 512 * 2)

@@ -148,6 +148,37 @@ def rocprof_kernel_us(workload):
     return t["kernel_us"]
 
 
+# The paper's NLP router model at a size that matches its stated 16.7 MB of fp32 parameters for d = 4096:
+# width 384, 6 heads, feed-forward 1536, MLP head 384 -> 384 -> K (4.08 M parameters).
+NLP_ROUTER = {"dm": 384, "n_heads": 6, "d_ff": 1536, "head_hidden": 384}
+
+
+def measure_router_nlp(cfg, x, calls=10):
+    """Time of one moqe_route_nlp call on the workload's token vectors (random parameters), not part of the step."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_2508_09204_amd import binding as mq
+    dev = x.device
+    g = NLP_ROUTER
+    p = wl.make_nlp_router(cfg.D, g["dm"], g["n_heads"], g["d_ff"], g["head_hidden"], cfg.K, cfg.seed + 77)
+    t = {k: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for k, v in p.items()}
+    head = mq.Router(t["head_w1"], t["head_b1"], t["head_w2"], t["head_b2"], g["dm"], g["head_hidden"], cfg.K)
+    r = mq.NlpRouter(t, head, cfg.D, g["dm"], g["n_heads"], g["d_ff"])
+    idx = torch.zeros(cfg.S, dtype=torch.int32, device=dev)
+    ws = torch.empty(mq.moqe_route_nlp_workspace_bytes(cfg.S, cfg.T, r), dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        mq.moqe_route_nlp(x, cfg.S, cfg.T, r, idx, None, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(calls):
+        mq.moqe_route_nlp(x, cfg.S, cfg.T, r, idx, None, ws)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / calls * 1e6
+    params = sum(int(v.size) for v in p.values())
+    return {"us_per_call": us, "parameters": params, "fp32_megabytes": params * 4 / 1e6, **g}
+
+
 def measure(name, steps, warmup, copies=0, with_graph=False, experts=None):
     """Builds the workload on the GPU, times `steps` forwards after `warmup` untimed ones, and returns the
     step metrics and the roofline of its dominant kernel (HIP events on the launch stream, recorded by the
@@ -259,6 +290,8 @@ def measure(name, steps, warmup, copies=0, with_graph=False, experts=None):
     roof["algorithmic_flops_per_launch"] = dom_flops
     res = {"cfg": cfg, "n_copies": n_copies, "hist": hist, "ms_per_step": ms_per_step, "value": units / (dt / steps),
            "graph_ms_per_step": graph_ms, "roofline": roof, "steps": steps}
+    if is_mlp and experts is None:
+        res["router_nlp"] = measure_router_nlp(cfg, x)
     del blocks, calls
     torch.cuda.empty_cache()
     return res
@@ -312,7 +345,8 @@ def main():
         c = r["cfg"]
         return {"workload": c.name, "samples": c.S, "rows_per_sample": c.T, "experts": [e.label() for e in c.experts],
                 "routing_histogram": r["hist"], "steps": r["steps"], "ms_per_step": r["ms_per_step"],
-                "value": r["value"], "unit": f"{c.unit}/s", "roofline": r["roofline"]}
+                "value": r["value"], "unit": f"{c.unit}/s", "roofline": r["roofline"],
+                **({"router_nlp": r["router_nlp"]} if "router_nlp" in r else {})}
 
     others = []
     if not args.no_other_workloads and args.workload == "llama7b_mlp_decode":
@@ -329,7 +363,8 @@ def main():
                    "experts": [e.label() for e in cfg.experts], "routing_histogram": head["hist"],
                    "arithmetic": "bf16 activations x exact integer weight codes on bf16 MFMA, fp32 accumulate and scales",
                    "rotating_weight_copies": head["n_copies"],
-                   "ms_per_step_graph_replay": head["graph_ms_per_step"]},
+                   "ms_per_step_graph_replay": head["graph_ms_per_step"],
+                   **({"router_nlp": head["router_nlp"]} if "router_nlp" in head else {})},
         "roofline": roof,
         "workloads": others,
     }

@@ -13,6 +13,7 @@
 // The MLP head on the pooled vector is the small router of route.hip.
 #include "qgemm_device.h"
 
+#include <algorithm>
 #include <cstring>
 
 namespace moqe {
@@ -66,6 +67,8 @@ struct LinArgs {
   uint16_t* c16;          // bf16 [M, n] or NULL
   int M, n, k;
   int relu;
+  int ksplit;             // > 1: work-group z multiplies its share of the k-tiles and stores the raw sums to part[z]
+  float* part;            // fp32 [ksplit, M, n]
 };
 
 __global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
@@ -75,6 +78,7 @@ __global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.y * LBM, n0 = blockIdx.x * LBN;
   const int KT = la.k / LBK;
+  const int kt0 = int(blockIdx.z) * KT / la.ksplit, kt1 = (int(blockIdx.z) + 1) * KT / la.ksplit;   // this work-group's k-tiles
   // staging: a tile is 128 rows x 8 units of 16 bytes = 1024 units, 4 per thread per operand
   const int s_unit = tid & 7, s_row0 = tid >> 3;             // rows s_row0 + 32 i
   const uint16_t* a_src[4];
@@ -111,12 +115,12 @@ __global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  fetch(0);
+  fetch(kt0);
   store(0);
-  fetch(1);
+  fetch(kt0 + 1);
   __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const int buf = (kt - kt0) & 1;
     const uint8_t* ab = lds + buf * 2 * L_TILE_BYTES + (wm * 64 + lr) * 128;
     const uint8_t* wb = lds + buf * 2 * L_TILE_BYTES + L_TILE_BYTES + (wn * 64 + lr) * 128;
 #pragma unroll
@@ -150,6 +154,10 @@ __global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
         const int row = m0 + wm * 64 + mb * 16 + 4 * lq + r;
         if (row < la.M) {
           const size_t o = size_t(row) * la.n + col;
+          if (la.ksplit > 1) {
+            la.part[size_t(blockIdx.z) * la.M * la.n + o] = acc[mb][nb][r];
+            continue;
+          }
           float v = acc[mb][nb][r] + bv;
           if (la.residual) v += la.residual[o];
           if (la.relu) v = fmaxf(v, 0.f);
@@ -157,6 +165,28 @@ __global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
           if (la.c16) la.c16[o] = float_to_bf16_rne(v);
         }
       }
+  }
+}
+
+// Split launches: C = (sum over the k-shares, in order) + bias [+ residual] [ReLU]; four columns per thread.
+__global__ __launch_bounds__(256) void k_lin_finish(const LinArgs la) {
+  const size_t i = (size_t(blockIdx.x) * 256 + threadIdx.x) * 4, total = size_t(la.M) * la.n;
+  if (i >= total) return;
+  float4 v = *reinterpret_cast<const float4*>(la.part + i);
+  for (int z = 1; z < la.ksplit; ++z) {
+    const float4 t = *reinterpret_cast<const float4*>(la.part + size_t(z) * total + i);
+    v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+  }
+  const int col = int(i % size_t(la.n));
+  if (la.bias) { const float4 t = *reinterpret_cast<const float4*>(la.bias + col); v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w; }
+  if (la.residual) { const float4 t = *reinterpret_cast<const float4*>(la.residual + i); v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w; }
+  if (la.relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+  if (la.c32) *reinterpret_cast<float4*>(la.c32 + i) = v;
+  if (la.c16) {
+    uint2 o;
+    o.x = pack_bf16x2(v.x, v.y);
+    o.y = pack_bf16x2(v.z, v.w);
+    *reinterpret_cast<uint2*>(la.c16 + i) = o;
   }
 }
 
@@ -298,22 +328,35 @@ __global__ __launch_bounds__(256) void k_layer_norm(const float* __restrict__ x,
   }
 }
 
-// pooled[s][c] = (sum over t in order of z[s][t][c]) / T
-__global__ __launch_bounds__(256) void k_pool_f32(const float* __restrict__ z, float* __restrict__ pooled, int S, int T, int n) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= S * n) return;
-  const int s = i / n, c = i - s * n;
-  const float* p = z + size_t(s) * T * n + c;
+// pooled[s][c] = (sum over the sample's tokens of z[s][t][c]) / T.  A work-group takes 64 columns of one sample; wave w
+// adds the tokens w, w + 16, ... in order, the 16 partial sums are added in wave order.
+__global__ __launch_bounds__(1024) void k_pool_f32(const float* __restrict__ z, float* __restrict__ pooled, int S, int T, int n) {
+  __shared__ float part[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int s = blockIdx.y, c = blockIdx.x * 64 + lane;
   float acc = 0.f;
-  for (int t = 0; t < T; ++t) acc += p[size_t(t) * n];
-  pooled[i] = __fdiv_rn(acc, float(T));
+  if (c < n) {
+    const float* p = z + size_t(s) * T * n + c;
+    for (int t = wave; t < T; t += 16) acc += p[size_t(t) * n];
+  }
+  part[wave][lane] = acc;
+  __syncthreads();
+  if (wave == 0 && c < n) {
+    float v = part[0][lane];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) v += part[w][lane];
+    pooled[size_t(s) * n + c] = __fdiv_rn(v, float(T));
+  }
 }
 
 // ---- host side -------------------------------------------------------------------------------------------------
 namespace {
+constexpr int LIN_SPLIT_MAX = 16;            // most k-shares of one product
+constexpr int LIN_SPLIT_MAX_ROWS = 512;      // products with more rows fill the chip without splitting
+
 struct NlpLayout {
   size_t w_in, wqkv1, wo1, wff1, wff2, wqkv2, wo2;          // bf16 parameter copies
-  size_t t32a, t32b, t32c, t16a, t16b, qkv, hid, pooled, head, total;
+  size_t t32a, t32b, t32c, t16a, t16b, qkv, hid, part, pooled, head, total;
 };
 
 NlpLayout nlp_layout(int S, int T, const moqe_nlp_router& r) {
@@ -335,6 +378,8 @@ NlpLayout nlp_layout(int S, int T, const moqe_nlp_router& r) {
   L.t16b = take(M * dm * 2);
   L.qkv = take(M * 3 * dm * 4);
   L.hid = take(M * size_t(r.d_ff) * 2);
+  const size_t widest = std::max<size_t>(3 * dm, size_t(r.d_ff));
+  L.part = take(M <= size_t(LIN_SPLIT_MAX_ROWS) ? size_t(LIN_SPLIT_MAX) * M * widest * 4 : 0);   // k-shares of launches with few rows
   L.pooled = take(size_t(S) * dm * 4);
   L.head = take(route_ws_bytes(S, 1, r.head));
   L.total = o;
@@ -342,10 +387,16 @@ NlpLayout nlp_layout(int S, int T, const moqe_nlp_router& r) {
 }
 
 int32_t lin(const uint16_t* a, const uint16_t* w, const float* bias, const float* residual, float* c32, uint16_t* c16, int M, int n,
-            int k, bool relu, hipStream_t st) {
-  LinArgs la{a, w, bias, residual, c32, c16, M, n, k, relu ? 1 : 0};
+            int k, bool relu, float* part, hipStream_t st) {
+  LinArgs la{a, w, bias, residual, c32, c16, M, n, k, relu ? 1 : 0, 1, part};
+  const int wgs = (n / LBN) * ((M + LBM - 1) / LBM), KT = k / LBK;
+  // few rows: the k-tiles are shared out over more work-groups (at least two tiles each), summed by a second launch
+  if (M <= LIN_SPLIT_MAX_ROWS)
+    while (wgs * la.ksplit < 96 && la.ksplit * 4 <= KT && la.ksplit < LIN_SPLIT_MAX) la.ksplit *= 2;
   ProfileScope ps(MOQE_PK_ROUTE, st);
-  hipLaunchKernelGGL(k_lin, dim3(n / LBN, (M + LBM - 1) / LBM), dim3(256), L_LDS_BYTES, st, la);
+  hipLaunchKernelGGL(k_lin, dim3(n / LBN, (M + LBM - 1) / LBM, la.ksplit), dim3(256), L_LDS_BYTES, st, la);
+  if (la.ksplit > 1)
+    hipLaunchKernelGGL(k_lin_finish, dim3(unsigned((size_t(M) * n / 4 + 255) / 256)), dim3(256), 0, st, la);
   return check_launch("route_nlp(linear)");
 }
 
@@ -422,24 +473,24 @@ int32_t launch_route_nlp(const void* x, int S, int T, const moqe_nlp_router& r, 
   if (rc) return rc;
   const uint16_t* xb = static_cast<const uint16_t*>(x);
   // u = x W_in^T + b_in                                             u: t32a / t16a
-  if ((rc = lin(xb, b16(L.w_in), r.b_in, nullptr, f32(L.t32a), b16(L.t16a), M, dm, r.d, false, st))) return rc;
+  if ((rc = lin(xb, b16(L.w_in), r.b_in, nullptr, f32(L.t32a), b16(L.t16a), M, dm, r.d, false, f32(L.part), st))) return rc;
   // encoder layer: v = LN1(u + attention(u))                         v: t32c / t16a
-  if ((rc = lin(b16(L.t16a), b16(L.wqkv1), r.bqkv1, nullptr, f32(L.qkv), nullptr, M, 3 * dm, dm, false, st))) return rc;
+  if ((rc = lin(b16(L.t16a), b16(L.wqkv1), r.bqkv1, nullptr, f32(L.qkv), nullptr, M, 3 * dm, dm, false, f32(L.part), st))) return rc;
   if ((rc = attention(f32(L.qkv), b16(L.t16b), S, T, dm, r.n_heads, st))) return rc;
-  if ((rc = lin(b16(L.t16b), b16(L.wo1), r.bo1, f32(L.t32a), f32(L.t32b), nullptr, M, dm, dm, false, st))) return rc;
+  if ((rc = lin(b16(L.t16b), b16(L.wo1), r.bo1, f32(L.t32a), f32(L.t32b), nullptr, M, dm, dm, false, f32(L.part), st))) return rc;
   if ((rc = layer_norm(f32(L.t32b), r.ln1_g, r.ln1_b, M, dm, f32(L.t32c), b16(L.t16a), st))) return rc;
   //                w = LN2(v + W2 relu(W1 v + b1) + b2)              w: t32a / t16a
-  if ((rc = lin(b16(L.t16a), b16(L.wff1), r.b_ff1, nullptr, nullptr, b16(L.hid), M, dff, dm, true, st))) return rc;
-  if ((rc = lin(b16(L.hid), b16(L.wff2), r.b_ff2, f32(L.t32c), f32(L.t32b), nullptr, M, dm, dff, false, st))) return rc;
+  if ((rc = lin(b16(L.t16a), b16(L.wff1), r.b_ff1, nullptr, nullptr, b16(L.hid), M, dff, dm, true, f32(L.part), st))) return rc;
+  if ((rc = lin(b16(L.hid), b16(L.wff2), r.b_ff2, f32(L.t32c), f32(L.t32b), nullptr, M, dm, dff, false, f32(L.part), st))) return rc;
   if ((rc = layer_norm(f32(L.t32b), r.ln2_g, r.ln2_b, M, dm, f32(L.t32a), b16(L.t16a), st))) return rc;
   // attention module: z = LN3(w + attention2(w))                     z: t32c
-  if ((rc = lin(b16(L.t16a), b16(L.wqkv2), r.bqkv2, nullptr, f32(L.qkv), nullptr, M, 3 * dm, dm, false, st))) return rc;
+  if ((rc = lin(b16(L.t16a), b16(L.wqkv2), r.bqkv2, nullptr, f32(L.qkv), nullptr, M, 3 * dm, dm, false, f32(L.part), st))) return rc;
   if ((rc = attention(f32(L.qkv), b16(L.t16b), S, T, dm, r.n_heads, st))) return rc;
-  if ((rc = lin(b16(L.t16b), b16(L.wo2), r.bo2, f32(L.t32a), f32(L.t32b), nullptr, M, dm, dm, false, st))) return rc;
+  if ((rc = lin(b16(L.t16b), b16(L.wo2), r.bo2, f32(L.t32a), f32(L.t32b), nullptr, M, dm, dm, false, f32(L.part), st))) return rc;
   if ((rc = layer_norm(f32(L.t32b), r.ln3_g, r.ln3_b, M, dm, f32(L.t32c), nullptr, st))) return rc;
   {
     ProfileScope ps(MOQE_PK_ROUTE, st);
-    hipLaunchKernelGGL(k_pool_f32, dim3((S * dm + 255) / 256), dim3(256), 0, st, f32(L.t32c), f32(L.pooled), S, T, dm);
+    hipLaunchKernelGGL(k_pool_f32, dim3((dm + 63) / 64, S), dim3(1024), 0, st, f32(L.t32c), f32(L.pooled), S, T, dm);
     if ((rc = check_launch("route_nlp(pool)"))) return rc;
   }
   return launch_route_features(f32(L.pooled), S, r.head, idx, logits, p + L.head, st);

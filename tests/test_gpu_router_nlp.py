@@ -23,6 +23,7 @@ CASES = {
     "ragged_tiles_dh64": (2, 70, 128, 256, 4, 256, 64, 5),
     "dh16_many_heads": (3, 19, 64, 128, 8, 128, 32, 2),
     "dh128": (2, 33, 64, 256, 2, 128, 32, 4),
+    "many_rows": (3, 200, 256, 128, 2, 256, 32, 4),
     "paper_size": (4, 37, 4096, 384, 6, 1536, 384, 4),
 }
 

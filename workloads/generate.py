@@ -16,7 +16,7 @@ nearest even) and back, which defines the input values themselves.
 """
 from __future__ import annotations
 
-from typing import Dict, Optional
+from typing import Dict, Optional, Sequence
 
 import numpy as np
 
@@ -128,4 +128,57 @@ def make_token_activations(S: int, T: int, D: int, seed: int, topic_std: float =
     vector (sequences differ in content) plus N(0, 1) noise per token."""
     a, b = [np.random.default_rng(s) for s in np.random.SeedSequence(seed).spawn(2)]
     x = a.standard_normal((S, 1, D), dtype=np.float32) * np.float32(topic_std) + b.standard_normal((S, T, D), dtype=np.float32)
+    return f32_to_bf16_bits(x)
+
+
+def make_cv_router(c_in: int, mlp: Sequence[int], stages: Sequence[int], strides: Sequence[int], K: int, seed: int) -> Dict[str, np.ndarray]:
+    """Random fp32 parameters of the CV router model.  Matrices [out, in] and filters [out, 3, 3, in] with N(0, 1/fan-in)
+    entries, biases N(0, 0.05); batch-norm gains 1 + N(0, 0.1), offsets N(0, 0.1), means N(0, 0.1), variances in
+    [0.5, 1.5]; zero-sum last layer (see make_router).  A stage has a 1x1 shortcut when its stride or width changes."""
+    rng = iter(np.random.default_rng(s) for s in np.random.SeedSequence(seed).spawn(128))
+
+    def mat(*shape):
+        fan = int(np.prod(shape[1:]))
+        return next(rng).standard_normal(shape, dtype=np.float32) * np.float32(1.0 / np.sqrt(fan))
+
+    def vec(n, std=0.05, mean=0.0):
+        return next(rng).standard_normal(n, dtype=np.float32) * np.float32(std) + np.float32(mean)
+
+    def bn(prefix, n, p):
+        p[prefix + "_g"], p[prefix + "_o"], p[prefix + "_m"] = vec(n, 0.1, 1.0), vec(n, 0.1), vec(n, 0.1)
+        p[prefix + "_v"] = (next(rng).random(n, dtype=np.float32) + np.float32(0.5))
+
+    p: Dict[str, np.ndarray] = {}
+    prev = c_in
+    for i, n in enumerate(mlp):
+        p["mlp%d_w" % i], p["mlp%d_b" % i] = mat(n, prev), vec(n)
+        bn("mlp%d_bn" % i, n, p)
+        prev = n
+    for i, (n, st) in enumerate(zip(stages, strides)):
+        p["st%d_a" % i] = mat(n, 3, 3, prev)
+        bn("st%d_abn" % i, n, p)
+        p["st%d_b" % i] = mat(n, 3, 3, n)
+        bn("st%d_bbn" % i, n, p)
+        p["st%d_se1" % i], p["st%d_se1b" % i] = mat(n // 4, n), vec(n // 4)
+        p["st%d_se2" % i], p["st%d_se2b" % i] = mat(n, n // 4), vec(n)
+        if st != 1 or n != prev:
+            p["st%d_s" % i] = mat(n, prev)
+            bn("st%d_sbn" % i, n, p)
+        prev = n
+    p["wqkv"], p["bqkv"] = mat(3 * prev, prev), vec(3 * prev)
+    p["wo"], p["bo"] = mat(prev, prev), vec(prev)
+    w = mat(K, prev)
+    w -= w.mean(axis=1, keepdims=True, dtype=np.float32)
+    p["w_out"], p["b_out"] = w, vec(K)
+    return p
+
+
+def make_image_activations(S: int, h: int, w: int, c: int, seed: int) -> np.ndarray:
+    """bf16 NHWC images [S, h, w, c] as uint16 bit patterns: a per-image N(0, 1) channel offset, a smooth per-image spatial
+    pattern and N(0, 1) noise per pixel, so that images differ in content and positions differ within an image."""
+    a, b, d = [np.random.default_rng(s) for s in np.random.SeedSequence(seed).spawn(3)]
+    x = a.standard_normal((S, 1, 1, c), dtype=np.float32) + b.standard_normal((S, h, w, c), dtype=np.float32)
+    yy, xx = np.meshgrid(np.linspace(-1, 1, h, dtype=np.float32), np.linspace(-1, 1, w, dtype=np.float32), indexing="ij")
+    slope = d.standard_normal((S, 2, c), dtype=np.float32)
+    x += slope[:, 0][:, None, None, :] * yy[None, :, :, None] + slope[:, 1][:, None, None, :] * xx[None, :, :, None]
     return f32_to_bf16_bits(x)

@@ -120,6 +120,38 @@ typedef struct moqe_nlp_router {
   int32_t d, dm, n_heads, d_ff;
 } moqe_nlp_router;
 
+/* The CV router model (Section 3.2, "CV Router Model"): a three-layer MLP, every linear layer followed by batch
+ * normalisation and ReLU; a three-stage SEResNet-8 (the paper: 16, 32, 64 channels, strides 1, 2, 2); the last
+ * feature map flattened into a sequence and fed to a multi-head self-attention module (the paper: 8 heads) that
+ * gives the routing logits.  The paper fixes this order; the rest is read as follows.
+ *   MLP      : on every pixel's channel vector, x <- relu(bn(W x + b)), three times (widths mlp_n).
+ *   bn       : (x - mean) / sqrt(var + 1e-5) * gain + offset per channel (stored statistics).
+ *   stage    : a = relu(bn_a(conv3x3(x, conv_a, stride)));  u = bn_b(conv3x3(a, conv_b, 1));
+ *              g = sigmoid(se_w2 relu(se_w1 mean_pixels(u) + se_b1) + se_b2)   (squeeze width cout / 4);
+ *              x <- relu(u * g + shortcut), shortcut = x, or short_bn(conv1x1(x, short_w, stride)) when short_w is
+ *              given (required when the stride is 2 or the width changes).  3x3 convolutions pad by 1; filters are
+ *              [cout, kh, kw, cin] (taps slow, channels fast), short_w is [cout, cin].
+ *   attention: on the h' * w' positions of the last map (width dm = stage[2].cout): [Q K V] = x Wqkv^T + bqkv (rows of
+ *              Wqkv: queries, keys, values), heads of width dm / n_heads, softmax(Q K^T / sqrt(dh)) V, Wo and bo,
+ *              mean over the positions;  logits = w_out mean + b_out.
+ * All parameters device fp32.  Widths multiples of 4 and at most 64, dm a multiple of 8, head width at most 16, at most
+ * 36 positions in the last map (inputs up to 24 x 24 with the paper's strides); w_out 16-byte aligned. */
+typedef struct moqe_bn { const float *gain, *offset, *mean, *var; } moqe_bn;
+typedef struct moqe_cv_stage {
+  const float* conv_a; moqe_bn bn_a;
+  const float* conv_b; moqe_bn bn_b;
+  const float *se_w1, *se_b1, *se_w2, *se_b2;
+  const float* short_w; moqe_bn short_bn;                /* short_w NULL: identity shortcut */
+  int32_t cout, stride;
+} moqe_cv_stage;
+typedef struct moqe_cv_router {
+  const float* mlp_w[3]; const float* mlp_b[3]; moqe_bn mlp_bn[3]; int32_t mlp_n[3];
+  moqe_cv_stage stage[3];
+  const float *wqkv, *bqkv, *wo, *bo;                    /* [3dm, dm], [3dm], [dm, dm], [dm] */
+  const float *w_out, *b_out;                            /* [K, dm], [K] or NULL */
+  int32_t c_in, n_heads, n_experts;
+} moqe_cv_router;
+
 /* One routed block.  w0/w1/w2 are host arrays of n_experts PACKED matrices.
  *   LINEAR   : y = x W0^T.                         x [S*T, d], y [S*T, n]
  *   SILU_MLP : h = bf16(silu(x Wg^T) * (x Wu^T)), y = h Wd^T with w0 = gate, w1 = up,
@@ -214,6 +246,16 @@ size_t moqe_route_nlp_workspace_bytes(int32_t S, int32_t T, const moqe_nlp_route
 int32_t moqe_route_nlp(const void* x, int32_t S, int32_t T, const moqe_nlp_router* r,
                        int32_t* expert_idx, float* logits,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Routing with the CV router model (Section 3.2; the stages are listed at moqe_cv_router).
+ *   x          : device bf16 NHWC [S, h, w, c_in] (the tensor the routed stage sees)
+ *   expert_idx : device int32 [S] out (top-1, ties to the lowest index);  logits: device float [S, K] out or NULL
+ * fp32 arithmetic throughout, every sum in a fixed order (deterministic).  About 20 small launches on `stream`;
+ * workspace as the query says, 256-byte aligned.  S == 0 is a no-op. */
+size_t moqe_route_cv_workspace_bytes(int32_t S, int32_t h, int32_t w, const moqe_cv_router* r);
+int32_t moqe_route_cv(const void* x, int32_t S, int32_t h, int32_t w, const moqe_cv_router* r,
+                      int32_t* expert_idx, float* logits,
+                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- expert weights ----------------------------------------------------------------- */
 

@@ -48,6 +48,23 @@ class _NlpRouter(C.Structure):
                                                          ("n_heads", C.c_int32), ("d_ff", C.c_int32)]
 
 
+class _Bn(C.Structure):
+    _fields_ = [("gain", C.c_void_p), ("offset", C.c_void_p), ("mean", C.c_void_p), ("var", C.c_void_p)]
+
+
+class _CvStage(C.Structure):
+    _fields_ = [("conv_a", C.c_void_p), ("bn_a", _Bn), ("conv_b", C.c_void_p), ("bn_b", _Bn),
+                ("se_w1", C.c_void_p), ("se_b1", C.c_void_p), ("se_w2", C.c_void_p), ("se_b2", C.c_void_p),
+                ("short_w", C.c_void_p), ("short_bn", _Bn), ("cout", C.c_int32), ("stride", C.c_int32)]
+
+
+class _CvRouter(C.Structure):
+    _fields_ = [("mlp_w", C.c_void_p * 3), ("mlp_b", C.c_void_p * 3), ("mlp_bn", _Bn * 3), ("mlp_n", C.c_int32 * 3),
+                ("stage", _CvStage * 3), ("wqkv", C.c_void_p), ("bqkv", C.c_void_p), ("wo", C.c_void_p), ("bo", C.c_void_p),
+                ("w_out", C.c_void_p), ("b_out", C.c_void_p), ("c_in", C.c_int32), ("n_heads", C.c_int32),
+                ("n_experts", C.c_int32)]
+
+
 class _Block(C.Structure):
     _fields_ = [("kind", C.c_int32), ("router", _Router),
                 ("w0", C.POINTER(_QMat)), ("w1", C.POINTER(_QMat)), ("w2", C.POINTER(_QMat)),
@@ -75,6 +92,8 @@ def _load() -> C.CDLL:
         "moqe_balance_stats": (i32, [vp, vp, i32, i32, C.c_float, vp, vp]),
         "moqe_route_nlp_workspace_bytes": (sz, [i32, i32, C.POINTER(_NlpRouter)]),
         "moqe_route_nlp": (i32, [vp, i32, i32, C.POINTER(_NlpRouter), vp, vp, vp, sz, vp]),
+        "moqe_route_cv_workspace_bytes": (sz, [i32, i32, i32, C.POINTER(_CvRouter)]),
+        "moqe_route_cv": (i32, [vp, i32, i32, i32, C.POINTER(_CvRouter), vp, vp, vp, sz, vp]),
         "moqe_route_ragged_workspace_bytes": (sz, [i32, C.POINTER(_Router)]),
         "moqe_route_ragged": (i32, [vp, vp, i32, C.POINTER(_Router), vp, vp, vp, sz, vp]),
         "moqe_expand_rows": (i32, [vp, vp, vp, i32, i32, vp, vp, vp, vp]),
@@ -111,7 +130,7 @@ INPUT_IN_BUCKET_ORDER = 2
 OUTPUT_BF16 = 4
 
 EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_route_workspace_bytes",
-            "moqe_route", "moqe_route_nlp_workspace_bytes", "moqe_route_nlp", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",
+            "moqe_route", "moqe_route_nlp_workspace_bytes", "moqe_route_nlp", "moqe_route_cv_workspace_bytes", "moqe_route_cv", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",
             "moqe_expand_rows", "moqe_workspace_bytes_ragged", "moqe_forward_ragged", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
             "moqe_workspace_bytes", "moqe_forward", "moqe_forward_static", "moqe_label_pass_workspace_bytes", "moqe_label_pass", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
@@ -188,6 +207,38 @@ class NlpRouter:
             setattr(r, n, _ptr(self.params[n]))
         r.head = self.head.c()
         r.d, r.dm, r.n_heads, r.d_ff = self.d, self.dm, self.n_heads, self.d_ff
+        return r
+
+
+@dataclass
+class CvRouter:
+    """The CV router model.  `params` holds fp32 device tensors under the names of workloads.make_cv_router:
+    mlp{i}_w / _b / _bn_{g,o,m,v}, st{i}_a / _abn_* / _b / _bbn_* / _se1 / _se1b / _se2 / _se2b [/ _s / _sbn_*],
+    wqkv, bqkv, wo, bo, w_out, b_out."""
+    params: dict
+    c_in: int
+    strides: Sequence[int]
+    n_heads: int
+    n_experts: int
+
+    def c(self) -> _CvRouter:
+        p = self.params
+        bn = lambda pre: _Bn(_ptr(p[pre + "_g"]), _ptr(p[pre + "_o"]), _ptr(p[pre + "_m"]), _ptr(p[pre + "_v"]))
+        r = _CvRouter()
+        for i in range(3):
+            r.mlp_w[i], r.mlp_b[i], r.mlp_bn[i] = _ptr(p["mlp%d_w" % i]), _ptr(p["mlp%d_b" % i]), bn("mlp%d_bn" % i)
+            r.mlp_n[i] = p["mlp%d_w" % i].shape[0]
+            st = r.stage[i]
+            st.conv_a, st.bn_a = _ptr(p["st%d_a" % i]), bn("st%d_abn" % i)
+            st.conv_b, st.bn_b = _ptr(p["st%d_b" % i]), bn("st%d_bbn" % i)
+            st.se_w1, st.se_b1 = _ptr(p["st%d_se1" % i]), _ptr(p["st%d_se1b" % i])
+            st.se_w2, st.se_b2 = _ptr(p["st%d_se2" % i]), _ptr(p["st%d_se2b" % i])
+            if ("st%d_s" % i) in p:
+                st.short_w, st.short_bn = _ptr(p["st%d_s" % i]), bn("st%d_sbn" % i)
+            st.cout, st.stride = p["st%d_a" % i].shape[0], self.strides[i]
+        r.wqkv, r.bqkv, r.wo, r.bo = _ptr(p["wqkv"]), _ptr(p["bqkv"]), _ptr(p["wo"]), _ptr(p["bo"])
+        r.w_out, r.b_out = _ptr(p["w_out"]), _ptr(p["b_out"])
+        r.c_in, r.n_heads, r.n_experts = self.c_in, self.n_heads, self.n_experts
         return r
 
 
@@ -276,6 +327,20 @@ def moqe_route_nlp(x: torch.Tensor, S: int, T: int, r: NlpRouter, expert_idx: to
         workspace = _workspace(lib.moqe_route_nlp_workspace_bytes(S, T, C.byref(rc)), x.device)
     _check(lib.moqe_route_nlp(_ptr(x), S, T, C.byref(rc), _ptr(expert_idx), _ptr(logits), _ptr(workspace),
                               workspace.numel(), _stream()))
+
+
+def moqe_route_cv_workspace_bytes(S: int, h: int, w: int, r: CvRouter) -> int:
+    rc = r.c()
+    return lib.moqe_route_cv_workspace_bytes(S, h, w, C.byref(rc))
+
+
+def moqe_route_cv(x: torch.Tensor, S: int, h: int, w: int, r: CvRouter, expert_idx: torch.Tensor,
+                  logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    rc = r.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_route_cv_workspace_bytes(S, h, w, C.byref(rc)), x.device)
+    _check(lib.moqe_route_cv(_ptr(x), S, h, w, C.byref(rc), _ptr(expert_idx), _ptr(logits), _ptr(workspace),
+                             workspace.numel(), _stream()))
 
 
 def moqe_balance_stats(logits: torch.Tensor, counts: torch.Tensor, S: int, K: int, alpha: float,

@@ -279,6 +279,26 @@ int32_t moqe_route_nlp(const void* x, int32_t S, int32_t T, const moqe_nlp_route
   return launch_route_nlp(x, S, T, *r, expert_idx, logits, workspace, static_cast<hipStream_t>(stream));
 }
 
+size_t moqe_route_cv_workspace_bytes(int32_t S, int32_t h, int32_t w, const moqe_cv_router* r) {
+  if (S < 0 || h <= 0 || w <= 0 || (long long)S * h * w > 0x7fffffffLL) return 0;
+  if (check_cv_router(r, h, w, "moqe_route_cv_workspace_bytes")) return 0;
+  return route_cv_ws_bytes(S, h, w, *r);
+}
+
+int32_t moqe_route_cv(const void* x, int32_t S, int32_t h, int32_t w, const moqe_cv_router* r, int32_t* expert_idx, float* logits,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (S < 0 || h <= 0 || w <= 0 || (long long)S * h * w > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_route_cv: S=%d h=%d w=%d", S, h, w);
+  int32_t rc = check_cv_router(r, h, w, "moqe_route_cv");
+  if (rc) return rc;
+  if (S == 0) return MOQE_OK;
+  if (!x || !expert_idx) return set_error(MOQE_E_NULL, "moqe_route_cv: x or expert_idx is NULL");
+  const size_t need = route_cv_ws_bytes(S, h, w, *r);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < need)
+    return set_error(MOQE_E_WORKSPACE, "moqe_route_cv: workspace needs %zu bytes, 256-byte aligned", need);
+  if (dry_run()) return MOQE_OK;
+  return launch_route_cv(x, S, h, w, *r, expert_idx, logits, workspace, static_cast<hipStream_t>(stream));
+}
+
 size_t moqe_route_ragged_workspace_bytes(int32_t S, const moqe_router* r) {
   if (!r || S < 0 || r->d <= 0) return 0;
   return route_ws_bytes(S, 2, *r);

@@ -200,6 +200,9 @@ int32_t launch_route(const void* x, int S, int T, const moqe_router& r, int32_t*
                      void* ws, hipStream_t st);
 size_t  route_ws_bytes(int S, int T, const moqe_router& r);
 int32_t launch_route_features(const float* feat, int S, const moqe_router& r, int32_t* idx, float* logits, void* ws, hipStream_t st);
+int32_t check_cv_router(const moqe_cv_router* r, int h, int w, const char* who);
+size_t  route_cv_ws_bytes(int S, int h, int w, const moqe_cv_router& r);
+int32_t launch_route_cv(const void* x, int S, int h, int w, const moqe_cv_router& r, int32_t* idx, float* logits, void* ws, hipStream_t st);
 int32_t check_nlp_router(const moqe_nlp_router* r, const char* who);
 size_t  route_nlp_ws_bytes(int S, int T, const moqe_nlp_router& r);
 int32_t launch_route_nlp(const void* x, int S, int T, const moqe_nlp_router& r, int32_t* idx, float* logits, void* ws, hipStream_t st);

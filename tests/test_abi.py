@@ -192,6 +192,31 @@ def test_route_and_forward_argument_errors(mq):
     nr.dm, nr.wo2 = 384, None
     assert lib.moqe_route_nlp(FAKE, 4, 33, C.byref(nr), FAKE, None, FAKE, wn, None) == -1
     assert lib.moqe_route_nlp_workspace_bytes(4, 33, C.byref(nr)) == 0
+    # the CV router model
+    cv = mq._CvRouter()
+    bn = mq._Bn(FAKE, FAKE, FAKE, FAKE)
+    widths, chans, strides = (64, 32, 16), (16, 32, 64), (1, 2, 2)
+    for i in range(3):
+        cv.mlp_w[i], cv.mlp_b[i], cv.mlp_bn[i], cv.mlp_n[i] = FAKE, FAKE, bn, widths[i]
+        st = cv.stage[i]
+        st.conv_a, st.bn_a, st.conv_b, st.bn_b = FAKE, bn, FAKE, bn
+        st.se_w1, st.se_b1, st.se_w2, st.se_b2 = FAKE, FAKE, FAKE, FAKE
+        st.cout, st.stride = chans[i], strides[i]
+        if i > 0:
+            st.short_w, st.short_bn = FAKE, bn
+    cv.wqkv, cv.bqkv, cv.wo, cv.bo, cv.w_out, cv.b_out = FAKE, FAKE, FAKE, FAKE, FAKE, FAKE
+    cv.c_in, cv.n_heads, cv.n_experts = 256, 8, 4
+    wc = lib.moqe_route_cv_workspace_bytes(8, 14, 14, C.byref(cv))
+    assert wc >= 4 * 8 * 14 * 14 * 64 * 4
+    assert lib.moqe_route_cv(FAKE, 8, 14, 14, C.byref(cv), FAKE, None, FAKE, wc, None) == 0
+    assert lib.moqe_route_cv(FAKE, 0, 14, 14, C.byref(cv), None, None, None, 0, None) == 0
+    assert lib.moqe_route_cv(FAKE, 8, 14, 14, C.byref(cv), FAKE, None, FAKE, wc - 256, None) == -4
+    assert lib.moqe_route_cv(FAKE, 8, 14, 14, C.byref(cv), None, None, FAKE, wc, None) == -1
+    assert lib.moqe_route_cv(FAKE, 8, 56, 56, C.byref(cv), FAKE, None, FAKE, wc, None) == -2     # 14 x 14 positions left: too many
+    cv.stage[1].short_w = None
+    assert lib.moqe_route_cv(FAKE, 8, 14, 14, C.byref(cv), FAKE, None, FAKE, wc, None) == -2     # a strided stage needs a shortcut
+    cv.stage[1].short_w, cv.n_heads = FAKE, 3
+    assert lib.moqe_route_cv(FAKE, 8, 14, 14, C.byref(cv), FAKE, None, FAKE, wc, None) == -2     # heads do not divide 64
     # the label pass: all K experts on every sample, so K times the rows of a routed forward
     lneed = lib.moqe_label_pass_workspace_bytes(C.byref(blk), 4, 3)
     assert lneed >= 2 * 4 * 3 * (256 * 4 + 512 * 2)

@@ -179,6 +179,36 @@ def measure_router_nlp(cfg, x, calls=10):
     return {"us_per_call": us, "parameters": params, "fp32_megabytes": params * 4 / 1e6, **g}
 
 
+# The paper's CV router model with its stated channel counts, strides and head count; MLP widths of our choosing.
+CV_ROUTER = {"mlp": (64, 32, 16), "stages": (16, 32, 64), "strides": (1, 2, 2), "n_heads": 8}
+
+
+def measure_router_cv(cfg, x, calls=10):
+    """Time of one moqe_route_cv call on the workload's images (random parameters), not part of the step."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_2508_09204_amd import binding as mq
+    dev = x.device
+    g = CV_ROUTER
+    p = wl.make_cv_router(cfg.D, g["mlp"], g["stages"], g["strides"], cfg.K, cfg.seed + 78)
+    t = {k: torch.from_numpy(np.ascontiguousarray(v)).to(dev) for k, v in p.items()}
+    r = mq.CvRouter(t, cfg.D, g["strides"], g["n_heads"], cfg.K)
+    idx = torch.zeros(cfg.S, dtype=torch.int32, device=dev)
+    ws = torch.empty(mq.moqe_route_cv_workspace_bytes(cfg.S, cfg.img_h, cfg.img_w, r), dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        mq.moqe_route_cv(x, cfg.S, cfg.img_h, cfg.img_w, r, idx, None, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(calls):
+        mq.moqe_route_cv(x, cfg.S, cfg.img_h, cfg.img_w, r, idx, None, ws)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / calls * 1e6
+    params = sum(int(v.size) for v in p.values())
+    return {"us_per_call": us, "parameters": params, "fp32_megabytes": params * 4 / 1e6,
+            "routing_histogram": np.bincount(idx.cpu().numpy(), minlength=cfg.K).tolist(), **{k: list(v) if isinstance(v, tuple) else v for k, v in g.items()}}
+
+
 def measure(name, steps, warmup, copies=0, with_graph=False, experts=None):
     """Builds the workload on the GPU, times `steps` forwards after `warmup` untimed ones, and returns the
     step metrics and the roofline of its dominant kernel (HIP events on the launch stream, recorded by the
@@ -292,6 +322,8 @@ def measure(name, steps, warmup, copies=0, with_graph=False, experts=None):
            "graph_ms_per_step": graph_ms, "roofline": roof, "steps": steps}
     if is_mlp and experts is None:
         res["router_nlp"] = measure_router_nlp(cfg, x)
+    if is_conv and experts is None:
+        res["router_cv"] = measure_router_cv(cfg, x)
     del blocks, calls
     torch.cuda.empty_cache()
     return res
@@ -346,7 +378,8 @@ def main():
         return {"workload": c.name, "samples": c.S, "rows_per_sample": c.T, "experts": [e.label() for e in c.experts],
                 "routing_histogram": r["hist"], "steps": r["steps"], "ms_per_step": r["ms_per_step"],
                 "value": r["value"], "unit": f"{c.unit}/s", "roofline": r["roofline"],
-                **({"router_nlp": r["router_nlp"]} if "router_nlp" in r else {})}
+                **({"router_nlp": r["router_nlp"]} if "router_nlp" in r else {}),
+                **({"router_cv": r["router_cv"]} if "router_cv" in r else {})}
 
     others = []
     if not args.no_other_workloads and args.workload == "llama7b_mlp_decode":
@@ -364,7 +397,8 @@ def main():
                    "arithmetic": "bf16 activations x exact integer weight codes on bf16 MFMA, fp32 accumulate and scales",
                    "rotating_weight_copies": head["n_copies"],
                    "ms_per_step_graph_replay": head["graph_ms_per_step"],
-                   **({"router_nlp": head["router_nlp"]} if "router_nlp" in head else {})},
+                   **({"router_nlp": head["router_nlp"]} if "router_nlp" in head else {}),
+                   **({"router_cv": head["router_cv"]} if "router_cv" in head else {})},
         "roofline": roof,
         "workloads": others,
     }

@@ -292,6 +292,7 @@ int32_t moqe_route_cv(const void* x, int32_t S, int32_t h, int32_t w, const moqe
   if (rc) return rc;
   if (S == 0) return MOQE_OK;
   if (!x || !expert_idx) return set_error(MOQE_E_NULL, "moqe_route_cv: x or expert_idx is NULL");
+  if (!aligned(x, 16)) return set_error(MOQE_E_SHAPE, "moqe_route_cv: x must be 16-byte aligned");
   const size_t need = route_cv_ws_bytes(S, h, w, *r);
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < need)
     return set_error(MOQE_E_WORKSPACE, "moqe_route_cv: workspace needs %zu bytes, 256-byte aligned", need);

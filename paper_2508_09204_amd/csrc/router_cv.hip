@@ -5,7 +5,8 @@
 // small LDS-tiled kernels, every sum in a fixed order.
 //
 //   k_cv_conv       out = [relu] [bn] (conv(in) + bias): 1x1 or 3x3 (padding 1), stride 1 or 2, NHWC, as an
-//                   implicit GEMM: 64 output pixels x up to 64 output channels per work-group, k in chunks of 32
+//                   implicit GEMM: 4096 / CT output pixels x CT output channels per work-group (CT = 16, 32, 64),
+//                   k in chunks of 32 through LDS, a thread owns 4 pixels x 4 channels
 //   k_cv_se_gate    per image: channel means of u, two small linear layers, sigmoid
 //   k_cv_se_apply   relu(u * gate + shortcut)
 //   k_cv_attn_pool  per image: queries/keys/values, softmax attention per head, mean over positions, output projection
@@ -30,20 +31,25 @@ struct CvConvArgs {
   int in_bf16, S, hi, wi, cin, ho, wo, cout, taps, stride, relu;
 };
 
+// CT = output channels per work-group (16, 32 or 64); the work-group takes 4096 / CT output pixels, a thread 4 x 4.
+// Both operands are staged four channels at a time (cin is a multiple of 4, so a group of four never straddles a tap).
+template <int CT>
 __global__ __launch_bounds__(256) void k_cv_conv(const CvConvArgs a) {
-  __shared__ __align__(16) float As[32][64];      // [k][pixel]
-  __shared__ __align__(16) float Ws[32][64];      // [k][output channel]
+  constexpr int PT = 4096 / CT;                    // pixels per work-group
+  constexpr int CG = CT / 4;                       // thread groups along the output channels
+  constexpr int PI = PT / 32;                      // pixels a thread stages per chunk
+  __shared__ __align__(16) float As[32][PT];       // [k][pixel]
+  __shared__ __align__(16) float Ws[32][CT];       // [k][output channel]
   const int tid = threadIdx.x;
-  const int pg = tid >> 4, cg = tid & 15;         // 4 pixels x 4 output channels per thread
+  const int pg = tid / CG, cg = tid % CG;
   const int M = a.S * a.ho * a.wo, K = a.taps * a.cin;
-  const int p0 = blockIdx.x * 64;
+  const int p0 = blockIdx.x * PT, c0 = blockIdx.y * CT;
   const int pad = a.taps == 9 ? 1 : 0;
-  // staging: this thread copies column k_l of 8 pixels and of 8 output channels per chunk
-  const int k_l = tid & 31, r_l = tid >> 5;
-  int s_img[8], s_iy[8], s_ix[8];
+  const int kq = tid & 7, r_l = tid >> 3;          // staging: channels 4 kq .. 4 kq + 3 of the chunk, rows r_l + 32 i
+  int s_img[PI], s_iy[PI], s_ix[PI];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int px = p0 + r_l + 8 * i;
+  for (int i = 0; i < PI; ++i) {
+    const int px = p0 + r_l + 32 * i;
     if (px < M) {
       const int s = px / (a.ho * a.wo), rem = px - s * (a.ho * a.wo), oy = rem / a.wo, ox = rem - oy * a.wo;
       s_img[i] = s; s_iy[i] = oy * a.stride - pad; s_ix[i] = ox * a.stride - pad;
@@ -58,21 +64,35 @@ __global__ __launch_bounds__(256) void k_cv_conv(const CvConvArgs a) {
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
 
   for (int kc = 0; kc < K; kc += 32) {
-    const int k = kc + k_l;
-    const bool kin = k < K;
+    const int k = kc + 4 * kq;
+    const bool kin = k < K;                         // K is a multiple of 4: the four channels are in or out together
     const int tap = kin ? k / a.cin : 0, c = kin ? k - tap * a.cin : 0;
     const int kh = a.taps == 9 ? tap / 3 : 0, kw = a.taps == 9 ? tap - kh * 3 : 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < PI; ++i) {
       const int iy = s_iy[i] + kh, ix = s_ix[i] + kw;
-      float v = 0.f;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (kin && s_img[i] >= 0 && iy >= 0 && iy < a.hi && ix >= 0 && ix < a.wi) {
         const size_t at = ((size_t(s_img[i]) * a.hi + iy) * a.wi + ix) * a.cin + c;
-        v = a.in_bf16 ? __uint_as_float(uint32_t(static_cast<const uint16_t*>(a.in)[at]) << 16) : static_cast<const float*>(a.in)[at];
+        if (a.in_bf16) {
+          const uint2 b = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a.in) + at);
+          v = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xffff0000u), __uint_as_float(b.y << 16),
+                          __uint_as_float(b.y & 0xffff0000u));
+        } else {
+          v = *reinterpret_cast<const float4*>(static_cast<const float*>(a.in) + at);
+        }
       }
-      As[k_l][r_l + 8 * i] = v;
-      const int co = r_l + 8 * i;
-      Ws[k_l][co] = (kin && co < a.cout) ? a.w[size_t(co) * K + k] : 0.f;
+      const int px_l = r_l + 32 * i;
+      As[4 * kq + 0][px_l] = v.x; As[4 * kq + 1][px_l] = v.y; As[4 * kq + 2][px_l] = v.z; As[4 * kq + 3][px_l] = v.w;
+    }
+#pragma unroll
+    for (int i = 0; i < (CT + 31) / 32; ++i) {
+      const int co_l = r_l + 32 * i;
+      if (co_l < CT) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (kin && c0 + co_l < a.cout) v = *reinterpret_cast<const float4*>(a.w + size_t(c0 + co_l) * K + k);
+        Ws[4 * kq + 0][co_l] = v.x; Ws[4 * kq + 1][co_l] = v.y; Ws[4 * kq + 2][co_l] = v.z; Ws[4 * kq + 3][co_l] = v.w;
+      }
     }
     __syncthreads();
 #pragma unroll 8
@@ -89,7 +109,7 @@ __global__ __launch_bounds__(256) void k_cv_conv(const CvConvArgs a) {
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int co = cg * 4 + j;
+    const int co = c0 + cg * 4 + j;
     if (co >= a.cout) continue;
     const float bv = a.bias ? a.bias[co] : 0.f;
     float mean = 0.f, inv = 1.f, gain = 1.f, off = 0.f;
@@ -248,7 +268,9 @@ int32_t conv(const void* in, bool in_bf16, const float* w, const float* bias, co
   a.ho = out_size(hi, taps, stride); a.wo = out_size(wi, taps, stride);
   const long M = long(S) * a.ho * a.wo;
   ProfileScope ps(MOQE_PK_ROUTE, st);
-  hipLaunchKernelGGL(k_cv_conv, dim3(unsigned((M + 63) / 64)), dim3(256), 0, st, a);
+  if (cout <= 16) hipLaunchKernelGGL(k_cv_conv<16>, dim3(unsigned((M + 255) / 256), (cout + 15) / 16), dim3(256), 0, st, a);
+  else if (cout <= 32) hipLaunchKernelGGL(k_cv_conv<32>, dim3(unsigned((M + 127) / 128), (cout + 31) / 32), dim3(256), 0, st, a);
+  else hipLaunchKernelGGL(k_cv_conv<64>, dim3(unsigned((M + 63) / 64), (cout + 63) / 64), dim3(256), 0, st, a);
   return check_launch("route_cv(convolution)");
 }
 
@@ -258,7 +280,8 @@ bool bn_ok(const moqe_bn& b) { return b.gain && b.offset && b.mean && b.var; }
 int32_t check_cv_router(const moqe_cv_router* r, int h, int w, const char* who) {
   if (!r) return set_error(MOQE_E_NULL, "%s: router is NULL", who);
   if (r->n_experts < 1 || r->n_experts > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "%s: n_experts=%d", who, r->n_experts);
-  if (r->c_in <= 0 || h <= 0 || w <= 0) return set_error(MOQE_E_SHAPE, "%s: image %d x %d x %d", who, h, w, r->c_in);
+  if (r->c_in <= 0 || r->c_in % 4 || h <= 0 || w <= 0)
+    return set_error(MOQE_E_SHAPE, "%s: image %d x %d x %d (channels a multiple of 4)", who, h, w, r->c_in);
   for (int i = 0; i < 3; ++i) {
     if (!r->mlp_w[i] || !r->mlp_b[i] || !bn_ok(r->mlp_bn[i])) return set_error(MOQE_E_NULL, "%s: MLP layer %d has a NULL parameter", who, i);
     if (r->mlp_n[i] <= 0 || r->mlp_n[i] > CV_MAX_C || r->mlp_n[i] % 4)
@@ -274,6 +297,11 @@ int32_t check_cv_router(const moqe_cv_router* r, int h, int w, const char* who) 
     if (s.short_w && !bn_ok(s.short_bn)) return set_error(MOQE_E_NULL, "%s: stage %d: the shortcut's batch norm is NULL", who, i);
   }
   if (!r->wqkv || !r->bqkv || !r->wo || !r->bo || !r->w_out) return set_error(MOQE_E_NULL, "%s: an attention or output parameter is NULL", who);
+  for (int i = 0; i < 3; ++i) {
+    const void* mats[] = {r->mlp_w[i], r->stage[i].conv_a, r->stage[i].conv_b, r->stage[i].short_w};
+    for (const void* m : mats)
+      if (reinterpret_cast<uintptr_t>(m) % 16) return set_error(MOQE_E_SHAPE, "%s: weight matrices and filters must be 16-byte aligned", who);
+  }
   const int dm = r->stage[2].cout;
   if (r->n_heads <= 0 || dm % r->n_heads || dm / r->n_heads > CV_MAX_DH || dm % 8)
     return set_error(MOQE_E_SHAPE, "%s: %d heads on %d channels (head width at most %d, channels a multiple of 8)", who, r->n_heads, dm, CV_MAX_DH);

@@ -116,3 +116,16 @@ def test_label_pass_clamps_targets_and_empty_batch():
                        torch.empty(0, device=gb.DEV), torch.empty(0, dtype=torch.int32, device=gb.DEV),
                        torch.empty(256, dtype=torch.uint8, device=gb.DEV))
     torch.cuda.synchronize()
+
+
+@pytest.mark.timeout(900)
+def test_label_pass_llama_decode_full_size():
+    """The decode workload at its full size (64 sequences x 1 token, 4096 -> 11008 -> 4096, 4 experts): every expert on
+    every sequence, i.e. the grouped launches of the bench with four full buckets."""
+    cfg = wl.get_config("llama7b_mlp_decode")
+    blk = ob.make_block(cfg)
+    bits, x64 = ob.activations_f64(cfg)
+    targets = wl.make_targets(cfg, cfg.D)
+    losses, labels = _label_pass_gpu(cfg, blk, bits, targets)
+    worst, agree = _check(cfg, blk, x64, targets, losses, labels)
+    assert len(set(labels.tolist())) > 1

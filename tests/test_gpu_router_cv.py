@@ -59,3 +59,30 @@ def test_route_cv_matches_oracle(case):
 def test_route_cv_is_deterministic():
     a, b = _run("odd_image"), _run("odd_image")
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.timeout(900)
+def test_route_cv_full_size_conv_workload_shape():
+    """The conv workload's batch shape (256 images of 14 x 14 x 256) with the paper's channels, strides and heads:
+    the library routes all images, the oracle checks a sample of them (its convolutions are Python loops)."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    S, h, w, c_in, mlp, stages, strides, heads, K = 256, 14, 14, 256, (64, 32, 16), (16, 32, 64), (1, 2, 2), 8, 4
+    p = wl.make_cv_router(c_in, mlp, stages, strides, K, 61)
+    bits = wl.make_image_activations(S, h, w, c_in, 62)
+    dev = {k: gb.to_dev(np.ascontiguousarray(v)) for k, v in p.items()}
+    r = mq.CvRouter(dev, c_in, strides, heads, K)
+    x = gb.bf16_dev(bits.reshape(S * h * w, c_in))
+    idx = torch.full((S,), -1, dtype=torch.int32, device=gb.DEV)
+    logits = torch.full((S, K), float("nan"), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_route_cv(x, S, h, w, r, idx, logits)
+    torch.cuda.synchronize()
+    lg, ix = logits.cpu().numpy(), idx.cpu().numpy()
+    assert np.all(np.isfinite(lg)) and np.array_equal(ix, np.argmax(lg, axis=1)) and len(set(ix.tolist())) > 1
+    sample = [0, 1, 63, 64, 127, 200, 254, 255]
+    ref_idx, ref_logits, _ = rc.route_cv(oc.bf16_bits_to_f64(bits[sample]), orc.make(p, 3, strides, heads))
+    tol = 1e-3 * max(1.0, float(np.abs(ref_logits).max()))
+    assert float(np.abs(lg[sample] - ref_logits).max()) <= tol
+    srt = np.sort(ref_logits, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) > 2 * tol
+    assert np.array_equal(ix[sample][clear], ref_idx[clear])

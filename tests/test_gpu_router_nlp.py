@@ -125,3 +125,27 @@ def test_router_model_drives_the_routed_mlp_block():
     keep = ~np.isin(e, a8)
     ok, worst = ob.tolerance_ok(y.cpu().numpy().reshape(cfg.S, cfg.T, cfg.D)[keep], y_ref[keep])
     assert ok, worst
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("S,T", [(64, 1), (16, 512)])
+def test_route_nlp_full_size_workload_shapes(S, T):
+    """The 16 MB router at the decode and prefill batch shapes the bench times (d = 4096): all logits against the oracle."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    d, dm, heads, dff, hh, K = 4096, 384, 6, 1536, 384, 4
+    p = wl.make_nlp_router(d, dm, heads, dff, hh, K, 51)
+    bits = wl.make_token_activations(S, T, d, 52)
+    r = _gpu_router(p, d, dm, heads, dff, hh, K)
+    x = gb.bf16_dev(bits.reshape(S * T, d))
+    idx = torch.full((S,), -1, dtype=torch.int32, device=gb.DEV)
+    logits = torch.full((S, K), float("nan"), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_route_nlp(x, S, T, r, idx, logits)
+    torch.cuda.synchronize()
+    ref_idx, ref_logits, _ = rn.route_nlp(oc.bf16_bits_to_f64(bits), orn.make(p, heads), round_operands=True)
+    tol = 2e-3 * max(1.0, float(np.abs(ref_logits).max()))
+    lg = logits.cpu().numpy()
+    assert float(np.abs(lg - ref_logits).max()) <= tol
+    srt = np.sort(ref_logits, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) > 2 * tol
+    assert np.array_equal(idx.cpu().numpy()[clear], ref_idx[clear]) and clear.mean() >= 0.5

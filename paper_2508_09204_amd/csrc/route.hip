@@ -213,7 +213,8 @@ static void launch_logits_argmax(const float* feat, int nslices, size_t stride, 
 // layer weights sit in LDS, every (sample, expert) dot product belongs to one thread (independent
 // 16-byte LDS reads, no cross-lane reductions), the chosen experts stay in LDS for the bucketing,
 // and results are only stored.
-// Needs S * K <= TAIL_MAX_PAIRS, S * (Dk + 4) <= TAIL_FEAT_FLOATS, S * Dk <= 4096 * TAIL_EPT and
+// Needs S * K <= TAIL_MAX_PAIRS, S * (Dk + 4) <= TAIL_FEAT_FLOATS, S * Dk <= 1024 * TAIL_EPT (256 threads x TAIL_EPT
+// groups of four floats) and
 // K * (Dk + 4) <= TAIL_MAX_W2.
 constexpr int TAIL_EPT = 16;               // float4 feature elements per thread, at most
 constexpr int TAIL_FEAT_FLOATS = 16384 + 4096;
@@ -438,7 +439,7 @@ int32_t launch_route_bucket(const void* x, int S, int T, const moqe_router& r, i
                             int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t st) {
   const int Dk = r.h > 0 ? r.h : r.d;
   if (S > TAIL_MAX_S || S * r.n_experts > TAIL_MAX_PAIRS || size_t(S) * (Dk + 4) > size_t(TAIL_FEAT_FLOATS) ||
-      size_t(S) * Dk > size_t(4096) * TAIL_EPT || r.n_experts * (Dk + 4) > TAIL_MAX_W2) {
+      size_t(S) * Dk > size_t(1024) * TAIL_EPT || r.n_experts * (Dk + 4) > TAIL_MAX_W2) {
     int32_t rc = launch_route(x, S, T, r, idx, logits, ws, st);
     if (rc) return rc;
     return launch_bucket(idx, S, r.n_experts, counts, offsets, perm, inv_perm, st);

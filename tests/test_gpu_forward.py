@@ -237,3 +237,17 @@ def test_forward_replays_from_a_captured_graph():
         call_e(torch.cuda.current_stream().cuda_stream)               # eager work between the replays
         torch.cuda.synchronize()
         assert torch.equal(y_graph, y_eager), rep
+
+
+@pytest.mark.parametrize("S,hidden", [(300, 64), (256, 64), (260, 60), (1000, 16), (40, 500)])
+def test_forward_router_batch_sizes_around_the_fused_tail_limits(S, hidden):
+    """Batches around the capacity of the fused logits + arg-max + bucket work-group (S * hidden floats of features,
+    S * K pairs): routing arrays bit-exact and outputs within tolerance on either side of each limit."""
+    cfg = wl.scaled(wl.get_config("toy_linear"), S=S, T=2, D=128, F=32, router_hidden=hidden)
+    blk = ob.make_block(cfg)
+    bits, x64 = ob.activations_f64(cfg)
+    y_ref, ref_idx, _ = oc.forward(blk, x64)
+    y, aux = _forward_gpu(cfg, blk, bits)
+    _check_routing(cfg, aux, ref_idx)
+    ok, worst = ob.tolerance_ok(y, y_ref)
+    assert ok, worst

@@ -7,7 +7,7 @@
 //   k_lin          C = A W^T + bias [+ residual] [ReLU] on the bf16 matrix cores, fp32 accumulation; A and W
 //                  are bf16, C is written as fp32 and/or bf16
 //   k_attention    softmax(Q K^T / sqrt(dh)) V per (sample, head) in fp32 on the fp32 matrix cores, one wave per
-//                  16 queries, keys streamed in tiles of 16 with a running maximum and sum (no LDS, no barrier)
+//                  32 queries, keys streamed in tiles of 16 with a running maximum and sum (no LDS, no barrier)
 //   k_layer_norm   per row, fp32, biased variance; writes fp32 and/or bf16
 //   k_pool_f32     mean over a sample's tokens, added in token order
 // The MLP head on the pooled vector is the small router of route.hip.
@@ -89,24 +89,25 @@ __global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
     a_src[i] = la.a + size_t(min(m0 + row, la.M - 1)) * la.k + s_unit * 8;    // rows past the end repeat the last row
     w_src[i] = la.w + size_t(n0 + row) * la.k + s_unit * 8;                    // n is a multiple of the tile
   }
-  u32x4 a_reg[4], w_reg[4];
-  auto fetch = [&](int kt) {
+  // two register stages: the loads of k-tile j are issued two iterations before they are written to LDS
+  u32x4 a_reg[2][4], w_reg[2][4];
+  auto fetch = [&](int set, int kt) {
     const int ko = min(kt, KT - 1) * LBK;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      a_reg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + ko);
-      w_reg[i] = *reinterpret_cast<const u32x4*>(w_src[i] + ko);
+      a_reg[set][i] = *reinterpret_cast<const u32x4*>(a_src[i] + ko);
+      w_reg[set][i] = *reinterpret_cast<const u32x4*>(w_src[i] + ko);
     }
   };
-  auto store = [&](int buf) {
+  auto store = [&](int set, int buf) {
     uint8_t* ab = lds + buf * 2 * L_TILE_BYTES;
     uint8_t* wb = ab + L_TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = s_row0 + 32 * i;
       const int off = row * 128 + ((s_unit ^ (row & 7)) * 16);
-      *reinterpret_cast<u32x4*>(ab + off) = a_reg[i];
-      *reinterpret_cast<u32x4*>(wb + off) = w_reg[i];
+      *reinterpret_cast<u32x4*>(ab + off) = a_reg[set][i];
+      *reinterpret_cast<u32x4*>(wb + off) = w_reg[set][i];
     }
   };
   f32x4 acc[4][4];
@@ -115,56 +116,69 @@ __global__ __launch_bounds__(256, 2) void k_lin(const LinArgs la) {
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  fetch(kt0);
-  store(0);
-  fetch(kt0 + 1);
-  __syncthreads();
-  for (int kt = kt0; kt < kt1; ++kt) {
-    const int buf = (kt - kt0) & 1;
+  auto compute = [&](int buf) {
     const uint8_t* ab = lds + buf * 2 * L_TILE_BYTES + (wm * 64 + lr) * 128;
     const uint8_t* wb = lds + buf * 2 * L_TILE_BYTES + L_TILE_BYTES + (wn * 64 + lr) * 128;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int uo = ((j * 4 + lq) ^ (lr & 7)) * 16;        // rows lr + 16 b share lr & 7
-      u32x4 af[4];
-      bf16x8 wf[4];
+      bf16x8 af[4];
+      u32x4 wf[4];
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
-        af[b] = *reinterpret_cast<const u32x4*>(ab + b * 16 * 128 + uo);
-        wf[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(wb + b * 16 * 128 + uo));
+        af[b] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ab + b * 16 * 128 + uo));
+        wf[b] = *reinterpret_cast<const u32x4*>(wb + b * 16 * 128 + uo);
       }
+      // the weights are the FIRST operand: the result block is C^T, a lane then holds four neighbouring columns of one row
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = mfma_bf16(af[mb], wf[nb], acc[mb][nb]);
+        for (int nb = 0; nb < 4; ++nb) acc[mb][nb] = mfma_bf16(wf[nb], af[mb], acc[mb][nb]);
     }
-    store(buf ^ 1);            // k-tile kt + 1; that buffer was last read in iteration kt - 1
-    fetch(kt + 2);
+  };
+  // k-tile kt0 + j: register set j & 1, LDS buffer j & 1
+  fetch(0, kt0);
+  store(0, 0);
+  fetch(1, kt0 + 1);
+  fetch(0, kt0 + 2);
+  __syncthreads();
+  int kt = kt0;
+  for (; kt + 2 <= kt1; kt += 2) {
+    compute(0);
+    store(1, 1);               // k-tile kt + 1; that buffer was last read in the iteration before
+    fetch(1, kt + 3);
+    __syncthreads();
+    compute(1);
+    store(0, 0);               // k-tile kt + 2
+    fetch(0, kt + 4);
     __syncthreads();
   }
-  // ---- epilogue: lane holds column n0 + wn*64 + nb*16 + lr, rows m0 + wm*64 + mb*16 + 4 lq + r
+  if (kt < kt1) compute(0);    // an odd number of k-tiles: the last one sits in buffer 0
+  // ---- epilogue: lane (lr, lq) holds row m0 + wm*64 + mb*16 + lr, columns n0 + wn*64 + nb*16 + 4 lq .. + 3
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb) {
-    const int col = n0 + wn * 64 + nb * 16 + lr;
-    const float bv = la.bias ? la.bias[col] : 0.f;
+  for (int mb = 0; mb < 4; ++mb) {
+    const int row = m0 + wm * 64 + mb * 16 + lr;
+    if (row >= la.M) continue;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int row = m0 + wm * 64 + mb * 16 + 4 * lq + r;
-        if (row < la.M) {
-          const size_t o = size_t(row) * la.n + col;
-          if (la.ksplit > 1) {
-            la.part[size_t(blockIdx.z) * la.M * la.n + o] = acc[mb][nb][r];
-            continue;
-          }
-          float v = acc[mb][nb][r] + bv;
-          if (la.residual) v += la.residual[o];
-          if (la.relu) v = fmaxf(v, 0.f);
-          if (la.c32) la.c32[o] = v;
-          if (la.c16) la.c16[o] = float_to_bf16_rne(v);
-        }
+    for (int nb = 0; nb < 4; ++nb) {
+      const int col = n0 + wn * 64 + nb * 16 + 4 * lq;
+      const size_t o = size_t(row) * la.n + col;
+      float4 v = make_float4(acc[mb][nb][0], acc[mb][nb][1], acc[mb][nb][2], acc[mb][nb][3]);
+      if (la.ksplit > 1) {
+        *reinterpret_cast<float4*>(la.part + size_t(blockIdx.z) * la.M * la.n + o) = v;
+        continue;
       }
+      if (la.bias) { const float4 t = *reinterpret_cast<const float4*>(la.bias + col); v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w; }
+      if (la.residual) { const float4 t = *reinterpret_cast<const float4*>(la.residual + o); v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w; }
+      if (la.relu) { v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f); }
+      if (la.c32) *reinterpret_cast<float4*>(la.c32 + o) = v;
+      if (la.c16) {
+        uint2 h;
+        h.x = pack_bf16x2(v.x, v.y);
+        h.y = pack_bf16x2(v.z, v.w);
+        *reinterpret_cast<uint2*>(la.c16 + o) = h;
+      }
+    }
   }
 }
 
@@ -197,92 +211,123 @@ __global__ __launch_bounds__(256) void k_lin_finish(const LinArgs la) {
 // lanes 16, 32, 48 further on, and the probabilities already sit where the second product wants them.
 // The sum over the head's dimensions and the sum over a tile's keys are order-free, which lets lane group q
 // (= lane / 16) take the contiguous quarter q of a row (dimensions) and the keys 4q .. 4q+3 of a tile.
+// A wave takes QT tiles of 16 queries against the same stream of key tiles (each key / value tile is loaded once per
+// wave and multiplied QT times), and the next key tile's loads are issued before the current tile's arithmetic.
+constexpr int ATT_QT = 1;
+
 template <int DH>
 __global__ __launch_bounds__(256) void k_attention(const float* __restrict__ qkv, uint16_t* __restrict__ out, int S, int T, int dm,
                                                     float scale) {
   constexpr int QS = DH / 4;            // dimensions per lane group = matrix-core steps of the first product
   constexpr int CB = DH / 16;           // 16-column blocks of the output
+  constexpr int QT = ATT_QT;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 15, lq = lane >> 4;
-  const int q0 = (blockIdx.x * 4 + wave) * 16;
+  const int q0 = (blockIdx.x * 4 + wave) * 16 * QT;
   const int head = blockIdx.y, s = blockIdx.z;
   if (q0 >= T) return;                                      // uniform over the wave; the kernel has no barrier
   const size_t ld = size_t(3) * dm;
   const float* base = qkv + size_t(s) * T * ld + head * DH;
-  // queries: lane (lr, lq) holds Q[q0 + lr][lq*QS .. +QS)
-  float qf[QS];
-  {
-    const float* qp = base + size_t(min(q0 + lr, T - 1)) * ld + lq * QS;
+  // queries: lane (lr, lq) holds Q[q0 + 16 t + lr][lq*QS .. +QS) of query tile t
+  float qf[QT][QS];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const float* qp = base + size_t(min(q0 + 16 * t + lr, T - 1)) * ld + lq * QS;
 #pragma unroll
     for (int i = 0; i < QS; i += 4) {
       const float4 v = *reinterpret_cast<const float4*>(qp + i);
-      qf[i] = v.x * scale; qf[i + 1] = v.y * scale; qf[i + 2] = v.z * scale; qf[i + 3] = v.w * scale;
+      qf[t][i] = v.x * scale; qf[t][i + 1] = v.y * scale; qf[t][i + 2] = v.z * scale; qf[t][i + 3] = v.w * scale;
     }
   }
-  f32x4 o[CB];
+  f32x4 o[QT][CB];
+  float m_run[QT], l_run[QT];
 #pragma unroll
-  for (int cb = 0; cb < CB; ++cb) o[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+  for (int t = 0; t < QT; ++t) {
+    m_run[t] = -INFINITY; l_run[t] = 0.f;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) o[t][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // key tile k0: lane (lr, lq) holds K[k0 + lr][lq*QS .. +QS) and V[k0 + 4 lq + r][16 cb + lr]; rows past T repeat row T - 1
+  float kf[QS], vf[4][CB];
+  auto load_tile = [&](int k0) {
+    const float* kp = base + dm + size_t(min(k0 + lr, T - 1)) * ld + lq * QS;
+#pragma unroll
+    for (int i = 0; i < QS; i += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(kp + i);
+      kf[i] = v.x; kf[i + 1] = v.y; kf[i + 2] = v.z; kf[i + 3] = v.w;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float* vp = base + 2 * dm + size_t(min(k0 + 4 * lq + r, T - 1)) * ld + lr;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) vf[r][cb] = vp[cb * 16];
+    }
+  };
+  load_tile(0);
   for (int k0 = 0; k0 < T; k0 += 16) {
-    // ---- scores^T[key][query] for keys k0 .. k0+15
-    f32x4 sc = {0.f, 0.f, 0.f, 0.f};
-    {
-      const float* kp = base + dm + size_t(min(k0 + lr, T - 1)) * ld + lq * QS;
-      float kf[QS];
+    float kc[QS], vc[4][CB];
 #pragma unroll
-      for (int i = 0; i < QS; i += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(kp + i);
-        kf[i] = v.x; kf[i + 1] = v.y; kf[i + 2] = v.z; kf[i + 3] = v.w;
+    for (int i = 0; i < QS; ++i) kc[i] = kf[i];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) vc[r][cb] = vf[r][cb];
+    load_tile(k0 + 16);                                     // clamped rows: valid addresses also past the last tile
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      if (q0 + 16 * t >= T) continue;                       // uniform: this query tile does not exist
+      // ---- scores^T[key][query] for keys k0 .. k0+15
+      f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < QS; ++i) sc = __builtin_amdgcn_mfma_f32_16x16x4f32(kc[i], qf[t][i], sc, 0, 0, 0);
+      // lane (lr, lq) now holds the scores of query q0 + 16 t + lr against keys k0 + 4 lq + r
+      float p[4];
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const bool live = k0 + 4 * lq + r < T;
+        p[r] = live ? sc[r] : -INFINITY;
+        tmax = fmaxf(tmax, p[r]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m_run[t], tmax);            // finite: key k0 itself is live
+      const float alpha = __expf(m_run[t] - m_new);         // exp(-inf) = 0 on the first tile
+      float tsum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        p[r] = __expf(p[r] - m_new);
+        tsum += p[r];
+      }
+      tsum += __shfl_xor(tsum, 16);
+      tsum += __shfl_xor(tsum, 32);
+      l_run[t] = l_run[t] * alpha + tsum;
+      m_run[t] = m_new;
+      // ---- out^T[c][query] += V^T P^T: step r multiplies the keys k0 + 4 kk + r (kk = lane group) of the tile
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[t][cb][r] *= alpha;
       }
 #pragma unroll
-      for (int i = 0; i < QS; ++i) sc = __builtin_amdgcn_mfma_f32_16x16x4f32(kf[i], qf[i], sc, 0, 0, 0);
-    }
-    // lane (lr, lq) now holds the scores of query q0 + lr against keys k0 + 4 lq + r
-    float p[4];
-    float tmax = -INFINITY;
+      for (int r = 0; r < 4; ++r)                           // dead keys have p = 0
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const bool live = k0 + 4 * lq + r < T;
-      p[r] = live ? sc[r] : -INFINITY;
-      tmax = fmaxf(tmax, p[r]);
-    }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-    const float m_new = fmaxf(m_run, tmax);                 // finite: key k0 itself is live
-    const float alpha = __expf(m_run - m_new);              // exp(-inf) = 0 on the first tile
-    float tsum = 0.f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      p[r] = __expf(p[r] - m_new);
-      tsum += p[r];
-    }
-    tsum += __shfl_xor(tsum, 16);
-    tsum += __shfl_xor(tsum, 32);
-    l_run = l_run * alpha + tsum;
-    m_run = m_new;
-    // ---- out^T[c][query] += V^T P^T: step r multiplies the keys k0 + 4 kk + r (kk = lane group) of the tile
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-#pragma unroll
-      for (int r = 0; r < 4; ++r) o[cb][r] *= alpha;
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float* vp = base + 2 * dm + size_t(min(k0 + 4 * lq + r, T - 1)) * ld + lr;   // dead keys have p = 0
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) o[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(vp[cb * 16], p[r], o[cb], 0, 0, 0);
+        for (int cb = 0; cb < CB; ++cb) o[t][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(vc[r][cb], p[r], o[t][cb], 0, 0, 0);
     }
   }
-  // lane (lr, lq) holds out[q0 + lr][16 cb + 4 lq + r]
-  if (q0 + lr < T) {
-    const float inv = 1.f / l_run;
-    uint16_t* op = out + (size_t(s) * T + q0 + lr) * dm + head * DH + 4 * lq;
+  // lane (lr, lq) holds out[q0 + 16 t + lr][16 cb + 4 lq + r]
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-      uint2 v;
-      v.x = pack_bf16x2(o[cb][0] * inv, o[cb][1] * inv);
-      v.y = pack_bf16x2(o[cb][2] * inv, o[cb][3] * inv);
-      *reinterpret_cast<uint2*>(op + cb * 16) = v;
+  for (int t = 0; t < QT; ++t) {
+    if (q0 + 16 * t + lr < T) {
+      const float inv = 1.f / l_run[t];
+      uint16_t* op = out + (size_t(s) * T + q0 + 16 * t + lr) * dm + head * DH + 4 * lq;
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+        uint2 v;
+        v.x = pack_bf16x2(o[t][cb][0] * inv, o[t][cb][1] * inv);
+        v.y = pack_bf16x2(o[t][cb][2] * inv, o[t][cb][3] * inv);
+        *reinterpret_cast<uint2*>(op + cb * 16) = v;
+      }
     }
   }
 }
@@ -403,7 +448,7 @@ int32_t lin(const uint16_t* a, const uint16_t* w, const float* bias, const float
 int32_t attention(const float* qkv, uint16_t* out, int S, int T, int dm, int heads, hipStream_t st) {
   const int dh = dm / heads;
   const float scale = 1.0f / sqrtf(float(dh));
-  const dim3 grid((T + 63) / 64, heads, S);
+  const dim3 grid((T + 64 * ATT_QT - 1) / (64 * ATT_QT), heads, S);
   ProfileScope ps(MOQE_PK_ROUTE, st);
   switch (dh) {
     case 16:  hipLaunchKernelGGL(k_attention<16>, grid, dim3(256), 0, st, qkv, out, S, T, dm, scale); break;
@@ -430,6 +475,9 @@ int32_t check_nlp_router(const moqe_nlp_router* r, const char* who) {
   const void* mats[] = {r->w_in, r->wqkv1, r->wo1, r->w_ff1, r->w_ff2, r->wqkv2, r->wo2};
   for (const void* p : mats)
     if (reinterpret_cast<uintptr_t>(p) % 16) return set_error(MOQE_E_SHAPE, "%s: parameter matrices must be 16-byte aligned", who);
+  const void* vecs[] = {r->b_in, r->bqkv1, r->bo1, r->b_ff1, r->b_ff2, r->bqkv2, r->bo2};
+  for (const void* p : vecs)
+    if (reinterpret_cast<uintptr_t>(p) % 16) return set_error(MOQE_E_SHAPE, "%s: bias vectors must be 16-byte aligned", who);
   if (r->d <= 0 || r->d % 64 || r->dm <= 0 || r->dm % 128 || r->dm > 64 * LN_MAX_PER_LANE || r->d_ff <= 0 || r->d_ff % 128)
     return set_error(MOQE_E_SHAPE, "%s: d=%d must be a multiple of 64, dm=%d and d_ff=%d multiples of 128, dm <= %d", who, r->d,
                      r->dm, r->d_ff, 64 * LN_MAX_PER_LANE);

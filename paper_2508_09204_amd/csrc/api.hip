@@ -172,9 +172,22 @@ static GemmPath choose_path(long long M, int T) {
 }
 
 // Enqueues one grouped GEMM (plus the int8 row quantization its act_mode-1 experts need).
+// A launch of at most 64 samples that can bucket them itself (see GemmArgs::expert_idx).
+struct SelfBucket {
+  const int32_t* expert_idx;
+  int32_t *counts, *offsets, *perm, *inv_perm;
+};
+
+// True when run_grouped(..., &SelfBucket) is possible for this launch: the register-resident streaming kernel alone
+// takes it, and no expert needs its rows quantized (that step reads the bucket arrays before the launch).
+static bool can_self_bucket(int S, int T, int k, const GroupedPlan& gp) {
+  return S <= 64 && !gp.any_a8 && choose_path((long long)S * T, T) == PATH_STREAM && k / 128 <= STREAM_REG_MAX_KT;
+}
+
 static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t* a_perm, const int32_t* y_perm, int S, int T,
                            const moqe_qmat* experts, const moqe_qmat* second, int K, const GroupedPlan& gp, void* y,
-                           uint8_t* a8_ws, hipStream_t st, int conv_h = 0, int conv_w = 0, int conv_c = 0, bool y_bf16 = false) {
+                           uint8_t* a8_ws, hipStream_t st, int conv_h = 0, int conv_w = 0, int conv_c = 0, bool y_bf16 = false,
+                           const SelfBucket* sb = nullptr) {
   // conv_c > 0: a is the NHWC image and the tiled kernel gathers the 3x3 neighbourhoods itself
   GemmArgs ga;
   memset(&ga, 0, sizeof(ga));
@@ -184,6 +197,10 @@ static int32_t run_grouped(const void* a, const int32_t* offsets, const int32_t*
   ga.a = a; ga.offsets = offsets; ga.a_perm = a_perm; ga.y_perm = y_perm; ga.y = y;
   ga.conv_h = conv_h; ga.conv_w = conv_w; ga.conv_c = conv_c;
   ga.y_bf16 = (y_bf16 && !second) ? 1 : 0;
+  if (sb) {
+    ga.expert_idx = sb->expert_idx;
+    ga.out_counts = sb->counts; ga.out_offsets = sb->offsets; ga.out_perm = sb->perm; ga.out_inv_perm = sb->inv_perm;
+  }
   for (int e = 0; e < K; ++e) fill_expert(experts[e], second ? &second[e] : nullptr, gp.pi[e], &ga.ex[e]);
   const int M = S * T;
   if (gp.any_a8) {
@@ -581,16 +598,23 @@ int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T,
     if (aux->inv_perm) inv_perm = aux->inv_perm;
   }
 
-  rc = launch_route_bucket(x, S, T, blk->router, idx, (aux && aux->logits) ? logits : nullptr, counts, offsets, perm,
-                           (aux && aux->inv_perm) ? inv_perm : nullptr, ws + L.route, st);
+  // Small batches whose first grouped launch is the streaming kernel: that launch buckets the samples itself, which takes
+  // the bucket kernel (and one dependent read of its result) out of the chain router -> experts.
+  const bool self = blk->kind != MOQE_KIND_CONV3X3 && can_self_bucket(S, T, blk->w0[0].k, g0);
+  float* want_logits = (aux && aux->logits) ? logits : nullptr;
+  int32_t* want_inv = (aux && aux->inv_perm) ? inv_perm : nullptr;
+  if (self) rc = launch_route(x, S, T, blk->router, idx, want_logits, ws + L.route, st);
+  else rc = launch_route_bucket(x, S, T, blk->router, idx, want_logits, counts, offsets, perm, want_inv, ws + L.route, st);
   if (rc) return rc;
+  const SelfBucket sb{idx, counts, offsets, perm, want_inv};
+  const SelfBucket* psb = self ? &sb : nullptr;
 
   if (blk->kind == MOQE_KIND_LINEAR) {
-    return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st);
+    return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, 0, 0, 0, false, psb);
   }
   if (blk->kind == MOQE_KIND_SILU_MLP) {
     void* h = (aux && aux->h) ? aux->h : static_cast<void*>(ws + L.h);
-    rc = run_grouped(x, offsets, perm, nullptr, S, T, blk->w0, blk->w1, K, g0, h, ws + L.a8, st);
+    rc = run_grouped(x, offsets, perm, nullptr, S, T, blk->w0, blk->w1, K, g0, h, ws + L.a8, st, 0, 0, 0, false, psb);
     if (rc) return rc;
     return run_grouped(h, offsets, nullptr, perm, S, T, blk->w2, nullptr, K, g2, y, ws + L.a8, st);
   }

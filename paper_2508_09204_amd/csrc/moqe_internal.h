@@ -164,6 +164,11 @@ struct GemmArgs {
   int32_t   conv_h, conv_w, conv_c;   // tiled kernel, 3x3 convolution: a is the NHWC image [S, h, w, c] and the
                              // k = (kh*3 + kw)*c + ch columns of a row are gathered from its pixel's neighbours
   int32_t   min_rows, max_rows;   // this launch handles the experts whose bucket has min_rows .. max_rows rows
+  // Streaming kernel, at most 64 samples: the launch buckets the samples itself from the router's choice (every
+  // work-group works the same stable counting sort out in registers) instead of reading offsets and perm, and its first
+  // work-group writes counts / offsets / perm / inv_perm (any may be NULL) for whatever runs after it.
+  const int32_t* expert_idx;      // [S] or NULL: offsets and perm come from memory
+  int32_t*  out_counts; int32_t* out_offsets; int32_t* out_perm; int32_t* out_inv_perm;
 };
 
 // ---------------------------------------------------------------------------------------

@@ -37,7 +37,8 @@ static_assert(MAX_KT == STREAM_REG_MAX_KT, "the launcher's limit is what the wav
 constexpr int STREAM_ROWS = 32;            // bucket rows per pass (two 16-row blocks)
 constexpr int BMT = 4;                     // (tile rows per batch) x (16-row blocks): results exchanged per barrier
 constexpr int PART_BYTES = 2 * BMT * SW * 64 * 16;     // two buffers of per-wave partial sums
-constexpr int STREAM_LDS_BYTES = PART_BYTES;
+constexpr int PERM_LDS_BYTES = SW * 64 * 4;           // a private copy of the permutation per wave (launches that bucket themselves)
+constexpr int STREAM_LDS_BYTES = PART_BYTES + PERM_LDS_BYTES;
 
 // ---- which expert and which of its weight tiles a work-group streams ---------------------------------
 struct StreamSeg {
@@ -68,11 +69,44 @@ static __device__ __forceinline__ uint32_t uni(uint32_t v) { return uint32_t(__b
 // Lane e (of every 16-lane row) fetches bucket e's bounds and expert e's descriptor, all in one round trip:
 // the kernel arguments live in memory that is slow to touch for the first time, and a chain of dependent
 // reads there would cost microseconds before the first weight is requested.
-static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, const int wg, const int G) {
+static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, const int wg, const int G, int32_t* perm_l) {
   const int K = ga.n_experts, NU = ga.n >> 4;
   const int e = threadIdx.x & 15;
   const int el_safe = e < K ? e : 0;
-  const int o0 = ga.offsets[el_safe], o1 = ga.offsets[el_safe + 1];
+  int o0, o1;
+  if (ga.expert_idx) {
+    // Stable counting sort of at most 64 samples, a sample per lane: the count of expert k is the population of the ballot
+    // "my sample goes to k", a sample's place in its bucket the population below its lane (the bucket kernel's arithmetic).
+    const int L = threadIdx.x & 63;
+    int es = L < ga.S ? ga.expert_idx[L] : -1;
+    if (es >= K) es = -1;
+    const unsigned long long below = L == 0 ? 0ull : (~0ull >> (64 - L));
+    int base = 0, my_pos = 0;
+    o0 = 0; o1 = 0;
+    for (int k = 0; k < K; ++k) {
+      const unsigned long long b = __ballot(es == k);
+      const int c = __popcll(b);
+      if (es == k) my_pos = base + __popcll(b & below);
+      if (e == k) { o0 = base; o1 = base + c; }
+      base += c;
+    }
+    if (es >= 0) perm_l[my_pos] = L;                    // this wave's own copy: read back by the same wave only
+    __builtin_amdgcn_wave_barrier();
+    if (wg == 0 && threadIdx.x < 64) {                  // first wave of the first work-group publishes the result
+      if (L < K) {
+        if (ga.out_counts) ga.out_counts[L] = o1 - o0;
+        if (ga.out_offsets) ga.out_offsets[L] = o0;
+      }
+      if (L == 0 && ga.out_offsets) ga.out_offsets[K] = base;
+      if (es >= 0) {
+        if (ga.out_perm) ga.out_perm[my_pos] = L;
+        if (ga.out_inv_perm) ga.out_inv_perm[L] = my_pos;
+      }
+    }
+  } else {
+    o0 = ga.offsets[el_safe];
+    o1 = ga.offsets[el_safe + 1];
+  }
   const ExpertDev mine_ex = ga.ex[el_safe];                        // per-lane copy (vector loads from the argument block)
   const int rows = e < K ? (o1 - o0) * ga.T : 0;
   const bool mine = rows >= ga.min_rows && rows <= ga.max_rows && rows > 0;
@@ -155,7 +189,8 @@ template <typename V> static __device__ __forceinline__ V pick4(int q, V a, V b,
 // One pass (at most 32 bucket rows, MT blocks of 16) of one expert's weight tiles [u0, u1).
 template <int FMT, int GM, bool GATEUP, int MT>
 static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const ExpertDev& ex, const int off_e, const int u0,
-                                                   const int u1, const int pass0, const int rows_here, uint8_t* lds) {
+                                                   const int u1, const int pass0, const int rows_here, uint8_t* lds,
+                                                   const int32_t* perm_l) {
   constexpr bool A8 = (FMT == FMT_I8A8);
   constexpr int NR = Raw<FMT>::N;
   constexpr int GPT = GM == GM_PC ? 0 : (GM == GM_G128 ? 1 : 2);
@@ -197,7 +232,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   for (int mt = 0; mt < MT; ++mt) {
     a_m[mt] = pass0 + min(mt * 16 + lr, rows_here - 1);
     a_src[mt] = off_e + a_m[mt] / T;
-    if (!A8 && ga.a_perm) a_src[mt] = ga.a_perm[a_src[mt]];
+    if (!A8 && ga.a_perm) a_src[mt] = perm_l ? perm_l[a_src[mt]] : ga.a_perm[a_src[mt]];
   }
   int out_row[MT][4];           // destination row of each result register
   float sx[MT][4];              // W8A8: activation scale of each result row
@@ -208,7 +243,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
       const int m = pass0 + min(mt * 16 + lq * 4 + r, rows_here - 1);
       const int brow = off_e * T + m;
       int dsmp = off_e + m / T;
-      if (!GATEUP && ga.y_perm) dsmp = ga.y_perm[dsmp];
+      if (!GATEUP && ga.y_perm) dsmp = perm_l ? perm_l[dsmp] : ga.y_perm[dsmp];
       out_row[mt][r] = dsmp;                                       // turned into a row index after the ring's first row
       sx[mt][r] = 1.f;
       if constexpr (A8) sx[mt][r] = ga.a_scale[brow];
@@ -554,30 +589,32 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
 }
 
 template <int FMT, int GM, bool GATEUP>
-static __device__ __forceinline__ void stream_expert(const GemmArgs& ga, const StreamSeg& sg, uint8_t* lds) {
+static __device__ __forceinline__ void stream_expert(const GemmArgs& ga, const StreamSeg& sg, uint8_t* lds, const int32_t* perm_l) {
   for (int pass0 = 0; pass0 < sg.rows_e; pass0 += STREAM_ROWS) {
     const int rows_here = min(STREAM_ROWS, sg.rows_e - pass0);
-    if (rows_here <= 16) stream_pass<FMT, GM, GATEUP, 1>(ga, sg.ex, sg.off_e, sg.u0, sg.u1, pass0, rows_here, lds);
-    else stream_pass<FMT, GM, GATEUP, 2>(ga, sg.ex, sg.off_e, sg.u0, sg.u1, pass0, rows_here, lds);
+    if (rows_here <= 16) stream_pass<FMT, GM, GATEUP, 1>(ga, sg.ex, sg.off_e, sg.u0, sg.u1, pass0, rows_here, lds, perm_l);
+    else stream_pass<FMT, GM, GATEUP, 2>(ga, sg.ex, sg.off_e, sg.u0, sg.u1, pass0, rows_here, lds, perm_l);
   }
 }
 
 template <bool GATEUP>
 __global__ __launch_bounds__(SW * 64, 2) void k_qgemm_stream(const GemmArgs ga) {
   extern __shared__ __align__(16) uint8_t lds[];
-  StreamSeg sg = stream_schedule(ga, int(blockIdx.x), int(gridDim.x));
+  // the permutation of a launch that buckets itself: one copy per wave behind the partial-sum buffers
+  int32_t* perm_l = ga.expert_idx ? reinterpret_cast<int32_t*>(lds + PART_BYTES) + (threadIdx.x >> 6) * 64 : nullptr;
+  StreamSeg sg = stream_schedule(ga, int(blockIdx.x), int(gridDim.x), perm_l);
   if (sg.e < 0 || sg.u1 <= sg.u0) return;             // uniform over the work-group
   sg.u0 = __builtin_amdgcn_readfirstlane(sg.u0); sg.u1 = __builtin_amdgcn_readfirstlane(sg.u1);
   sg.off_e = __builtin_amdgcn_readfirstlane(sg.off_e); sg.rows_e = __builtin_amdgcn_readfirstlane(sg.rows_e);
   switch (sg.ex.fmt * 4 + sg.ex.gm) {
-    case FMT_I8 * 4 + GM_PC:     stream_expert<FMT_I8, GM_PC, GATEUP>(ga, sg, lds); break;
-    case FMT_I8A8 * 4 + GM_PC:   stream_expert<FMT_I8A8, GM_PC, GATEUP>(ga, sg, lds); break;
-    case FMT_N6 * 4 + GM_PC:     stream_expert<FMT_N6, GM_PC, GATEUP>(ga, sg, lds); break;
-    case FMT_N4 * 4 + GM_PC:     stream_expert<FMT_N4, GM_PC, GATEUP>(ga, sg, lds); break;
-    case FMT_N4 * 4 + GM_G128:   stream_expert<FMT_N4, GM_G128, GATEUP>(ga, sg, lds); break;
-    case FMT_N4 * 4 + GM_G64:    stream_expert<FMT_N4, GM_G64, GATEUP>(ga, sg, lds); break;
-    case FMT_N3 * 4 + GM_G128:   stream_expert<FMT_N3, GM_G128, GATEUP>(ga, sg, lds); break;
-    case FMT_N3 * 4 + GM_G64:    stream_expert<FMT_N3, GM_G64, GATEUP>(ga, sg, lds); break;
+    case FMT_I8 * 4 + GM_PC:     stream_expert<FMT_I8, GM_PC, GATEUP>(ga, sg, lds, perm_l); break;
+    case FMT_I8A8 * 4 + GM_PC:   stream_expert<FMT_I8A8, GM_PC, GATEUP>(ga, sg, lds, perm_l); break;
+    case FMT_N6 * 4 + GM_PC:     stream_expert<FMT_N6, GM_PC, GATEUP>(ga, sg, lds, perm_l); break;
+    case FMT_N4 * 4 + GM_PC:     stream_expert<FMT_N4, GM_PC, GATEUP>(ga, sg, lds, perm_l); break;
+    case FMT_N4 * 4 + GM_G128:   stream_expert<FMT_N4, GM_G128, GATEUP>(ga, sg, lds, perm_l); break;
+    case FMT_N4 * 4 + GM_G64:    stream_expert<FMT_N4, GM_G64, GATEUP>(ga, sg, lds, perm_l); break;
+    case FMT_N3 * 4 + GM_G128:   stream_expert<FMT_N3, GM_G128, GATEUP>(ga, sg, lds, perm_l); break;
+    case FMT_N3 * 4 + GM_G64:    stream_expert<FMT_N3, GM_G64, GATEUP>(ga, sg, lds, perm_l); break;
     default: break;
   }
 }

@@ -240,7 +240,8 @@ int32_t moqe_balance_stats(const float* logits, const int32_t* counts, int32_t S
  * Arithmetic: the matrix products of the token stages multiply bf16 operands (x as given; parameters and the
  * activations between stages rounded to bf16, nearest even) on the matrix cores with fp32 accumulation;
  * softmax, LayerNorm, residual sums, the mean over the tokens and the MLP head are fp32.  All sums run in a
- * fixed order (deterministic).  About 16 launches on `stream`; workspace as the query says, 256-byte aligned.
+ * fixed order (deterministic).  About 16 launches on `stream` (23 for batches of at most 512 rows, whose products
+ * are split along k); workspace as the query says, 256-byte aligned.  At most 65535 samples and 8388480 rows per call.
  * S == 0 is a no-op. */
 size_t moqe_route_nlp_workspace_bytes(int32_t S, int32_t T, const moqe_nlp_router* r);
 int32_t moqe_route_nlp(const void* x, int32_t S, int32_t T, const moqe_nlp_router* r,

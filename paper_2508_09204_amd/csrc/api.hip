@@ -288,7 +288,8 @@ int32_t moqe_route_nlp(const void* x, int32_t S, int32_t T, const moqe_nlp_route
   if (S == 0) return MOQE_OK;
   if (!x || !expert_idx) return set_error(MOQE_E_NULL, "moqe_route_nlp: x or expert_idx is NULL");
   if (!aligned(x, 16)) return set_error(MOQE_E_SHAPE, "moqe_route_nlp: x must be 16-byte aligned");
-  if (S > 65535) return set_error(MOQE_E_SHAPE, "moqe_route_nlp: at most 65535 samples per call");
+  if (S > 65535 || (long long)S * T > 65535LL * 128)
+    return set_error(MOQE_E_SHAPE, "moqe_route_nlp: at most 65535 samples and 8388480 token rows per call");
   const size_t need = route_nlp_ws_bytes(S, T, *r);
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < need)
     return set_error(MOQE_E_WORKSPACE, "moqe_route_nlp: workspace needs %zu bytes, 256-byte aligned", need);

@@ -335,6 +335,14 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
 int32_t moqe_forward_static(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y,
                             const moqe_aux* aux, void* stream);
 
+/* The block on experts that the caller has chosen: as moqe_forward, but the samples' experts come from
+ * expert_idx (device int32 [S], values in [0, n_experts); e.g. the output of moqe_route_nlp or moqe_route_cv,
+ * the router models of Section 3.2) and the block's own router is neither checked nor run.  aux->expert_idx and
+ * aux->logits are not written; the other aux members as in moqe_forward. */
+size_t  moqe_workspace_bytes_routed(const moqe_block* blk, int32_t S, int32_t T);
+int32_t moqe_forward_routed(const moqe_block* blk, const int32_t* expert_idx, const void* x, int32_t S, int32_t T,
+                            void* y, const moqe_aux* aux, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- samples of different lengths ---------------------------------------------------- */
 
 /* The same path for samples that do not all have T rows (sequences of different lengths): x is device

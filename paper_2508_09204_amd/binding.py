@@ -107,6 +107,8 @@ def _load() -> C.CDLL:
         "moqe_grouped_qgemm": (i32, [vp, vp, vp, i32, i32, C.POINTER(_QMat), i32, vp, i32, vp, sz, vp]),
         "moqe_workspace_bytes": (sz, [C.POINTER(_Block), i32, i32]),
         "moqe_forward": (i32, [C.POINTER(_Block), vp, i32, i32, vp, C.POINTER(_Aux), vp, sz, vp]),
+        "moqe_workspace_bytes_routed": (sz, [C.POINTER(_Block), i32, i32]),
+        "moqe_forward_routed": (i32, [C.POINTER(_Block), vp, vp, i32, i32, vp, C.POINTER(_Aux), vp, sz, vp]),
         "moqe_forward_static": (i32, [C.POINTER(_Block), vp, i32, i32, vp, C.POINTER(_Aux), vp]),
         "moqe_label_pass_workspace_bytes": (sz, [C.POINTER(_Block), i32, i32]),
         "moqe_label_pass": (i32, [C.POINTER(_Block), vp, vp, i32, i32, vp, vp, vp, sz, vp]),
@@ -133,7 +135,7 @@ EXPORTED = ["moqe_version", "moqe_last_error_string", "moqe_set_dry_run", "moqe_
             "moqe_route", "moqe_route_nlp_workspace_bytes", "moqe_route_nlp", "moqe_route_cv_workspace_bytes", "moqe_route_cv", "moqe_bucket", "moqe_balance_stats", "moqe_route_ragged_workspace_bytes", "moqe_route_ragged",
             "moqe_expand_rows", "moqe_workspace_bytes_ragged", "moqe_forward_ragged", "moqe_quantize_rtn", "moqe_packed_bytes", "moqe_pack_qmat",
             "moqe_unpack_qmat", "moqe_grouped_qgemm_workspace_bytes", "moqe_grouped_qgemm",
-            "moqe_workspace_bytes", "moqe_forward", "moqe_forward_static", "moqe_label_pass_workspace_bytes", "moqe_label_pass", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
+            "moqe_workspace_bytes", "moqe_forward", "moqe_forward_static", "moqe_workspace_bytes_routed", "moqe_forward_routed", "moqe_label_pass_workspace_bytes", "moqe_label_pass", "moqe_cache_create", "moqe_cache_destroy", "moqe_cache_acquire",
             "moqe_cache_stats", "moqe_profile_enable", "moqe_profile_read"]
 
 
@@ -440,6 +442,17 @@ def moqe_label_pass(blk: Block, x: torch.Tensor, targets: torch.Tensor, S: int, 
         workspace = _workspace(lib.moqe_label_pass_workspace_bytes(C.byref(b), S, T), x.device)
     _check(lib.moqe_label_pass(C.byref(b), _ptr(x), _ptr(targets), S, T, _ptr(losses), _ptr(labels),
                                _ptr(workspace), workspace.numel(), _stream()))
+
+
+def moqe_forward_routed(blk: Block, expert_idx: torch.Tensor, x: torch.Tensor, S: int, T: int, y: torch.Tensor,
+                        aux: Optional[Aux] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    """The block on experts chosen by the caller (e.g. by moqe_route_nlp or moqe_route_cv)."""
+    b = blk.c()
+    if workspace is None:
+        workspace = _workspace(lib.moqe_workspace_bytes_routed(C.byref(b), S, T), x.device)
+    a = aux.c() if aux is not None else None
+    _check(lib.moqe_forward_routed(C.byref(b), _ptr(expert_idx), _ptr(x), S, T, _ptr(y),
+                                   C.byref(a) if a is not None else None, _ptr(workspace), workspace.numel(), _stream()))
 
 
 STATIC_SCRATCH_BYTES = 16 << 20

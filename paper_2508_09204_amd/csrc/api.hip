@@ -443,12 +443,18 @@ struct FwdLayout {
   size_t route, idx, logits, counts, offsets, perm, inv_perm, h, a8, total;
 };
 
-int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedPlan* gp0, GroupedPlan* gp2) {
+// routed: the caller brings the experts' indices; the block's own router is neither checked nor used
+int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedPlan* gp0, GroupedPlan* gp2, bool routed = false) {
   if (!b) return set_error(MOQE_E_NULL, "moqe_forward: block is NULL");
-  int32_t rc = check_router(&b->router, "moqe_forward");
-  if (rc) return rc;
+  int32_t rc;
   const int K = b->n_experts;
-  if (K != b->router.n_experts) return set_error(MOQE_E_SHAPE, "moqe_forward: block has %d experts, router %d", K, b->router.n_experts);
+  if (routed) {
+    if (K < 1 || K > MOQE_MAX_EXPERTS) return set_error(MOQE_E_SHAPE, "moqe_forward_routed: n_experts=%d outside [1, %d]", K, MOQE_MAX_EXPERTS);
+  } else {
+    rc = check_router(&b->router, "moqe_forward");
+    if (rc) return rc;
+    if (K != b->router.n_experts) return set_error(MOQE_E_SHAPE, "moqe_forward: block has %d experts, router %d", K, b->router.n_experts);
+  }
   if (S < 0 || T <= 0 || (long long)S * T > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_forward: S=%d T=%d", S, T);
   if (!b->w0) return set_error(MOQE_E_NULL, "moqe_forward: w0 is NULL");
   if (b->kind == MOQE_KIND_SILU_MLP) {
@@ -457,17 +463,17 @@ int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedP
     if (rc) return rc;
     rc = plan_experts(b->w2, K, nullptr, gp2, "moqe_forward(down)");
     if (rc) return rc;
-    if (b->w0[0].k != b->router.d || b->w2[0].k != b->w0[0].n || b->w2[0].n != b->w0[0].k)
+    if ((!routed && b->w0[0].k != b->router.d) || b->w2[0].k != b->w0[0].n || b->w2[0].n != b->w0[0].k)
       return set_error(MOQE_E_SHAPE, "moqe_forward: MLP shapes do not chain (d=%d, gate %dx%d, down %dx%d)", b->router.d,
                        b->w0[0].n, b->w0[0].k, b->w2[0].n, b->w2[0].k);
   } else if (b->kind == MOQE_KIND_LINEAR) {
     rc = plan_experts(b->w0, K, nullptr, gp0, "moqe_forward(linear)");
     if (rc) return rc;
-    if (b->w0[0].k != b->router.d) return set_error(MOQE_E_SHAPE, "moqe_forward: linear k=%d but router d=%d", b->w0[0].k, b->router.d);
+    if (!routed && b->w0[0].k != b->router.d) return set_error(MOQE_E_SHAPE, "moqe_forward: linear k=%d but router d=%d", b->w0[0].k, b->router.d);
   } else if (b->kind == MOQE_KIND_CONV3X3) {
     rc = plan_experts(b->w0, K, nullptr, gp0, "moqe_forward(conv)");
     if (rc) return rc;
-    if (b->img_h <= 0 || b->img_w <= 0 || b->cin <= 0 || b->img_h * b->img_w != T || b->cin != b->router.d ||
+    if (b->img_h <= 0 || b->img_w <= 0 || b->cin <= 0 || b->img_h * b->img_w != T || (!routed && b->cin != b->router.d) ||
         b->w0[0].k != b->cin * 9 || (b->cin % 8) != 0)
       return set_error(MOQE_E_SHAPE, "moqe_forward: conv needs T = img_h*img_w, cin = router d (a multiple of 8), k = 9*cin");
     if (gp0->any_a8) return set_error(MOQE_E_FORMAT, "moqe_forward: conv experts take bf16 activations (act_mode 0)");
@@ -476,14 +482,14 @@ int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedP
   }
   const size_t M = size_t(S) * T;
   // every activation matrix a kernel indexes: x itself, and the bf16 intermediate of the MLP
-  rc = check_activation_bytes((long long)M, b->router.d, "moqe_forward");
+  rc = check_activation_bytes((long long)M, b->kind == MOQE_KIND_CONV3X3 ? b->cin : b->w0[0].k, "moqe_forward");
   if (rc) return rc;
   if (b->kind == MOQE_KIND_SILU_MLP) {
     rc = check_activation_bytes((long long)M, b->w0[0].n, "moqe_forward");
     if (rc) return rc;
   }
   size_t o = 0;
-  L->route = o;    o += align256(route_ws_bytes(S, T, b->router));
+  L->route = o;    o += routed ? 0 : align256(route_ws_bytes(S, T, b->router));
   L->idx = o;      o += align256(size_t(S) * 4);
   L->logits = o;   o += align256(size_t(S) * K * 4);
   L->counts = o;   o += align256(size_t(K) * 4);
@@ -539,7 +545,8 @@ int32_t static_scratch(void** out) {
 }
 
 int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
-                     const FwdLayout& L, const GroupedPlan& g0, const GroupedPlan& g2, void* workspace, void* stream);
+                     const FwdLayout& L, const GroupedPlan& g0, const GroupedPlan& g2, void* workspace, void* stream,
+                     const int32_t* given_idx = nullptr);
 }  // namespace
 
 int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
@@ -555,6 +562,28 @@ int32_t moqe_forward(const moqe_block* blk, const void* x, int32_t S, int32_t T,
     return set_error(MOQE_E_WORKSPACE, "moqe_forward: workspace needs %zu bytes, 256-byte aligned", L.total);
   if (dry_run()) return MOQE_OK;
   return forward_body(blk, x, S, T, y, aux, L, g0, g2, workspace, stream);
+}
+
+int32_t moqe_forward_routed(const moqe_block* blk, const int32_t* expert_idx, const void* x, int32_t S, int32_t T, void* y,
+                            const moqe_aux* aux, void* workspace, size_t workspace_bytes, void* stream) {
+  FwdLayout L;
+  GroupedPlan g0, g2;
+  int32_t rc = forward_layout(blk, S, T, &L, &g0, &g2, true);
+  if (rc) return rc;
+  if (S == 0) return MOQE_OK;
+  if (!x || !y || !expert_idx) return set_error(MOQE_E_NULL, "moqe_forward_routed: x, y or expert_idx is NULL");
+  if (!aligned(x, 16) || !aligned(y, 16)) return set_error(MOQE_E_SHAPE, "moqe_forward_routed: x and y must be 16-byte aligned");
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total)
+    return set_error(MOQE_E_WORKSPACE, "moqe_forward_routed: workspace needs %zu bytes, 256-byte aligned", L.total);
+  if (dry_run()) return MOQE_OK;
+  return forward_body(blk, x, S, T, y, aux, L, g0, g2, workspace, stream, expert_idx);
+}
+
+size_t moqe_workspace_bytes_routed(const moqe_block* blk, int32_t S, int32_t T) {
+  FwdLayout L;
+  GroupedPlan g0, g2;
+  if (forward_layout(blk, S, T, &L, &g0, &g2, true)) return 0;
+  return L.total;
 }
 
 int32_t moqe_forward_static(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
@@ -579,7 +608,8 @@ int32_t moqe_forward_static(const moqe_block* blk, const void* x, int32_t S, int
 
 namespace {
 int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T, void* y, const moqe_aux* aux,
-                     const FwdLayout& L, const GroupedPlan& g0, const GroupedPlan& g2, void* workspace, void* stream) {
+                     const FwdLayout& L, const GroupedPlan& g0, const GroupedPlan& g2, void* workspace, void* stream,
+                     const int32_t* given_idx) {
   int32_t rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint8_t* ws = static_cast<uint8_t*>(workspace);
@@ -604,10 +634,17 @@ int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T,
   const bool self = blk->kind != MOQE_KIND_CONV3X3 && can_self_bucket(S, T, blk->w0[0].k, g0);
   float* want_logits = (aux && aux->logits) ? logits : nullptr;
   int32_t* want_inv = (aux && aux->inv_perm) ? inv_perm : nullptr;
-  if (self) rc = launch_route(x, S, T, blk->router, idx, want_logits, ws + L.route, st);
-  else rc = launch_route_bucket(x, S, T, blk->router, idx, want_logits, counts, offsets, perm, want_inv, ws + L.route, st);
+  const int32_t* chosen = idx;
+  if (given_idx) {                      // routed by the caller: only the bucketing is left to do
+    chosen = given_idx;
+    rc = self ? MOQE_OK : launch_bucket(given_idx, S, K, counts, offsets, perm, want_inv, st);
+  } else if (self) {
+    rc = launch_route(x, S, T, blk->router, idx, want_logits, ws + L.route, st);
+  } else {
+    rc = launch_route_bucket(x, S, T, blk->router, idx, want_logits, counts, offsets, perm, want_inv, ws + L.route, st);
+  }
   if (rc) return rc;
-  const SelfBucket sb{idx, counts, offsets, perm, want_inv};
+  const SelfBucket sb{chosen, counts, offsets, perm, want_inv};
   const SelfBucket* psb = self ? &sb : nullptr;
 
   if (blk->kind == MOQE_KIND_LINEAR) {

@@ -167,6 +167,14 @@ def test_route_and_forward_argument_errors(mq):
     assert lib.moqe_forward(C.byref(blk), FAKE, 4, 3, FAKE, None, FAKE, need, None) == 0
     assert lib.moqe_forward(C.byref(blk), FAKE, 4, 3, FAKE, None, FAKE, need - 256, None) == -4
     assert lib.moqe_forward(C.byref(blk), None, 4, 3, FAKE, None, FAKE, need, None) == -1
+    # the block on experts chosen by the caller: the block's own router may be empty
+    norouter = mq._Block(1, mq._Router(None, None, None, None, 0, 0, 0), gate, up, down, 2, 0, 0, 0)
+    rneed = lib.moqe_workspace_bytes_routed(C.byref(norouter), 4, 3)
+    assert 0 < rneed <= need
+    assert lib.moqe_forward_routed(C.byref(norouter), FAKE, FAKE, 4, 3, FAKE, None, FAKE, rneed, None) == 0
+    assert lib.moqe_forward_routed(C.byref(norouter), None, FAKE, 4, 3, FAKE, None, FAKE, rneed, None) == -1
+    assert lib.moqe_forward_routed(C.byref(norouter), FAKE, FAKE, 4, 3, FAKE, None, FAKE, rneed - 256, None) == -4
+    assert lib.moqe_forward(C.byref(norouter), FAKE, 4, 3, FAKE, None, FAKE, need, None) != 0     # the plain entry needs the router
     # the variant on the built-in scratch buffer: same checks, and a batch that does not fit is refused
     assert lib.moqe_forward_static(C.byref(blk), FAKE, 4, 3, FAKE, None, None) == 0
     assert lib.moqe_forward_static(C.byref(blk), None, 4, 3, FAKE, None, None) == -1

@@ -86,3 +86,31 @@ def test_route_cv_full_size_conv_workload_shape():
     srt = np.sort(ref_logits, axis=1)
     clear = (srt[:, -1] - srt[:, -2]) > 2 * tol
     assert np.array_equal(ix[sample][clear], ref_idx[clear])
+
+
+def test_router_model_drives_the_routed_conv_stage():
+    """moqe_route_cv -> moqe_forward_routed on a 3x3 convolution stage: experts against the oracle's router, the stage's
+    output against the oracle's stage run on the experts the GPU router chose."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    from tests import oracle_blocks as ob
+    cfg = wl.scaled(wl.get_config("resnet50_conv"), S=9, T=30, D=128, F=48, img_h=5, img_w=6, router_hidden=16)
+    blk = ob.make_block(cfg)
+    mlp, stages, strides, heads = (32, 16, 16), (16, 32, 64), (1, 2, 2), 8
+    p = wl.make_cv_router(cfg.D, mlp, stages, strides, cfg.K, 72)      # a seed whose random router uses two experts
+    bits = wl.make_image_activations(cfg.S, cfg.img_h, cfg.img_w, cfg.D, 72)
+    x64 = oc.bf16_bits_to_f64(bits).reshape(cfg.S, cfg.T, cfg.D)
+    dev = {k: gb.to_dev(np.ascontiguousarray(v)) for k, v in p.items()}
+    r = mq.CvRouter(dev, cfg.D, strides, heads, cfg.K)
+    x = gb.bf16_dev(bits.reshape(cfg.M, cfg.D))
+    idx = torch.full((cfg.S,), -1, dtype=torch.int32, device=gb.DEV)
+    mq.moqe_route_cv(x, cfg.S, cfg.img_h, cfg.img_w, r, idx)
+    y = torch.full((cfg.M, cfg.F), float("nan"), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_forward_routed(gb.block_dev(blk), idx, x, cfg.S, cfg.T, y)
+    torch.cuda.synchronize()
+    e = idx.cpu().numpy()
+    ref_idx, _, _ = rc.route_cv(oc.bf16_bits_to_f64(bits), orc.make(p, 3, strides, heads))
+    assert len(set(e.tolist())) > 1 and np.mean(e == ref_idx) >= 0.8
+    y_ref, _, _ = oc.forward(blk, x64, expert_idx=e)
+    ok, worst = ob.tolerance_ok(y.cpu().numpy().reshape(cfg.S, cfg.T, cfg.F), y_ref)
+    assert ok, worst

@@ -84,14 +84,15 @@ def test_route_nlp_is_deterministic_and_feeds_the_bucket():
     assert np.array_equal(counts.cpu().numpy(), c) and np.array_equal(perm.cpu().numpy(), pm)
 
 
-def test_router_model_drives_the_routed_mlp_block():
-    """The paper's router in front of the routed experts: moqe_route_nlp -> moqe_bucket -> grouped GEMM with gather and
-    scatter (the down projection of the block's experts, fed with the oracle's bf16 intermediate).  Compared with the
-    oracle's block run on the experts the GPU router chose (which are checked against the oracle's router above)."""
+@pytest.mark.parametrize("S,T", [(11, 6), (5, 70)])         # a batch that buckets itself in the first launch / one that does not
+def test_router_model_drives_the_routed_mlp_block(S, T):
+    """The paper's router in front of the routed experts: moqe_route_nlp -> moqe_forward_routed (bucketing, grouped
+    gate/up GEMM with the SiLU gate, grouped down GEMM, scatter).  The experts the GPU router chose are checked against the
+    oracle's router, the block's output against the oracle's block run on those experts."""
     from paper_2508_09204_amd import binding as mq
     from tests import gpu_blocks as gb
     from tests import oracle_blocks as ob
-    cfg = wl.scaled(wl.get_config("llama7b_mlp_decode"), S=11, T=6, D=256, F=384, router_hidden=32)
+    cfg = wl.scaled(wl.get_config("llama7b_mlp_decode"), S=S, T=T, D=256, F=384, router_hidden=32)
     blk = ob.make_block(cfg)
     dm, heads, dff, hh = 128, 4, 256, 32
     p = wl.make_nlp_router(cfg.D, dm, heads, dff, hh, cfg.K, 31)
@@ -101,30 +102,23 @@ def test_router_model_drives_the_routed_mlp_block():
     x = gb.bf16_dev(bits.reshape(cfg.M, cfg.D))
     idx = torch.full((cfg.S,), -1, dtype=torch.int32, device=gb.DEV)
     mq.moqe_route_nlp(x, cfg.S, cfg.T, r, idx)
-    counts = torch.zeros(cfg.K, dtype=torch.int32, device=gb.DEV)
-    offsets = torch.zeros(cfg.K + 1, dtype=torch.int32, device=gb.DEV)
-    perm = torch.zeros(cfg.S, dtype=torch.int32, device=gb.DEV)
-    mq.moqe_bucket(idx, cfg.S, cfg.K, counts, offsets, perm, None)
     dblk = gb.block_dev(blk)
     y = torch.full((cfg.M, cfg.D), float("nan"), dtype=torch.float32, device=gb.DEV)
+    aux = gb.new_aux(cfg.S, cfg.K, cfg.M, cfg.F)
+    aux.expert_idx = None
+    aux.logits = None
+    mq.moqe_forward_routed(dblk, idx, x, cfg.S, cfg.T, y, aux)
     torch.cuda.synchronize()
     e = idx.cpu().numpy()
     assert len(set(e.tolist())) > 1
     ref_idx, _, _ = rn.route_nlp(x64, orn.make(p, heads), round_operands=True)
     assert np.mean(e == ref_idx) >= 0.8
-    c, o, pm, _ = oc.bucket(e, cfg.K)
-    assert np.array_equal(counts.cpu().numpy(), c) and np.array_equal(offsets.cpu().numpy(), o) and np.array_equal(perm.cpu().numpy(), pm)
-    # the intermediate rows are in the caller's order, so the launch gathers them through perm and scatters the result back
-    y_ref, _, _ = oc.forward(blk, x64, expert_idx=e)
-    hs = np.stack([oc.silu_mlp(x64[s], blk.w0[int(e[s])], blk.w1[int(e[s])], blk.w2[int(e[s])])[1] for s in range(cfg.S)])
-    h_bits = wl.f32_to_bf16_bits(hs.astype(np.float32).reshape(cfg.M, cfg.F))
-    h_dev = gb.bf16_dev(h_bits)
-    mq.moqe_grouped_qgemm(h_dev, offsets, perm, cfg.S, cfg.T, dblk.w2, y, mq.SCATTER_OUTPUT)
-    torch.cuda.synchronize()
-    a8 = [k for k in range(cfg.K) if blk.w0[k].act_mode]
-    keep = ~np.isin(e, a8)
-    ok, worst = ob.tolerance_ok(y.cpu().numpy().reshape(cfg.S, cfg.T, cfg.D)[keep], y_ref[keep])
-    assert ok, worst
+    c, o, pm, iv = oc.bucket(e, cfg.K)
+    assert np.array_equal(aux.counts.cpu().numpy(), c) and np.array_equal(aux.offsets.cpu().numpy(), o)
+    assert np.array_equal(aux.perm.cpu().numpy(), pm) and np.array_equal(aux.inv_perm.cpu().numpy(), iv)
+    # stage-wise, as for moqe_forward: H against the oracle's H, the down projection against the oracle's on the GPU's H
+    from tests.test_gpu_forward import _check_mlp_stages
+    _check_mlp_stages(cfg, blk, x64, aux, y.cpu().numpy().reshape(cfg.S, cfg.T, cfg.D), e)
 
 
 @pytest.mark.timeout(900)

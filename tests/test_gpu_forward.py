@@ -251,3 +251,38 @@ def test_forward_router_batch_sizes_around_the_fused_tail_limits(S, hidden):
     _check_routing(cfg, aux, ref_idx)
     ok, worst = ob.tolerance_ok(y, y_ref)
     assert ok, worst
+
+
+@pytest.mark.parametrize("S,T", [(64, 1), (37, 2), (5, 20), (1, 7)])
+def test_forward_small_batch_equals_the_separate_stages_bit_for_bit(S, T):
+    """Batches of at most 64 samples are bucketed inside the first grouped launch; the same block through the separate
+    entry points (route, bucket kernel, two grouped launches reading the bucket arrays from memory) must give the very
+    same bits: routing arrays, H and Y."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    cfg = wl.scaled(wl.get_config("llama7b_mlp_decode"), S=S, T=T, D=256, F=384, router_hidden=32)
+    blk = ob.make_block(cfg)
+    bits, _ = ob.activations_f64(cfg)
+    dblk = gb.block_dev(blk)
+    x = gb.bf16_dev(bits.reshape(cfg.M, cfg.D))
+    y = torch.full((cfg.M, cfg.D), float("nan"), dtype=torch.float32, device=gb.DEV)
+    aux = gb.new_aux(cfg.S, cfg.K, cfg.M, cfg.F)
+    mq.moqe_forward(dblk, x, cfg.S, cfg.T, y, aux)
+    # the stages one by one
+    idx = torch.full((S,), -1, dtype=torch.int32, device=gb.DEV)
+    ws = torch.empty(mq.moqe_route_workspace_bytes(S, T, dblk.router), dtype=torch.uint8, device=gb.DEV)
+    mq.moqe_route(x, S, T, dblk.router, idx, None, ws)
+    counts = torch.zeros(cfg.K, dtype=torch.int32, device=gb.DEV)
+    offsets = torch.zeros(cfg.K + 1, dtype=torch.int32, device=gb.DEV)
+    perm = torch.zeros(S, dtype=torch.int32, device=gb.DEV)
+    inv = torch.zeros(S, dtype=torch.int32, device=gb.DEV)
+    mq.moqe_bucket(idx, S, cfg.K, counts, offsets, perm, inv)
+    y2 = torch.full((cfg.M, cfg.D), float("nan"), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_grouped_qgemm(aux.h, offsets, perm, S, T, dblk.w2, y2, mq.SCATTER_OUTPUT | mq.INPUT_IN_BUCKET_ORDER)
+    y3 = torch.full((cfg.M, cfg.D), float("nan"), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_forward_routed(dblk, idx, x, S, T, y3)
+    torch.cuda.synchronize()
+    for a, b in ((aux.expert_idx, idx), (aux.counts, counts), (aux.offsets, offsets), (aux.perm, perm), (aux.inv_perm, inv)):
+        assert torch.equal(a, b)
+    assert torch.equal(y.view(torch.int32), y2.view(torch.int32))        # the down launch from memory-resident bucket arrays
+    assert torch.equal(y.view(torch.int32), y3.view(torch.int32))        # the whole block on the given experts

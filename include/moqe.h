@@ -12,6 +12,10 @@
  * counts are the n_i of Eq. 2), run each group through its expert's low-bit weights
  * (moqe_grouped_qgemm) and put results back in the caller's order; moqe_forward chains
  * these for one block.  The per-sample result is the same as serving samples one by one.
+ * Beside the block: the paper's two router models (moqe_route_nlp, moqe_route_cv; Section 3.2), whose choice
+ * drives the block through moqe_forward_routed; the router-training label pass and the load-balance
+ * statistics of Section 3.3 (moqe_label_pass, moqe_balance_stats); samples of different lengths
+ * (moqe_*_ragged); on-demand residency of the experts' weights (moqe_cache_*, Section 4.4).
  *
  * Conventions (all entry points).
  *  - Return value: 0 on success, a negative MOQE_E_* code on failure.  Every argument
@@ -23,7 +27,7 @@
  *    library does not allocate, free or retain device memory, with one exception: an expert
  *    cache (moqe_cache_create) owns the device slots it allocates until moqe_cache_destroy.
  *    An activation matrix (rows x features, bf16) must stay below 4 GiB.  Descriptor structs
- *    (moqe_qmat, moqe_router, moqe_block, moqe_aux) and arrays of them are HOST memory,
+ *    (moqe_qmat, moqe_router, moqe_nlp_router, moqe_cv_router, moqe_block, moqe_aux) and arrays of them are HOST memory,
  *    read during the call only.  Scratch memory is a caller-provided device workspace
  *    whose size comes from the matching *_workspace_bytes query; it must be 256-byte
  *    aligned and may be reused between calls on the same stream.

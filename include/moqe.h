@@ -162,7 +162,7 @@ typedef struct moqe_cv_router {
  *              w2 = down; gate and up of an expert share one format.
  *   CONV3X3  : per image, 3x3 convolution, stride 1, zero padding 1, no bias.  x is NHWC
  *              [S, img_h, img_w, cin] (T = img_h*img_w), w0[e] is [cout, cin*9] with
- *              k = (kh*3 + kw)*cin + c (taps slow, channels fast, like x); y is NHWC fp32. */
+ *              k = (kh*3 + kw)*cin + c (taps slow, channels fast, like x); y is NHWC fp32 (bf16 with y_bf16). */
 typedef struct moqe_block {
   int32_t kind;
   moqe_router router;
@@ -171,6 +171,8 @@ typedef struct moqe_block {
   const moqe_qmat* w2;
   int32_t n_experts;
   int32_t img_h, img_w, cin;          /* CONV3X3 only */
+  int32_t y_bf16;                     /* 0: y is fp32; 1: y is bf16 (each result rounded once, nearest even): half the
+                                         output bytes where the next layer takes bf16 anyway */
 } moqe_block;
 
 /* Optional extra outputs of moqe_forward (any member may be NULL; all device). */

@@ -68,7 +68,8 @@ class _CvRouter(C.Structure):
 class _Block(C.Structure):
     _fields_ = [("kind", C.c_int32), ("router", _Router),
                 ("w0", C.POINTER(_QMat)), ("w1", C.POINTER(_QMat)), ("w2", C.POINTER(_QMat)),
-                ("n_experts", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32), ("cin", C.c_int32)]
+                ("n_experts", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32), ("cin", C.c_int32),
+                ("y_bf16", C.c_int32)]
 
 
 class _Aux(C.Structure):
@@ -254,6 +255,7 @@ class Block:
     img_h: int = 0
     img_w: int = 0
     cin: int = 0
+    y_bf16: int = 0
     _keep: list = field(default_factory=list, repr=False)
 
     def c(self) -> _Block:
@@ -265,7 +267,7 @@ class Block:
             return a
         self._keep.clear()
         return _Block(self.kind, self.router.c(), arr(self.w0), arr(self.w1), arr(self.w2), len(self.w0),
-                      self.img_h, self.img_w, self.cin)
+                      self.img_h, self.img_w, self.cin, self.y_bf16)
 
 
 @dataclass

@@ -480,6 +480,7 @@ int32_t forward_layout(const moqe_block* b, int S, int T, FwdLayout* L, GroupedP
   } else {
     return set_error(MOQE_E_FORMAT, "moqe_forward: unknown block kind %d", b->kind);
   }
+  if (b->y_bf16 != 0 && b->y_bf16 != 1) return set_error(MOQE_E_FORMAT, "moqe_forward: y_bf16=%d (0 or 1)", b->y_bf16);
   const size_t M = size_t(S) * T;
   // every activation matrix a kernel indexes: x itself, and the bf16 intermediate of the MLP
   rc = check_activation_bytes((long long)M, b->kind == MOQE_KIND_CONV3X3 ? b->cin : b->w0[0].k, "moqe_forward");
@@ -647,17 +648,18 @@ int32_t forward_body(const moqe_block* blk, const void* x, int32_t S, int32_t T,
   const SelfBucket sb{chosen, counts, offsets, perm, want_inv};
   const SelfBucket* psb = self ? &sb : nullptr;
 
+  const bool yb = blk->y_bf16 != 0;
   if (blk->kind == MOQE_KIND_LINEAR) {
-    return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, 0, 0, 0, false, psb);
+    return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, 0, 0, 0, yb, psb);
   }
   if (blk->kind == MOQE_KIND_SILU_MLP) {
     void* h = (aux && aux->h) ? aux->h : static_cast<void*>(ws + L.h);
     rc = run_grouped(x, offsets, perm, nullptr, S, T, blk->w0, blk->w1, K, g0, h, ws + L.a8, st, 0, 0, 0, false, psb);
     if (rc) return rc;
-    return run_grouped(h, offsets, nullptr, perm, S, T, blk->w2, nullptr, K, g2, y, ws + L.a8, st);
+    return run_grouped(h, offsets, nullptr, perm, S, T, blk->w2, nullptr, K, g2, y, ws + L.a8, st, 0, 0, 0, yb);
   }
   // CONV3X3: the tiled kernel gathers each row's 3x3 neighbourhood from the image itself
-  return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, blk->img_h, blk->img_w, blk->cin);
+  return run_grouped(x, offsets, perm, perm, S, T, blk->w0, nullptr, K, g0, y, ws + L.a8, st, blk->img_h, blk->img_w, blk->cin, yb);
 }
 }  // namespace
 
@@ -767,6 +769,7 @@ int32_t ragged_layout(const moqe_block* b, int S, long long M, RaggedLayout* L, 
   if (b->kind != MOQE_KIND_LINEAR && b->kind != MOQE_KIND_SILU_MLP)
     return set_error(MOQE_E_FORMAT, "moqe_forward_ragged: kind %d (images have a fixed number of pixels)", b->kind);
   if (S < 0 || M < S || M > 0x7fffffffLL) return set_error(MOQE_E_SHAPE, "moqe_forward_ragged: S=%d M=%lld", S, M);
+  if (b->y_bf16 != 0 && b->y_bf16 != 1) return set_error(MOQE_E_FORMAT, "moqe_forward_ragged: y_bf16=%d (0 or 1)", b->y_bf16);
   if (!b->w0) return set_error(MOQE_E_NULL, "moqe_forward_ragged: w0 is NULL");
   rc = plan_experts(b->w0, K, b->kind == MOQE_KIND_SILU_MLP ? b->w1 : nullptr, gp0, "moqe_forward_ragged");
   if (rc) return rc;
@@ -858,11 +861,11 @@ int32_t moqe_forward_ragged(const moqe_block* blk, const void* x, const int32_t*
   if (rc) return rc;
   // from here on every row is its own "sample": bucket offsets and permutation at row granularity
   if (blk->kind == MOQE_KIND_LINEAR)
-    return run_grouped(x, row_offsets, row_perm, row_perm, M, 1, blk->w0, nullptr, K, g0, y, ws + L.a8, st);
+    return run_grouped(x, row_offsets, row_perm, row_perm, M, 1, blk->w0, nullptr, K, g0, y, ws + L.a8, st, 0, 0, 0, blk->y_bf16 != 0);
   void* h = (aux && aux->h) ? aux->h : static_cast<void*>(ws + L.h);
   rc = run_grouped(x, row_offsets, row_perm, nullptr, M, 1, blk->w0, blk->w1, K, g0, h, ws + L.a8, st);
   if (rc) return rc;
-  return run_grouped(h, row_offsets, nullptr, row_perm, M, 1, blk->w2, nullptr, K, g2, y, ws + L.a8, st);
+  return run_grouped(h, row_offsets, nullptr, row_perm, M, 1, blk->w2, nullptr, K, g2, y, ws + L.a8, st, 0, 0, 0, blk->y_bf16 != 0);
 }
 
 // ---- timing --------------------------------------------------------------------------------

@@ -286,3 +286,27 @@ def test_forward_small_batch_equals_the_separate_stages_bit_for_bit(S, T):
         assert torch.equal(a, b)
     assert torch.equal(y.view(torch.int32), y2.view(torch.int32))        # the down launch from memory-resident bucket arrays
     assert torch.equal(y.view(torch.int32), y3.view(torch.int32))        # the whole block on the given experts
+
+
+@pytest.mark.parametrize("which", ["linear", "mlp", "mlp_prefill", "conv"])
+def test_forward_bf16_output_is_the_fp32_output_rounded_once(which):
+    """moqe_block.y_bf16: the same block with bf16 results must give exactly the fp32 results rounded to nearest even
+    (the rounding is the last step of the same arithmetic), on the streaming and on the tiled kernel."""
+    from paper_2508_09204_amd import binding as mq
+    from tests import gpu_blocks as gb
+    kw = dict(SMALL[which])
+    cfg = wl.scaled(wl.get_config(kw.pop("base")), **kw)
+    blk = ob.make_block(cfg)
+    bits, _ = ob.activations_f64(cfg)
+    x = gb.bf16_dev(bits.reshape(cfg.M, cfg.D))
+    n_out = cfg.D if cfg.kind == K_MLP else cfg.F
+    d32 = gb.block_dev(blk)
+    y32 = torch.full((cfg.M, n_out), float("nan"), dtype=torch.float32, device=gb.DEV)
+    mq.moqe_forward(d32, x, cfg.S, cfg.T, y32)
+    d16 = gb.block_dev(blk)
+    d16.y_bf16 = 1
+    y16 = torch.full((cfg.M, n_out), float("nan"), dtype=torch.bfloat16, device=gb.DEV)
+    mq.moqe_forward(d16, x, cfg.S, cfg.T, y16)
+    torch.cuda.synchronize()
+    assert torch.equal(y16.view(torch.int16), y32.to(torch.bfloat16).view(torch.int16))
+    assert bool(torch.isfinite(y32).all())

@@ -120,6 +120,30 @@ def test_bucket_sizes_around_tile_edges(rows):
     assert ok, worst
 
 
+@pytest.mark.parametrize("S,T,counts", [
+    (200, 1, [150, 20, 1, 0, 29]),        # more than 128 rows in all: both kernels run, the 150-row bucket is tiled
+    (100, 2, [75, 16, 9]),                # the same with two rows per sample: buckets of 150, 32 and 18 rows
+    (129, 1, [33, 32, 32, 32]),           # every bucket at the limit of one streaming pass, one just above it
+    (1, 200, [1]),                        # one sample of 200 tokens: the tiled kernel alone
+    (4, 32, [2, 1, 1]),                   # samples of exactly one streaming pass: 128 rows, the streaming kernel alone
+    (5, 32, [3, 1, 1]),                   # 160 rows in samples of 32: a 96-row bucket tiled, two of 32 streamed
+])
+def test_launches_that_split_the_experts_between_the_kernels(S, T, counts):
+    """Which kernel takes a bucket follows its number of rows; one launch can use both."""
+    rng = np.random.default_rng(S * 7 + T)
+    n, k = 48, 384
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    specs = [(4, 128, False, 1.0, 0), (8, 0, True, 1.0, 1), (3, 64, False, 1.0, 0), (6, 0, True, 1.0, 0),
+             (8, 0, True, 1.0, 0)]
+    qms = [oc.quantize(w, *specs[i]) for i in range(len(counts))]
+    assert sum(counts) == S
+    e = rng.permutation(np.repeat(np.arange(len(counts)), counts)).astype(np.int32)
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((S * T, k)).astype(np.float32))
+    y = _run(a_bits, e, qms, S, T)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, qms, S, T))
+    assert ok, worst
+
+
 def test_w8a8_integer_accumulators_are_exact():
     """With unit scales the W8A8 output IS the int32 dot product: compare exactly."""
     rng = np.random.default_rng(3)

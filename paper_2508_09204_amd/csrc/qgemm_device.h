@@ -34,6 +34,37 @@ template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr 
 template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 4; };
 template <> struct Raw<FMT_N6>   { static constexpr int N = 6; static constexpr int PF = 2; };
 
+// A pointer the compiler cannot trace back to a kernel argument (one put together from integers, say) is
+// loaded through the flat path, and a pending flat load turns every later wait for memory into a wait for
+// ALL memory operations: a ring of loads in flight drains at each use.  Such pointers are cast to the
+// global address space once; loads through them are global loads with exact, in-order wait counts.
+#define MOQE_GLOBAL __attribute__((address_space(1)))
+typedef const MOQE_GLOBAL uint8_t* gbytes;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ gbytes as_global(const uint8_t* p) { return (gbytes)p; }
+template <typename T> static __device__ __forceinline__ T load_global(gbytes p) { return *(const MOQE_GLOBAL T*)p; }
+
+// The packed codes of one 16 x 128 tile, this lane's share, through a global-address-space pointer.
+template <int FMT>
+static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], gbytes tile, int lane) {
+  if constexpr (FMT == FMT_I8 || FMT == FMT_I8A8) {
+    const u32x4 a = load_global<u32x4>(tile + lane * 16), b = load_global<u32x4>(tile + 1024 + lane * 16);
+    r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w; r[4] = b.x; r[5] = b.y; r[6] = b.z; r[7] = b.w;
+  } else if constexpr (FMT == FMT_N4) {
+    const u32x4 a = load_global<u32x4>(tile + lane * 16);
+    r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w;
+  } else if constexpr (FMT == FMT_N3) {
+    const u32x2 a = load_global<u32x2>(tile + lane * 8);
+    r[0] = a.x; r[1] = a.y;
+    r[2] = load_global<uint32_t>(tile + 512 + lane * 4);
+  } else {
+    const u32x4 a = load_global<u32x4>(tile + lane * 16);
+    const u32x2 b = load_global<u32x2>(tile + 1024 + lane * 8);
+    r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w; r[4] = b.x; r[5] = b.y;
+  }
+}
+
 template <int FMT>
 static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], const uint8_t* tile, int lane) {
   if constexpr (FMT == FMT_I8 || FMT == FMT_I8A8) {

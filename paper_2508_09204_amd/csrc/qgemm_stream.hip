@@ -113,11 +113,11 @@ static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, 
   // Relative time of one weight tile row: mostly its bytes, plus what unpacking costs (measured per format on
   // MI355X), a little more when the bucket needs both 16-row blocks; times the passes over the bucket.
   const int f = mine_ex.fmt;
-  const int per_tile = f == FMT_I8 ? 28 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 26 : (f == FMT_N4 ? 20 : 23)));
+  const int per_tile = f == FMT_I8 ? 28 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 26 : (f == FMT_N4 ? 20 : 27)));
   const int passes = (rows + STREAM_ROWS - 1) / STREAM_ROWS;
   const int last = rows - (passes - 1) * STREAM_ROWS;              // rows of the last pass
-  const int eighths = (passes - 1) * 9 + (last > 16 ? 9 : 8);      // a pass with two blocks counts 9/8
-  const int cost = mine ? per_tile * eighths : 0;                  // small integers
+  const int parts = (passes - 1) * 5 + (last > 16 ? 5 : 4);        // a pass with two blocks counts 5/4
+  const int cost = mine ? per_tile * parts : 0;                    // small integers
   const int total = row16_sum(cost);
   StreamSeg sg;
   sg.e = -1; sg.u0 = 0; sg.u1 = 0; sg.off_e = 0; sg.rows_e = 0;
@@ -176,12 +176,6 @@ static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, 
   return sg;
 }
 
-static __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-static __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-static __device__ __forceinline__ float sum8(const u32x4& a) {
-  return ((bf16_lo(a.x) + bf16_hi(a.x)) + (bf16_lo(a.y) + bf16_hi(a.y))) +
-         ((bf16_lo(a.z) + bf16_hi(a.z)) + (bf16_lo(a.w) + bf16_hi(a.w)));
-}
 template <typename V> static __device__ __forceinline__ V pick4(int q, V a, V b, V c, V d) {
   return q == 0 ? a : (q == 1 ? b : (q == 2 ? c : d));
 }
@@ -224,14 +218,18 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   // ---- rows of this pass ---------------------------------------------------------------------------------
   // operand rows: lane (lr, lq) feeds row mt*16 + lr of the pass; result rows: register r of lane (lr, lq) is
   // row mt*16 + 4 lq + r.  Rows past the end repeat the last one and are never stored.
-  // The rows' gather / scatter indices and activation scales.
+  // The rows' gather / scatter indices and activation scales.  (An integer division by a run-time number is some
+  // forty instructions, and there are twenty of them here: one row per sample, the decode case, skips them.)
+  const bool one_row = T == 1;                          // uniform
+  auto div_t = [&](int m) { return one_row ? m : m / T; };
+  auto mod_t = [&](int m) { return one_row ? 0 : m % T; };
   const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
   int a_src[MT];                // sample of operand row mt*16 + lr (its gather index), before the row offset inside the sample
   int a_m[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     a_m[mt] = pass0 + min(mt * 16 + lr, rows_here - 1);
-    a_src[mt] = off_e + a_m[mt] / T;
+    a_src[mt] = off_e + div_t(a_m[mt]);
     if (!A8 && ga.a_perm) a_src[mt] = perm_l ? perm_l[a_src[mt]] : ga.a_perm[a_src[mt]];
   }
   int out_row[MT][4];           // destination row of each result register
@@ -242,7 +240,7 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
     for (int r = 0; r < 4; ++r) {
       const int m = pass0 + min(mt * 16 + lq * 4 + r, rows_here - 1);
       const int brow = off_e * T + m;
-      int dsmp = off_e + m / T;
+      int dsmp = off_e + div_t(m);
       if (!GATEUP && ga.y_perm) dsmp = perm_l ? perm_l[dsmp] : ga.y_perm[dsmp];
       out_row[mt][r] = dsmp;                                       // turned into a row index after the ring's first row
       sx[mt][r] = 1.f;
@@ -251,24 +249,25 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   size_t a_row_off[MT];
 
   // ---- weight ring -----------------------------------------------------------------------------------------
-  // The work-group walks its tile rows in order, padded to whole batches (a padding row repeats the last row's
-  // tiles and is never added up).  The ring holds D consecutive rows, KPW tiles each; tile (row, t) is requested
+  // The work-group walks its tile rows in order, whole batches first, the rows left over last (requests past
+  // the last row repeat it and are never used).  The ring holds D consecutive rows, KPW tiles each; tile (row, t) is requested
   // again, for the row D places further on, right after its matrix-core operations, so KPW * D - 1 tiles are in
   // flight behind the one being multiplied, across batch boundaries alike.  `cur_i` is the next row to request.
   uint32_t raw[D][KPW][NR];
   float sc[D][KPW][GP1];                                // group scales; per-channel formats: [0] of tile 0 is the row's scale
   uint32_t zp[D][KPW];
   const uint32_t tile_bytes = ex.tile_bytes, scale_off = ex.scale_off, zero_off = ex.zero_off;
-  const uint8_t* const blob0 = ex.w[0];
-  const uint8_t* const blob1 = ex.w[GATEUP ? 1 : 0];
+  // the schedule hands the blob addresses over as integers: typed as global memory here (see as_global)
+  const gbytes blob0 = as_global(ex.w[0]);
+  const gbytes blob1 = as_global(ex.w[GATEUP ? 1 : 0]);
   int cur_i = 0;
   // derived from the position: which blob, first tile index of the row's KPW tiles, tile row
-  const uint8_t* cur_blob = blob0;
+  gbytes cur_blob = blob0;
   uint32_t cur_t0 = 0u;
   int cur_nt = u0;
   const int cur_tmax = max(nkt - 1, 0);                  // tiles the wave does not have repeat its last one (or the row's last)
   auto cur_derive = [&]() {
-    const int i = min(cur_i, ntr - 1);                   // padding rows and rows past the end: the last row again
+    const int i = min(cur_i, ntr - 1);                   // rows past the end: the last row again
     cur_nt = GATEUP ? u0 + (i >> 1) : u0 + i;
     cur_blob = (GATEUP && (i & 1)) ? blob1 : blob0;
     cur_t0 = uint32_t(cur_nt) * uint32_t(KT) + uint32_t(min(ktw0, KT - 1));
@@ -281,21 +280,21 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
     const uint32_t tl = cur_t0 + uint32_t(min(t, cur_tmax));
     load_raw<FMT>(raw[d][t], cur_blob + size_t(tl) * tile_bytes, lane);
     if constexpr (GPT > 0) {
-      const uint8_t* sp = cur_blob + scale_off + size_t(tl) * (16 * GPT * 4) + lr * (GPT * 4);
+      const gbytes sp = cur_blob + scale_off + size_t(tl) * (16 * GPT * 4) + lr * (GPT * 4);
       // zero-points: the aligned dword that holds the lane's byte(s); shifted down where it is used (a
       // narrower load would get its zero-extension placed right behind the load, which waits for the ring)
-      const uint8_t* zq = cur_blob + zero_off + size_t(tl) * (16 * GPT) + ((lr * GPT) & ~3);
-      zp[d][t] = *reinterpret_cast<const uint32_t*>(zq);
+      const gbytes zq = cur_blob + zero_off + size_t(tl) * (16 * GPT) + ((lr * GPT) & ~3);
+      zp[d][t] = load_global<uint32_t>(zq);
       if constexpr (GPT == 1) {
-        sc[d][t][0] = *reinterpret_cast<const float*>(sp);
+        sc[d][t][0] = load_global<float>(sp);
       } else {
-        const float2 v = *reinterpret_cast<const float2*>(sp);
+        const f32x2 v = load_global<f32x2>(sp);
         sc[d][t][0] = v.x; sc[d][t][GP1 - 1] = v.y;
       }
     } else {
       zp[d][t] = 0u;
       sc[d][t][0] = 1.f;
-      if (t == 0) sc[d][t][0] = reinterpret_cast<const float*>(cur_blob + scale_off)[cur_nt * 16 + lr];
+      if (t == 0) sc[d][t][0] = load_global<float>(cur_blob + scale_off + size_t(cur_nt * 16 + lr) * 4);
     }
   };
   // ---- this wave's slice of the activations, as matrix-core operands ---------------------------------------------
@@ -320,21 +319,25 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   // in L2 issued behind them would still wait for them all.
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    a_row_off[mt] = (size_t(a_src[mt]) * T + size_t(a_m[mt] % T)) * size_t(ga.k) * (A8 ? 1 : 2);
+    a_row_off[mt] = (size_t(a_src[mt]) * T + size_t(mod_t(a_m[mt]))) * size_t(ga.k) * (A8 ? 1 : 2);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int m = pass0 + min(mt * 16 + lq * 4 + r, rows_here - 1);
-      out_row[mt][r] = out_row[mt][r] * T + (m % T);
+      out_row[mt][r] = out_row[mt][r] * T + mod_t(m);
     }
   }
   load_a();
   cur_derive();
+  // the ring's first row right behind the activations; the rows after it once the activations have been
+  // used (below): a wave that requested its whole ring first would sit behind the other waves' rings too
+  // (scheduling barriers: the first fill must request the tiles in the loop's order, see the loop's head)
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int d = 0; d < D; ++d) {
-#pragma unroll
-    for (int t = 0; t < KPW; ++t) issue_tile(d, t);
-    cur_advance();
+  for (int t = 0; t < KPW; ++t) {
+    issue_tile(0, t);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  cur_advance();
 
   {
     {
@@ -350,27 +353,28 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
 #pragma unroll
         for (int g = 0; g < GP1; ++g) xs_op[mt][g] = 0.f;
       }
+      const u32x4 ones_u = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
       if constexpr (!A8 && GPT > 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
           for (int g = 0; g < GPT; ++g) {
+            // all-ones first operand, the activations as second: every result register of lane (lr, .) is the sum
+            // of row lr over the columns multiplied (fp32 accumulation inside the matrix core)
             float pt[KPW];
 #pragma unroll
             for (int t = 0; t < KPW; ++t) {
-              float v;
-              if constexpr (GPT == 1) v = (sum8(areg[t][0][mt]) + sum8(areg[t][1][mt])) + (sum8(areg[t][2][mt]) + sum8(areg[t][3][mt]));
-              else v = sum8(areg[t][2 * g][mt]) + sum8(areg[t][2 * g + 1][mt]);
-              v += __shfl_xor(v, 16, 64);
-              v += __shfl_xor(v, 32, 64);
-              pt[t] = v;                                           // zero for k-tiles the wave does not have
+              f32x4 v = zero4;
+#pragma unroll
+              for (int j = (GPT == 1 ? 0 : 2 * g); j < (GPT == 1 ? 4 : 2 * g + 2); ++j)
+                v = mfma_bf16(ones_u, __builtin_bit_cast(bf16x8, areg[t][j][mt]), v);
+              pt[t] = v[0];                                        // zero for k-tiles the wave does not have
             }
             xs_op[mt][g] = pick4(lq, pt[0], pt[1], pt[2], pt[3]);
           }
       }
       if constexpr (!A8 && GPT == 0) {
-        const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-        const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones);
+        const bf16x8 ones_b = __builtin_bit_cast(bf16x8, ones_u);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           f32x4 v = zero4;
@@ -381,6 +385,18 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
           xs_c[mt] = v;
         }
       }
+
+      // the rest of the ring, in the order the loop below requests it again
+#pragma unroll
+      for (int d = 1; d < D; ++d) {
+#pragma unroll
+        for (int t = 0; t < KPW; ++t) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue_tile(d, t);
+        }
+        cur_advance();
+      }
+      __builtin_amdgcn_sched_barrier(0);
 
       // The ring values arrive through the loop's back edge.  Pinning a tile's registers where the tile is
       // used keeps the optimizer from moving arithmetic on them (a mask, a conversion) up to the end of the
@@ -393,10 +409,10 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
         for (int g = 0; g < GP1; ++g) asm volatile("" : "+v"(sc[d][t][g]));
       };
       // ---- one tile row from ring slot d: the wave's partial result, ready to be added across waves.  Straight-
-      // line code: a k-tile the wave does not have is multiplied by all-zero activation operands, a padding row
-      // is multiplied like any other and never added up.  With no branch around a load the waits can be exact,
-      // and the compiler may overlap one tile's unpacking with the matrix-core operations of another. -------
-      auto multiply = [&](int d, bool row_live, f32x4 (&res)[MT], float& row_scale) {
+      // line code: a k-tile the wave does not have is multiplied by all-zero activation operands.  With no branch
+      // around a load the waits can be exact, and the compiler may overlap one tile's unpacking with the
+      // matrix-core operations of another. -------
+      auto multiply = [&](int d, f32x4 (&res)[MT], float& row_scale) {
         pin_tile(d, 0);
         row_scale = sc[d][0][0];                                   // per-channel formats: kept for the epilogue
         if constexpr (A8) {
@@ -499,16 +515,23 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
       };
 
       // ---- the tile rows, a batch per barrier ---------------------------------------------------------------
-      int bi = 0;
-#pragma unroll 1
-      for (int i0 = 0; i0 < ntr; i0 += B, ++bi) {
+      // Wait counts are static: at the loop's head the compiler takes, per register, the stricter of the count
+      // the loop's back edge needs and the count the code before the loop needs.  The first fill above requests
+      // the ring in the loop's own order, so both agree and a tile waits for its own load only.
+      // A batch of B tile rows starting at row i0.  Full batches run in the loop below, whose code has no branch
+      // around a row.  The rows left over (fewer than B) run once through a second copy of the same code that
+      // skips the absent rows: its wait counts are the cautious ones of branching code, which costs nothing
+      // when no further row is on its way, and a work-group with 22 rows pays for 22, not for 24.
+      auto batch = [&](auto tail_tag, const int i0, const int bi) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         uint8_t* pbuf = part + (bi & 1) * (PART_BYTES / 2);
         float pcs_b[B];                                            // the per-channel scales of this batch's tile rows
 #pragma unroll
         for (int b = 0; b < B; ++b) {
-          const bool row_live = i0 + b < ntr;                      // uniform over the work-group
+          const bool row_live = !TAIL || i0 + b < ntr;             // uniform over the work-group
           f32x4 res[MT];
-          multiply(b % D, row_live, res, pcs_b[b]);
+          pcs_b[b] = 0.f;
+          if (row_live) multiply(b % D, res, pcs_b[b]);
           if (row_live) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -582,7 +605,11 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
             }
           }
         }
-      }
+      };
+      int bi = 0, i0 = 0;
+#pragma unroll 1
+      for (; i0 + B <= ntr; i0 += B, ++bi) batch(std::false_type{}, i0, bi);
+      if (i0 < ntr) batch(std::true_type{}, i0, bi);
       __syncthreads();          // the partial-sum buffers are free again before the next pass writes them
     }
   }

@@ -187,3 +187,31 @@ def test_decode_shape_llama_gate_matrix():
     y = _run(a_bits, e, qms, cfg.S, 1)
     ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, qms, cfg.S, 1))
     assert ok, worst
+
+
+def _random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    K = int(rng.integers(1, 7))
+    T = int(rng.choice([1, 1, 2, 3, 5, 17, 33, 40]))
+    S = int(rng.integers(1, max(2, 260 // T)))
+    n = 16 * int(rng.integers(1, 11))
+    k = 128 * int(rng.choice([1, 2, 3, 5, 8, 33, 34]))       # 33 and 34 k-tiles: rows too long for the register-resident kernel
+    specs = [FORMATS[int(i)] for i in rng.integers(0, len(FORMATS), K)]
+    e = rng.integers(0, K, S).astype(np.int32)
+    if K > 1 and rng.random() < 0.5:
+        e[e == K - 1] = 0                                     # an empty expert, a heavier first one
+    return rng, K, S, T, n, k, specs, e
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_formats_and_routings(seed):
+    """Seeded random problems across the kernels' dispatch (few rows / many rows / both in one launch, short and long
+    weight rows, every format, empty experts), compared element by element with the oracle."""
+    rng, K, S, T, n, k, specs, e = _random_case(seed)
+    w = (rng.standard_normal((n, k)) * 0.02).astype(np.float32)
+    qms = [oc.quantize(w, *s) for s in specs]
+    a_bits = wl.f32_to_bf16_bits(rng.standard_normal((S * T, k)).astype(np.float32))
+    scatter, use_perm = bool(seed % 2 == 0), bool(seed % 3 != 0)
+    y = _run(a_bits, e, qms, S, T, scatter, use_perm)
+    ok, worst = ob.tolerance_ok(y, _ref(a_bits, e, qms, S, T))
+    assert ok, (worst, K, S, T, n, k, specs)

@@ -310,3 +310,35 @@ def test_forward_bf16_output_is_the_fp32_output_rounded_once(which):
     torch.cuda.synchronize()
     assert torch.equal(y16.view(torch.int16), y32.to(torch.bfloat16).view(torch.int16))
     assert bool(torch.isfinite(y32).all())
+
+
+_SPECS = [wl.configs.ExpertSpec(8, 0, True), wl.configs.ExpertSpec(8, 0, True, 1.0, 1), wl.configs.ExpertSpec(6, 0, True),
+          wl.configs.ExpertSpec(4, 0, True), wl.configs.ExpertSpec(4, 64, False), wl.configs.ExpertSpec(4, 128, False, 0.9),
+          wl.configs.ExpertSpec(3, 64, False), wl.configs.ExpertSpec(3, 128, False)]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_forward_random_blocks(seed):
+    """Seeded random MLP and linear blocks (sizes, formats, router with or without a hidden layer, rows per sample):
+    routing and bucketing bit for bit, outputs stage by stage as for the named workloads."""
+    rng = np.random.default_rng(500 + seed)
+    mlp = seed % 3 != 0
+    K = int(rng.integers(2, 7))
+    T = int(rng.choice([1, 1, 2, 4, 9, 36]))
+    S = int(rng.integers(2, max(3, 150 // T)))
+    D = 128 * int(rng.integers(1, 5))
+    F = 128 * int(rng.integers(1, 5)) if mlp else 16 * int(rng.integers(1, 9))
+    experts = tuple(_SPECS[int(i)] for i in rng.integers(0, len(_SPECS), K))
+    base = wl.get_config("llama7b_mlp_decode" if mlp else "toy_linear")
+    cfg = wl.scaled(base, S=S, T=T, D=D, F=F, experts=experts, router_hidden=int(rng.choice([0, 16, 48])),
+                    router_w_std=0.05, router_bias=(), seed=900 + seed)
+    blk = ob.make_block(cfg)
+    bits, x64 = ob.activations_f64(cfg)
+    y_ref, ref_idx, _ = oc.forward(blk, x64)
+    y, aux = _forward_gpu(cfg, blk, bits)
+    _check_routing(cfg, aux, ref_idx)
+    if mlp:
+        _check_mlp_stages(cfg, blk, x64, aux, y, ref_idx)
+    else:
+        ok, worst = ob.tolerance_ok(y, y_ref)
+        assert ok, (worst, K, S, T, D, F)

@@ -30,12 +30,12 @@ MFMA_INT8_PEAK_TOPS = 5000.0    # dense int8, published
 # this file are handed to the kernel launch itself and read within about 5 % of the trace (2-3 us on the decode
 # kernel); `frac_rocprof` is the roofline fraction with the profiler's own average duration.  Tied to the kernel
 # sources like the traffic figure.
-_SOURCES_AT_PROFILE = "40cb961e0012f8e595e886c311c0176060b8df2f1b8936fc77c9eb0b9c79dfa3"
+_SOURCES_AT_PROFILE = "17b57b22ebfb6b33c08c8d656e7ae452230ad5abd3db5cca05e4917b5753519b"
 ROCPROF_KERNEL_US = {
-    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 55.65},
-    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1855.93},
-    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 10661.74},
-    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 97.29},
+    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 54.88},
+    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1906.09},
+    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 10946.29},
+    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 95.33},
 }
 
 
@@ -45,8 +45,8 @@ ROCPROF_KERNEL_US = {
 # their hash and is ignored (traffic = null) once they have changed.
 KERNEL_SOURCES = ("qgemm_stream.hip", "qgemm_stream_lds.hip", "qgemm_tile.hip", "qgemm_device.h")       # the GEMM kernels' own sources
 MEASURED_TRAFFIC = {
-    "llama7b_mlp_decode": {"sources_sha256": "40cb961e0012f8e595e886c311c0176060b8df2f1b8936fc77c9eb0b9c79dfa3",
-                           "bytes_per_launch": 241690828},   # fetch 233.84 MB + write 7.85 MB
+    "llama7b_mlp_decode": {"sources_sha256": "17b57b22ebfb6b33c08c8d656e7ae452230ad5abd3db5cca05e4917b5753519b",
+                           "bytes_per_launch": 241686016},   # fetch 233.86 MB + write 7.83 MB
 }
 
 

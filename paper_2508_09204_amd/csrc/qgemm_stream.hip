@@ -53,18 +53,39 @@ struct StreamSeg {
 // work-groups carry the most.  Lane e of every 16-lane row holds expert e and the sums are cross-lane
 // reductions, so the deal costs a few dozen instructions; every work-group runs the same arithmetic on the
 // same inputs and gets the same deal.
+// Reductions over a row of 16 lanes with data-parallel-primitive moves (vector instructions of a few cycles; a
+// shuffle through the LDS crossbar costs a hundred and these chains are serial): partner lane^1 and lane^2 inside a
+// quad, then the mirrored half row and the mirrored row, which pair lanes that already agree within their quad
+// and half row.  Every lane ends with the reduction of its row.
+template <int CTRL> static __device__ __forceinline__ int dpp_move(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+constexpr int DPP_QUAD_XOR1 = 0xB1, DPP_QUAD_XOR2 = 0x4E, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_MIRROR = 0x140;
 static __device__ __forceinline__ int row16_sum(int v) {
-#pragma unroll
-  for (int m = 1; m < 16; m <<= 1) v += __shfl_xor(v, m, 16);
+  v += dpp_move<DPP_QUAD_XOR1>(v);
+  v += dpp_move<DPP_QUAD_XOR2>(v);
+  v += dpp_move<DPP_ROW_HALF_MIRROR>(v);
+  v += dpp_move<DPP_ROW_MIRROR>(v);
   return v;
 }
 static __device__ __forceinline__ int row16_max(int v) {
-#pragma unroll
-  for (int m = 1; m < 16; m <<= 1) v = max(v, __shfl_xor(v, m, 16));
+  v = max(v, dpp_move<DPP_QUAD_XOR1>(v));
+  v = max(v, dpp_move<DPP_QUAD_XOR2>(v));
+  v = max(v, dpp_move<DPP_ROW_HALF_MIRROR>(v));
+  v = max(v, dpp_move<DPP_ROW_MIRROR>(v));
   return v;
 }
-
-static __device__ __forceinline__ uint32_t uni(uint32_t v) { return uint32_t(__builtin_amdgcn_readfirstlane(int(v))); }
+// Inclusive prefix sum over the 16 lanes of a row: shifts by 1, 2, 4, 8 lanes to the right, zero shifted in.
+template <int N> static __device__ __forceinline__ int row_shr_or_zero(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, 0x110 + N, 0xf, 0xf, true);
+}
+static __device__ __forceinline__ int row16_prefix_sum(int v) {
+  v += row_shr_or_zero<1>(v);
+  v += row_shr_or_zero<2>(v);
+  v += row_shr_or_zero<4>(v);
+  v += row_shr_or_zero<8>(v);
+  return v;
+}
 
 // Lane e (of every 16-lane row) fetches bucket e's bounds and expert e's descriptor, all in one round trip:
 // the kernel arguments live in memory that is slow to touch for the first time, and a chain of dependent
@@ -122,7 +143,8 @@ static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, 
   StreamSeg sg;
   sg.e = -1; sg.u0 = 0; sg.u1 = 0; sg.off_e = 0; sg.rows_e = 0;
   if (total <= 0) return sg;
-  int g = cost > 0 ? max(1, min(NU, int((long long)cost * G / total))) : 0;
+  // cost is at most a few hundred (price x passes) and G the number of compute units: the product fits 32 bits
+  int g = cost > 0 ? max(1, min(NU, int(unsigned(cost) * unsigned(G) / unsigned(total)))) : 0;
   int sum = row16_sum(g);
   // more than G (tiny shares rounded up to one): take from the largest
   for (int it = 0; it < MOQE_MAX_EXPERTS && sum > G; ++it) {
@@ -142,37 +164,34 @@ static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, 
     sum += 1;
   }
   // first work-group of each expert: exclusive prefix sum over the lanes of the row
-  int first = g;
-#pragma unroll
-  for (int m = 1; m < 16; m <<= 1) {
-    const int o = __shfl_up(first, m, 16);
-    if (e >= m) first += o;
-  }
-  first -= g;
+  const int first = row16_prefix_sum(g) - g;
   const bool here = g > 0 && wg >= first && wg < first + g;
   const unsigned long long who = __ballot(here) & 0xffffull;       // row 0 of the wave; at most one lane
   if (who == 0ull) return sg;
   const int el = __ffsll(who) - 1;
-  const int ge = __shfl(g, el, 64), fe = __shfl(first, el, 64);
+  // everything of the chosen expert is read from its lane into scalar registers (el is uniform)
+  auto from_lane = [&](int v) { return __builtin_amdgcn_readlane(v, el); };
+  const int ge = from_lane(g), fe = from_lane(first);
   const unsigned i = unsigned(wg - fe);
   sg.e = el;
-  sg.u0 = int(i * unsigned(NU) / unsigned(ge));                    // i < G and NU < 2^20: the products fit 32 bits
-  sg.u1 = int((i + 1u) * unsigned(NU) / unsigned(ge));
-  sg.off_e = __shfl(o0, el, 64);
-  sg.rows_e = __shfl(rows, el, 64);
-  // the chosen expert's descriptor, broadcast from its lane and made uniform
+  // NU = q ge + r units over ge work-groups: the first r take q + 1 (one division instead of two)
+  const unsigned q = unsigned(NU) / unsigned(ge), r = unsigned(NU) - q * unsigned(ge);
+  sg.u0 = int(i * q + min(i, r));
+  sg.u1 = sg.u0 + int(q) + (i < r ? 1 : 0);
+  sg.off_e = from_lane(o0);
+  sg.rows_e = from_lane(rows);
   const uint64_t w0 = reinterpret_cast<uint64_t>(mine_ex.w[0]), w1 = reinterpret_cast<uint64_t>(mine_ex.w[1]);
-  const uint64_t w0u = (uint64_t(uni(__shfl(uint32_t(w0 >> 32), el, 64))) << 32) | uni(__shfl(uint32_t(w0), el, 64));
-  const uint64_t w1u = (uint64_t(uni(__shfl(uint32_t(w1 >> 32), el, 64))) << 32) | uni(__shfl(uint32_t(w1), el, 64));
+  const uint64_t w0u = (uint64_t(uint32_t(from_lane(int(w0 >> 32)))) << 32) | uint32_t(from_lane(int(uint32_t(w0))));
+  const uint64_t w1u = (uint64_t(uint32_t(from_lane(int(w1 >> 32)))) << 32) | uint32_t(from_lane(int(uint32_t(w1))));
   sg.ex.w[0] = reinterpret_cast<const uint8_t*>(w0u);
   sg.ex.w[1] = reinterpret_cast<const uint8_t*>(w1u);
-  sg.ex.fmt = int(uni(__shfl(uint32_t(mine_ex.fmt), el, 64)));
-  sg.ex.gm = int(uni(__shfl(uint32_t(mine_ex.gm), el, 64)));
-  sg.ex.zc = int(uni(__shfl(uint32_t(mine_ex.zc), el, 64)));
-  sg.ex.asym = int(uni(__shfl(uint32_t(mine_ex.asym), el, 64)));
-  sg.ex.tile_bytes = uni(__shfl(mine_ex.tile_bytes, el, 64));
-  sg.ex.scale_off = uni(__shfl(mine_ex.scale_off, el, 64));
-  sg.ex.zero_off = uni(__shfl(mine_ex.zero_off, el, 64));
+  sg.ex.fmt = from_lane(mine_ex.fmt);
+  sg.ex.gm = from_lane(mine_ex.gm);
+  sg.ex.zc = from_lane(mine_ex.zc);
+  sg.ex.asym = from_lane(mine_ex.asym);
+  sg.ex.tile_bytes = uint32_t(from_lane(int(mine_ex.tile_bytes)));
+  sg.ex.scale_off = uint32_t(from_lane(int(mine_ex.scale_off)));
+  sg.ex.zero_off = uint32_t(from_lane(int(mine_ex.zero_off)));
   return sg;
 }
 

@@ -112,6 +112,10 @@ template <int FMT> static __device__ __forceinline__ FragK<FMT> frag_constants()
 }
 
 static __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t orv) { return (x & mask) | orv; }
+// A value the optimizer must take as it is (no instruction is emitted).  Two-field codes are put together as
+// (a & m0) | ((b & m1) | pattern): seen whole, the expression is regrouped into two ANDs and a three-input OR;
+// with the inner part kept apart both halves stay and-or instructions, one instruction less per code pair.
+static __device__ __forceinline__ uint32_t kept(uint32_t v) { asm("" : "+v"(v)); return v; }
 
 template <int SH> static __device__ __forceinline__ uint32_t shift_by(uint32_t v) {
   if constexpr (SH >= 0) return v >> SH; else return v << (-SH);
@@ -143,17 +147,17 @@ static __device__ __forceinline__ bf16x8 frag(const uint32_t (&r)[Raw<FMT>::N], 
     const uint32_t lo = r[J / 2], hi = r[2];      // 0x4080 | c << 4: two low bits from `lo`, the high bit from `hi`
     constexpr int P0 = 4 * (J % 2);       // first 2-bit field of this step inside `lo`
     constexpr int Q0 = 4 * J;             // first 1-bit field of this step inside `hi`
-    d.x = and_or(shift_by<2 * (P0 + 0) - 4>(lo), k.m0, and_or(shift_by<Q0 + 0 - 6>(hi), k.m1, k.pat));
-    d.y = and_or(shift_by<2 * (P0 + 1) - 4>(lo), k.m0, and_or(shift_by<Q0 + 1 - 6>(hi), k.m1, k.pat));
-    d.z = and_or(shift_by<2 * (P0 + 2) - 4>(lo), k.m0, and_or(shift_by<Q0 + 2 - 6>(hi), k.m1, k.pat));
-    d.w = and_or(shift_by<2 * (P0 + 3) - 4>(lo), k.m0, and_or(shift_by<Q0 + 3 - 6>(hi), k.m1, k.pat));
+    d.x = and_or(shift_by<2 * (P0 + 0) - 4>(lo), k.m0, kept(and_or(shift_by<Q0 + 0 - 6>(hi), k.m1, k.pat)));
+    d.y = and_or(shift_by<2 * (P0 + 1) - 4>(lo), k.m0, kept(and_or(shift_by<Q0 + 1 - 6>(hi), k.m1, k.pat)));
+    d.z = and_or(shift_by<2 * (P0 + 2) - 4>(lo), k.m0, kept(and_or(shift_by<Q0 + 2 - 6>(hi), k.m1, k.pat)));
+    d.w = and_or(shift_by<2 * (P0 + 3) - 4>(lo), k.m0, kept(and_or(shift_by<Q0 + 3 - 6>(hi), k.m1, k.pat)));
   } else {  // FMT_N6: 0x4200 | c << 1: four low bits from `w`, two high bits from `hi`
     const uint32_t w = r[J], hi = r[4 + J / 2];
     constexpr int P0 = 4 * (J % 2);
-    d.x = and_or(shift_by<-1>(w), k.m0, and_or(shift_by<2 * (P0 + 0) - 5>(hi), k.m1, k.pat));
-    d.y = and_or(shift_by<3>(w), k.m0, and_or(shift_by<2 * (P0 + 1) - 5>(hi), k.m1, k.pat));
-    d.z = and_or(shift_by<7>(w), k.m0, and_or(shift_by<2 * (P0 + 2) - 5>(hi), k.m1, k.pat));
-    d.w = and_or(shift_by<11>(w), k.m0, and_or(shift_by<2 * (P0 + 3) - 5>(hi), k.m1, k.pat));
+    d.x = and_or(shift_by<-1>(w), k.m0, kept(and_or(shift_by<2 * (P0 + 0) - 5>(hi), k.m1, k.pat)));
+    d.y = and_or(shift_by<3>(w), k.m0, kept(and_or(shift_by<2 * (P0 + 1) - 5>(hi), k.m1, k.pat)));
+    d.z = and_or(shift_by<7>(w), k.m0, kept(and_or(shift_by<2 * (P0 + 2) - 5>(hi), k.m1, k.pat)));
+    d.w = and_or(shift_by<11>(w), k.m0, kept(and_or(shift_by<2 * (P0 + 3) - 5>(hi), k.m1, k.pat)));
   }
   return __builtin_bit_cast(bf16x8, d);
 }

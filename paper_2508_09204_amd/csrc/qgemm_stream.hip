@@ -134,7 +134,7 @@ static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, 
   // Relative time of one weight tile row: mostly its bytes, plus what unpacking costs (measured per format on
   // MI355X), a little more when the bucket needs both 16-row blocks; times the passes over the bucket.
   const int f = mine_ex.fmt;
-  const int per_tile = f == FMT_I8 ? 28 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 26 : (f == FMT_N4 ? 20 : 27)));
+  const int per_tile = f == FMT_I8 ? 28 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 26 : (f == FMT_N4 ? 20 : 24)));
   const int passes = (rows + STREAM_ROWS - 1) / STREAM_ROWS;
   const int last = rows - (passes - 1) * STREAM_ROWS;              // rows of the last pass
   const int parts = (passes - 1) * 5 + (last > 16 ? 5 : 4);        // a pass with two blocks counts 5/4

@@ -85,6 +85,9 @@ static int32_t check_qmat_format(const moqe_qmat& m, PackedInfo* pi, const char*
     return set_error(MOQE_E_FORMAT, "%s: unsupported format bits=%d group=%d symmetric=%d act_mode=%d", who, m.bits,
                      m.group, m.symmetric, m.act_mode);
   }
+  // the kernels address a packed matrix with 32-bit byte offsets from its start
+  if (pi->total >= (size_t(1) << 32))
+    return set_error(MOQE_E_SHAPE, "%s: packed matrix %d x %d takes %zu bytes, the limit is 4 GiB", who, m.n, m.k, pi->total);
   return MOQE_OK;
 }
 

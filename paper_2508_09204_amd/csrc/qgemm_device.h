@@ -34,33 +34,45 @@ template <> struct Raw<FMT_N4>   { static constexpr int N = 4; static constexpr 
 template <> struct Raw<FMT_N3>   { static constexpr int N = 3; static constexpr int PF = 4; };
 template <> struct Raw<FMT_N6>   { static constexpr int N = 6; static constexpr int PF = 2; };
 
-// A pointer the compiler cannot trace back to a kernel argument (one put together from integers, say) is
-// loaded through the flat path, and a pending flat load turns every later wait for memory into a wait for
-// ALL memory operations: a ring of loads in flight drains at each use.  Such pointers are cast to the
-// global address space once; loads through them are global loads with exact, in-order wait counts.
-#define MOQE_GLOBAL __attribute__((address_space(1)))
-typedef const MOQE_GLOBAL uint8_t* gbytes;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-static __device__ __forceinline__ gbytes as_global(const uint8_t* p) { return (gbytes)p; }
-template <typename T> static __device__ __forceinline__ T load_global(gbytes p) { return *(const MOQE_GLOBAL T*)p; }
 
-// The packed codes of one 16 x 128 tile, this lane's share, through a global-address-space pointer.
+// A buffer descriptor over a packed blob (a blob is smaller than 4 GiB): a load through it takes a scalar byte
+// offset and a per-lane byte offset of 32 bits each, so a tile's address costs a scalar multiply-add and no
+// 64-bit arithmetic in the vector unit (a global load of base + uniform offset + lane offset was compiled to four
+// to six 64-bit vector additions per tile).  It also keeps such loads out of the flat path: a pointer that the
+// compiler cannot trace back to a kernel argument (one put together from integers, say) is loaded with flat
+// instructions, and a pending flat load turns every later wait for memory into a wait for ALL memory operations,
+// so that a ring of loads in flight drains at each use.
+typedef __amdgpu_buffer_rsrc_t buf_rsrc;
+static __device__ __forceinline__ buf_rsrc blob_rsrc(const uint8_t* p) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p), 0, -1, 0x00020000);   // raw buffer, 32-bit data format
+}
+static __device__ __forceinline__ u32x4 buf_load128(buf_rsrc rs, int voff, uint32_t soff) {
+  return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, int(soff), 0));
+}
+static __device__ __forceinline__ u32x2 buf_load64(buf_rsrc rs, int voff, uint32_t soff) {
+  return __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rs, voff, int(soff), 0));
+}
+static __device__ __forceinline__ uint32_t buf_load32(buf_rsrc rs, int voff, uint32_t soff) {
+  return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, int(soff), 0));
+}
+
+// The packed codes of the tile that starts `soff` bytes into the blob, this lane's share.
 template <int FMT>
-static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], gbytes tile, int lane) {
+static __device__ __forceinline__ void load_raw(uint32_t (&r)[Raw<FMT>::N], buf_rsrc rs, uint32_t soff, int lane) {
   if constexpr (FMT == FMT_I8 || FMT == FMT_I8A8) {
-    const u32x4 a = load_global<u32x4>(tile + lane * 16), b = load_global<u32x4>(tile + 1024 + lane * 16);
+    const u32x4 a = buf_load128(rs, lane * 16, soff), b = buf_load128(rs, lane * 16 + 1024, soff);
     r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w; r[4] = b.x; r[5] = b.y; r[6] = b.z; r[7] = b.w;
   } else if constexpr (FMT == FMT_N4) {
-    const u32x4 a = load_global<u32x4>(tile + lane * 16);
+    const u32x4 a = buf_load128(rs, lane * 16, soff);
     r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w;
   } else if constexpr (FMT == FMT_N3) {
-    const u32x2 a = load_global<u32x2>(tile + lane * 8);
+    const u32x2 a = buf_load64(rs, lane * 8, soff);
     r[0] = a.x; r[1] = a.y;
-    r[2] = load_global<uint32_t>(tile + 512 + lane * 4);
+    r[2] = buf_load32(rs, lane * 4 + 512, soff);
   } else {
-    const u32x4 a = load_global<u32x4>(tile + lane * 16);
-    const u32x2 b = load_global<u32x2>(tile + 1024 + lane * 8);
+    const u32x4 a = buf_load128(rs, lane * 16, soff);
+    const u32x2 b = buf_load64(rs, lane * 8 + 1024, soff);
     r[0] = a.x; r[1] = a.y; r[2] = a.z; r[3] = a.w; r[4] = b.x; r[5] = b.y;
   }
 }

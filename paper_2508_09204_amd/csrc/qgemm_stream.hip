@@ -134,10 +134,10 @@ static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, 
   // Relative time of one weight tile row: mostly its bytes, plus what unpacking costs (measured per format on
   // MI355X), a little more when the bucket needs both 16-row blocks; times the passes over the bucket.
   const int f = mine_ex.fmt;
-  const int per_tile = f == FMT_I8 ? 28 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 26 : (f == FMT_N4 ? 20 : 24)));
+  const int per_tile = f == FMT_I8 ? 30 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 25 : (f == FMT_N4 ? 20 : 25)));
   const int passes = (rows + STREAM_ROWS - 1) / STREAM_ROWS;
   const int last = rows - (passes - 1) * STREAM_ROWS;              // rows of the last pass
-  const int parts = (passes - 1) * 5 + (last > 16 ? 5 : 4);        // a pass with two blocks counts 5/4
+  const int parts = (passes - 1) * 21 + (last > 16 ? 21 : 16);     // a pass with two blocks counts 21/16
   const int cost = mine ? per_tile * parts : 0;                    // small integers
   const int total = row16_sum(cost);
   StreamSeg sg;
@@ -276,12 +276,12 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
   float sc[D][KPW][GP1];                                // group scales; per-channel formats: [0] of tile 0 is the row's scale
   uint32_t zp[D][KPW];
   const uint32_t tile_bytes = ex.tile_bytes, scale_off = ex.scale_off, zero_off = ex.zero_off;
-  // the schedule hands the blob addresses over as integers: typed as global memory here (see as_global)
-  const gbytes blob0 = as_global(ex.w[0]);
-  const gbytes blob1 = as_global(ex.w[GATEUP ? 1 : 0]);
+  // weights are read through buffer descriptors: scalar tile offset + lane offset, no vector address arithmetic
+  const buf_rsrc blob0 = blob_rsrc(ex.w[0]);
+  const buf_rsrc blob1 = blob_rsrc(ex.w[GATEUP ? 1 : 0]);
   int cur_i = 0;
   // derived from the position: which blob, first tile index of the row's KPW tiles, tile row
-  gbytes cur_blob = blob0;
+  buf_rsrc cur_blob = blob0;
   uint32_t cur_t0 = 0u;
   int cur_nt = u0;
   const int cur_tmax = max(nkt - 1, 0);                  // tiles the wave does not have repeat its last one (or the row's last)
@@ -296,24 +296,22 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
     cur_derive();
   };
   auto issue_tile = [&](int d, int t) {                  // d, t are compile-time constants at every call
-    const uint32_t tl = cur_t0 + uint32_t(min(t, cur_tmax));
-    load_raw<FMT>(raw[d][t], cur_blob + size_t(tl) * tile_bytes, lane);
+    const uint32_t tl = cur_t0 + uint32_t(min(t, cur_tmax));                      // uniform; byte offsets below fit 32 bits
+    load_raw<FMT>(raw[d][t], cur_blob, tl * tile_bytes, lane);
     if constexpr (GPT > 0) {
-      const gbytes sp = cur_blob + scale_off + size_t(tl) * (16 * GPT * 4) + lr * (GPT * 4);
       // zero-points: the aligned dword that holds the lane's byte(s); shifted down where it is used (a
       // narrower load would get its zero-extension placed right behind the load, which waits for the ring)
-      const gbytes zq = cur_blob + zero_off + size_t(tl) * (16 * GPT) + ((lr * GPT) & ~3);
-      zp[d][t] = load_global<uint32_t>(zq);
+      zp[d][t] = buf_load32(cur_blob, (lr * GPT) & ~3, zero_off + tl * uint32_t(16 * GPT));
       if constexpr (GPT == 1) {
-        sc[d][t][0] = load_global<float>(sp);
+        sc[d][t][0] = __uint_as_float(buf_load32(cur_blob, lr * 4, scale_off + tl * 64u));
       } else {
-        const f32x2 v = load_global<f32x2>(sp);
-        sc[d][t][0] = v.x; sc[d][t][GP1 - 1] = v.y;
+        const u32x2 v = buf_load64(cur_blob, lr * 8, scale_off + tl * 128u);
+        sc[d][t][0] = __uint_as_float(v.x); sc[d][t][GP1 - 1] = __uint_as_float(v.y);
       }
     } else {
       zp[d][t] = 0u;
       sc[d][t][0] = 1.f;
-      if (t == 0) sc[d][t][0] = load_global<float>(cur_blob + scale_off + size_t(cur_nt * 16 + lr) * 4);
+      if (t == 0) sc[d][t][0] = __uint_as_float(buf_load32(cur_blob, lr * 4, scale_off + uint32_t(cur_nt) * 64u));
     }
   };
   // ---- this wave's slice of the activations, as matrix-core operands ---------------------------------------------

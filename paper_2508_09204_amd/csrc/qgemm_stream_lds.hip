@@ -89,6 +89,8 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
     sv[0] = active_task && nt[0] < NT; sv[1] = active_task && nt[1] < NT;
     blob[0] = blob[1] = ex.w[0];
   }
+  // weights are read through buffer descriptors: scalar tile offset + lane offset, no vector address arithmetic
+  const buf_rsrc rsrc[NS] = {blob_rsrc(blob[0]), blob_rsrc(blob[1])};
   const int slice_tiles = (KT + wk - 1) / wk;              // k-tiles per slice (last slice may be shorter)
   const int kt0 = ks * slice_tiles, kt1 = min(KT, kt0 + slice_tiles);
   constexpr int KC = 128;                                  // columns staged per slice and step
@@ -118,7 +120,8 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
     // step offset that stays inside the unit's slice.  Nothing is zero-filled: rows past the end of
     // the bucket repeat its last row (their products land in result rows that are never stored), and
     // steps past the end of a slice re-read its last tile and are not multiplied.
-    const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
+    // the activation matrix is smaller than 4 GiB (checked before the launch): 32-bit offsets through a descriptor
+    const buf_rsrc a_rsrc = blob_rsrc(reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a));
     uint32_t uoff[AU_MAX];
     int ukend[AU_MAX];
 #pragma unroll
@@ -142,7 +145,7 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
       const int koff = c * KC * EB;
 #pragma unroll
       for (int i = 0; i < AU_MAX; ++i)
-        areg[i] = *reinterpret_cast<const u32x4*>(abase + size_t(uoff[i]) + min(koff, ukend[i]));
+        areg[i] = buf_load128(a_rsrc, int(uoff[i] + uint32_t(min(koff, ukend[i]))), 0u);
     };
     auto a_store = [&](uint8_t* dst) {     // registers -> LDS; dst = buffer + k-tile position inside the chunk
 #pragma unroll
@@ -171,18 +174,16 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
       const int kt = min(kt_want, kt_last);
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        const size_t t = size_t(nt_ld[s]) * KT + kt;
-        load_raw<FMT>(raw[p][s], blob[s] + t * ex.tile_bytes, lane);
+        const uint32_t t = uint32_t(nt_ld[s]) * uint32_t(KT) + uint32_t(kt);          // uniform; byte offsets fit 32 bits
+        load_raw<FMT>(raw[p][s], rsrc[s], t * ex.tile_bytes, lane);
         if constexpr (GPT > 0) {          // group formats are asymmetric: scale and zero-point per group
-          const float* sp = reinterpret_cast<const float*>(blob[s] + ex.scale_off) + (t * 16 + lr) * GPT;
-          const uint8_t* zq = blob[s] + ex.zero_off + (t * 16 + lr) * GPT;
           if constexpr (GPT == 1) {
-            sc[p][s][0] = sp[0];
-            zp[p][s] = uint32_t(zq[0]);
+            sc[p][s][0] = __uint_as_float(buf_load32(rsrc[s], lr * 4, ex.scale_off + t * 64u));
+            zp[p][s] = uint32_t(__builtin_amdgcn_raw_buffer_load_b8(rsrc[s], lr, int(ex.zero_off + t * 16u), 0));
           } else {
-            float2 v = *reinterpret_cast<const float2*>(sp);
-            sc[p][s][0] = v.x; sc[p][s][1] = v.y;
-            zp[p][s] = uint32_t(*reinterpret_cast<const uint16_t*>(zq));
+            const u32x2 v = buf_load64(rsrc[s], lr * 8, ex.scale_off + t * 128u);
+            sc[p][s][0] = __uint_as_float(v.x); sc[p][s][1] = __uint_as_float(v.y);
+            zp[p][s] = uint32_t(__builtin_amdgcn_raw_buffer_load_b16(rsrc[s], lr * 2, int(ex.zero_off + t * 32u), 0));
           }
         }
       }

@@ -85,7 +85,11 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
   }
 
   // ---- activation rows this thread copies per k-step ------------------------------------------------
+  // activations and weights are read through buffer descriptors (each matrix is smaller than 4 GiB, checked before
+  // the launch): 32-bit offsets, a scalar one and a per-lane one, and no 64-bit address arithmetic in the vector unit
   const uint8_t* abase = reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a);
+  const buf_rsrc a_rsrc = blob_rsrc(abase);
+  const buf_rsrc w_rsrc[2] = {blob_rsrc(ex.w[0]), blob_rsrc(ex.w[GATEUP ? 1 : 0])};
   uint32_t a_off[A_ITERS];
   const int a_unit = tid % A_UNITS, a_row0 = tid / A_UNITS;
   uint32_t a_taps[CONV ? A_ITERS : 1];       // convolution: bit t set = filter tap t of the row's pixel lies inside its image
@@ -150,7 +154,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
     } else {
       const uint32_t koff = uint32_t(min(kt, KT - 1)) * (128 * EB);
 #pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) a_reg[i] = *reinterpret_cast<const u32x4*>(abase + (a_off[i] + koff));
+      for (int i = 0; i < A_ITERS; ++i) a_reg[i] = buf_load128(a_rsrc, int(a_off[i]), koff);
     }
   };
   auto a_store = [&](uint8_t* buf) {
@@ -176,18 +180,34 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
 #pragma unroll
     for (int b = 0; b < TNB; ++b) {
       const uint32_t t = tbase[b] + kt;
-      load_raw<FMT>(raw[p][b], blob[b] + t * ex.tile_bytes, lane);
-      if constexpr (GPT > 0) {
-        const uint8_t* sp = blob[b] + (ex.scale_off + t * uint32_t(16 * GPT * 4));
-        const uint8_t* zq = blob[b] + (ex.zero_off + t * uint32_t(16 * GPT));
-        // zero-points: the aligned dword holding the lane's byte(s), shifted down where it is used
-        if constexpr (GPT == 1) {
-          sc[p][b][0] = *reinterpret_cast<const float*>(sp + uint32_t(lr) * 4u);
-          zp[p][b] = *reinterpret_cast<const uint32_t*>(zq + (uint32_t(lr) & ~3u));
-        } else {
-          const float2 v = *reinterpret_cast<const float2*>(sp + uint32_t(lr) * 8u);
-          sc[p][b][0] = v.x; sc[p][b][1] = v.y;
-          zp[p][b] = *reinterpret_cast<const uint32_t*>(zq + ((uint32_t(lr) * 2u) & ~3u));
+      if constexpr (CONV) {
+        // plain loads: with the descriptors the convolution's kernel ran out of registers (spills inside its loops)
+        load_raw<FMT>(raw[p][b], blob[b] + t * ex.tile_bytes, lane);
+        if constexpr (GPT > 0) {
+          const uint8_t* sp = blob[b] + (ex.scale_off + t * uint32_t(16 * GPT * 4));
+          const uint8_t* zq = blob[b] + (ex.zero_off + t * uint32_t(16 * GPT));
+          if constexpr (GPT == 1) {
+            sc[p][b][0] = *reinterpret_cast<const float*>(sp + uint32_t(lr) * 4u);
+            zp[p][b] = *reinterpret_cast<const uint32_t*>(zq + (uint32_t(lr) & ~3u));
+          } else {
+            const float2 v = *reinterpret_cast<const float2*>(sp + uint32_t(lr) * 8u);
+            sc[p][b][0] = v.x; sc[p][b][1] = v.y;
+            zp[p][b] = *reinterpret_cast<const uint32_t*>(zq + ((uint32_t(lr) * 2u) & ~3u));
+          }
+        }
+      } else {
+        const buf_rsrc rs = w_rsrc[GATEUP ? (b >> 1) : 0];
+        load_raw<FMT>(raw[p][b], rs, t * ex.tile_bytes, lane);
+        if constexpr (GPT > 0) {
+          // zero-points: the aligned dword holding the lane's byte(s), shifted down where it is used
+          if constexpr (GPT == 1) {
+            sc[p][b][0] = __uint_as_float(buf_load32(rs, lr * 4, ex.scale_off + t * 64u));
+            zp[p][b] = buf_load32(rs, lr & ~3, ex.zero_off + t * 16u);
+          } else {
+            const u32x2 v = buf_load64(rs, lr * 8, ex.scale_off + t * 128u);
+            sc[p][b][0] = __uint_as_float(v.x); sc[p][b][1] = __uint_as_float(v.y);
+            zp[p][b] = buf_load32(rs, (lr * 2) & ~3, ex.zero_off + t * 32u);
+          }
         }
       }
     }

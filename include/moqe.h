@@ -26,7 +26,8 @@
  *  - Pointers named in "device" comments are DEVICE pointers owned by the caller; the
  *    library does not allocate, free or retain device memory, with one exception: an expert
  *    cache (moqe_cache_create) owns the device slots it allocates until moqe_cache_destroy.
- *    An activation matrix (rows x features, bf16) must stay below 4 GiB.  Descriptor structs
+ *    An activation matrix (rows x features, bf16) and a packed weight matrix must each stay below 4 GiB
+ *    (the kernels address them with 32-bit byte offsets; larger ones are refused with MOQE_E_SHAPE).  Descriptor structs
  *    (moqe_qmat, moqe_router, moqe_nlp_router, moqe_cv_router, moqe_block, moqe_aux) and arrays of them are HOST memory,
  *    read during the call only.  Scratch memory is a caller-provided device workspace
  *    whose size comes from the matching *_workspace_bytes query; it must be 256-byte

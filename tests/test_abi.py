@@ -142,6 +142,12 @@ def test_grouped_qgemm_argument_errors(mq):
     assert call(FAKE, FAKE, FAKE, 4, 1, a8, 1, FAKE, 1, FAKE, need - 1) == -4
     assert call(FAKE, FAKE, FAKE, 4, 1, a8, 1, FAKE, 1, FAKE, need) == 0
     assert call(FAKE, FAKE, FAKE, 0, 1, ex, 2, FAKE, 1, None, 0) == 0            # empty batch: nothing to do
+    # a packed matrix is addressed with 32-bit byte offsets: 4 GiB or more is refused (the largest that fits is accepted)
+    big = (mq._QMat * 1)(_qmat(mq, n=65536, k=65536, bits=8, group=0, sym=1))
+    assert call(FAKE, FAKE, FAKE, 4, 1, big, 1, FAKE, 1, None, 0) == -2
+    assert b"4 GiB" in lib.moqe_last_error_string()
+    ok = (mq._QMat * 1)(_qmat(mq, n=65536, k=65536, bits=4, group=0, sym=1))
+    assert call(FAKE, FAKE, FAKE, 4, 1, ok, 1, FAKE, 1, None, 0) == 0
 
 
 def test_route_and_forward_argument_errors(mq):

@@ -38,7 +38,8 @@ constexpr int STREAM_ROWS = 32;            // bucket rows per pass (two 16-row b
 constexpr int BMT = 4;                     // (tile rows per batch) x (16-row blocks): results exchanged per barrier
 constexpr int PART_BYTES = 2 * BMT * SW * 64 * 16;     // two buffers of per-wave partial sums
 constexpr int PERM_LDS_BYTES = SW * 64 * 4;           // a private copy of the permutation per wave (launches that bucket themselves)
-constexpr int STREAM_LDS_BYTES = PART_BYTES + PERM_LDS_BYTES;
+constexpr int ROWTAB_BYTES = STREAM_ROWS * 8;          // per row of the pass: where its result goes, its activation scale
+constexpr int STREAM_LDS_BYTES = PART_BYTES + PERM_LDS_BYTES + ROWTAB_BYTES;
 
 // ---- which expert and which of its weight tiles a work-group streams ---------------------------------
 struct StreamSeg {
@@ -134,7 +135,7 @@ static __device__ __forceinline__ StreamSeg stream_schedule(const GemmArgs& ga, 
   // Relative time of one weight tile row: mostly its bytes, plus what unpacking costs (measured per format on
   // MI355X), a little more when the bucket needs both 16-row blocks; times the passes over the bucket.
   const int f = mine_ex.fmt;
-  const int per_tile = f == FMT_I8 ? 30 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 25 : (f == FMT_N4 ? 20 : 25)));
+  const int per_tile = f == FMT_I8 ? 31 : (f == FMT_I8A8 ? 24 : (f == FMT_N6 ? 25 : (f == FMT_N4 ? 20 : 25)));
   const int passes = (rows + STREAM_ROWS - 1) / STREAM_ROWS;
   const int last = rows - (passes - 1) * STREAM_ROWS;              // rows of the last pass
   const int parts = (passes - 1) * 21 + (last > 16 ? 21 : 16);     // a pass with two blocks counts 21/16
@@ -342,6 +343,16 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
       const int m = pass0 + min(mt * 16 + lq * 4 + r, rows_here - 1);
       out_row[mt][r] = out_row[mt][r] * T + mod_t(m);
     }
+  }
+  // The epilogue picks a row's destination by a run-time register number.  Held in registers, the eight values
+  // end up as an indexed array in scratch memory, and the one scratch load per batch makes the epilogue wait for
+  // every load in flight (loads return in order), i.e. for the whole weight ring.  They go through LDS instead.
+  int2* const row_tab = reinterpret_cast<int2*>(lds + PART_BYTES + PERM_LDS_BYTES);
+  if (wave == 0 && lr == 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) row_tab[mt * 16 + lq * 4 + r] = make_int2(out_row[mt][r], __float_as_int(sx[mt][r]));
   }
   load_a();
   cur_derive();
@@ -593,14 +604,10 @@ static __device__ __forceinline__ void stream_pass(const GemmArgs& ga, const Exp
 #pragma unroll
               for (int rr = 0; rr < RPW; ++rr) {
                 const int r = r0 + rr;
-                // this register's result row, picked without dynamic register indexing
-                int orow = out_row[0][0];
-                float osx = sx[0][0];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                  for (int q = 0; q < 4; ++q)
-                    if (mt_dyn == mt && r == q) { orow = out_row[mt][q]; osx = sx[mt][q]; }
+                // this register's result row (written before the batch's barrier, by the first wave)
+                const int2 rt = row_tab[mt_dyn * 16 + lq * 4 + r];
+                const int orow = rt.x;
+                const float osx = __int_as_float(rt.y);
                 float val[NV];
 #pragma unroll
                 for (int s = 0; s < NV; ++s) {

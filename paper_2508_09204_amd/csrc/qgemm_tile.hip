@@ -343,6 +343,9 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
   auto step = [&](int kt, int p) {
     compute(p, lds + p * (TBM * T_SLOT));
     issue_w(p, kt + 2);
+    // the stored activations were requested a k-step ago; their wait must stay BEHIND the weight requests above,
+    // or it is a wait for everything in flight (the convolution's masking of the loaded words was moved up otherwise)
+    __builtin_amdgcn_sched_barrier(0);
     a_store(lds + (p ^ 1) * (TBM * T_SLOT));       // k-step kt+1; that buffer was last read in step kt-1
     a_fetch(kt + 2);
     __syncthreads();

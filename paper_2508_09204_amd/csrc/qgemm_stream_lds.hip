@@ -210,12 +210,15 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
           }
         }
       } else {
-        // Operands of the activations are read from LDS where they are used (once per weight
-        // stream) instead of being held for the whole tile: LDS has bandwidth to spare, registers
-        // are what limits the depth of the weight prefetch.
-        auto a_op = [&](int mt, int j) {
-          return *reinterpret_cast<const u32x4*>(arow0 + mt * 16 * A_SLOT + (((j * 4 + lq) ^ lr) * 16));
-        };
+        // The operands of the activations are read from LDS once per k-tile, all of them at the top and without a
+        // branch around them (rows past the end of the bucket repeat its last row), and meet both weight streams:
+        // read where they were used, inside the per-block branches, every read was followed by a wait for it.
+        u32x4 aop[MT][4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            aop[mt][j] = *reinterpret_cast<const u32x4*>(arow0 + mt * 16 * A_SLOT + (((j * 4 + lq) ^ lr) * 16));
         f32x4 xs[MT][GPT ? GPT : 1];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
@@ -226,7 +229,7 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
             if (mt * 16 < rows_here) {
-              const u32x4 a0 = a_op(mt, 0), a1 = a_op(mt, 1), a2 = a_op(mt, 2), a3 = a_op(mt, 3);
+              const u32x4 a0 = aop[mt][0], a1 = aop[mt][1], a2 = aop[mt][2], a3 = aop[mt][3];
               const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
               if (s == 0) {                 // row sums of the activations over the tile's groups, once per tile
                 if constexpr (GM == GM_PC) {

@@ -48,8 +48,8 @@ static __device__ __forceinline__ int a_unit_pos(int row, int unit) { return (un
 static constexpr int LDS_BYTES = 2 * 8 * ROWS * A_SLOT;
 
 template <int FMT, int GM, bool GATEUP, int WK>
-static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const ExpertDev& ex, const int e, const int wgi,
-                                                   uint8_t* lds) {
+static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const ExpertDev& ex, const int off_e, const int M_e,
+                                                   const int wgi, uint8_t* lds) {
   constexpr bool A8 = (FMT == FMT_I8A8);
   // tiles in flight per stream (a deeper ring was measured and bought nothing)
   constexpr int PF = 2;
@@ -69,8 +69,6 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
   const int T = ga.T;
   constexpr int wk = WK;
   constexpr int WN = WAVES / WK;                // tasks per work-group
-  const int off_e = ga.offsets[e];
-  const int M_e = (ga.offsets[e + 1] - off_e) * T;
   if (M_e <= 0 || M_e < ga.min_rows || M_e > ga.max_rows) return;     // uniform over the work-group (one expert per work-group)
 
   const int ks = wave % wk;
@@ -124,36 +122,53 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
     const buf_rsrc a_rsrc = blob_rsrc(reinterpret_cast<const uint8_t*>(A8 ? static_cast<const void*>(ga.a_q) : ga.a));
     uint32_t uoff[AU_MAX];
     int ukend[AU_MAX];
+    int32_t src_row[AU_MAX];               // source row of the unit in the activation matrix
+#pragma unroll
+    for (int i = 0; i < AU_MAX; ++i) {
+      const int u = tid + i * nthreads;
+      const int row = (u % (ROWS * upr)) / upr;
+      src_row[i] = off_e * T + pass0 + min(row, rows_here - 1);
+    }
+    if constexpr (!A8) {
+      if (ga.a_perm != nullptr) {          // uniform; all gather indices requested before any of them is used
+        int32_t g[AU_MAX];
+#pragma unroll
+        for (int i = 0; i < AU_MAX; ++i) {
+          const int mc = src_row[i] - off_e * T;
+          g[i] = ga.a_perm[off_e + (T == 1 ? mc : mc / T)];
+        }
+#pragma unroll
+        for (int i = 0; i < AU_MAX; ++i) {
+          const int mc = src_row[i] - off_e * T;
+          src_row[i] = T == 1 ? g[i] : g[i] * T + (mc % T);
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < AU_MAX; ++i) {
       const int u = tid + i * nthreads;
       uoff[i] = 0u; ukend[i] = 0;
       if (ALL_STAGE || u < n_units) {
-        const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
+        const int sl = u / (ROWS * upr), cu = u % upr;
         const int sk0 = min(sl * slice_tiles, KT - 1), sk1 = min(KT, sl * slice_tiles + slice_tiles);
-        const int m = pass0 + min(row, rows_here - 1);
-        size_t src;
-        if constexpr (A8) src = size_t(off_e) * T + m;
-        else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
-        else src = size_t(off_e) * T + m;
-        uoff[i] = uint32_t((src * size_t(ga.k) + size_t(sk0) * 128) * EB + cu * 16);
+        uoff[i] = uint32_t((size_t(src_row[i]) * size_t(ga.k) + size_t(sk0) * 128) * EB + cu * 16);
         ukend[i] = max(sk1 - sk0 - 1, 0) * 128 * EB;      // offset of the slice's last tile
       }
     }
-    u32x4 areg[AU_MAX];
-    auto a_fetch = [&](int c) {       // global -> registers, k-tile c of every slice
+    u32x4 areg[2][AU_MAX];                 // two sets: a k-tile is requested one step before it is stored
+    auto a_fetch = [&](int set, int c) {   // global -> registers, k-tile c of every slice
       const int koff = c * KC * EB;
 #pragma unroll
       for (int i = 0; i < AU_MAX; ++i)
-        areg[i] = buf_load128(a_rsrc, int(uoff[i] + uint32_t(min(koff, ukend[i]))), 0u);
+        areg[set][i] = buf_load128(a_rsrc, int(uoff[i] + uint32_t(min(koff, ukend[i]))), 0u);
     };
-    auto a_store = [&](uint8_t* dst) {     // registers -> LDS; dst = buffer + k-tile position inside the chunk
+    auto a_store = [&](int set, uint8_t* dst) {     // registers -> LDS; dst = buffer + k-tile position inside the chunk
 #pragma unroll
       for (int i = 0; i < AU_MAX; ++i) {
         const int u = tid + i * nthreads;
         const int sl = u / (ROWS * upr), rem = u % (ROWS * upr), row = rem / upr, cu = rem % upr;
         if (ALL_STAGE || u < n_units)
-          *reinterpret_cast<u32x4*>(dst + (sl * CH * ROWS + row) * A_SLOT + a_unit_pos(row, cu)) = areg[i];
+          *reinterpret_cast<u32x4*>(dst + (sl * CH * ROWS + row) * A_SLOT + a_unit_pos(row, cu)) = areg[set][i];
       }
     };
 
@@ -168,7 +183,7 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
 
     uint32_t raw[PF][NS][NR];
     float sc[PF][NS][GPT ? GPT : 1];
-    uint32_t zp[PF][NS];
+    uint16_t zp[PF][NS];      // as loaded: widened where it is used, so that nothing between request and use touches it
 
     auto issue_w = [&](int p, int kt_want) {
       const int kt = min(kt_want, kt_last);
@@ -179,11 +194,11 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
         if constexpr (GPT > 0) {          // group formats are asymmetric: scale and zero-point per group
           if constexpr (GPT == 1) {
             sc[p][s][0] = __uint_as_float(buf_load32(rsrc[s], lr * 4, ex.scale_off + t * 64u));
-            zp[p][s] = uint32_t(__builtin_amdgcn_raw_buffer_load_b8(rsrc[s], lr, int(ex.zero_off + t * 16u), 0));
+            zp[p][s] = uint16_t(__builtin_amdgcn_raw_buffer_load_b8(rsrc[s], lr, int(ex.zero_off + t * 16u), 0));
           } else {
             const u32x2 v = buf_load64(rsrc[s], lr * 8, ex.scale_off + t * 128u);
             sc[p][s][0] = __uint_as_float(v.x); sc[p][s][1] = __uint_as_float(v.y);
-            zp[p][s] = uint32_t(__builtin_amdgcn_raw_buffer_load_b16(rsrc[s], lr * 2, int(ex.zero_off + t * 32u), 0));
+            zp[p][s] = uint16_t(__builtin_amdgcn_raw_buffer_load_b16(rsrc[s], lr * 2, int(ex.zero_off + t * 32u), 0));
           }
         }
       }
@@ -259,15 +274,15 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
                 v = mfma_bf16(a1, b1, v);
                 v = mfma_bf16(a2, b2, v);
                 v = mfma_bf16(a3, b3, v);
-                const float o = BASE + CM * float(zp[p][s] & 0xffu);
+                const float o = BASE + CM * float(uint32_t(zp[p][s]) & 0xffu);
                 const float scv = sc[p][s][0] * INV_CM;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) tot[s][mt][r] += scv * (v[r] - o * xs[mt][0][r]);
               } else {
                 f32x4 v0 = mfma_bf16(a1, b1, mfma_bf16(a0, b0, zero));
                 f32x4 v1 = mfma_bf16(a3, b3, mfma_bf16(a2, b2, zero));
-                const float o0 = BASE + CM * float(zp[p][s] & 0xffu);
-                const float o1 = BASE + CM * float((zp[p][s] >> 8) & 0xffu);
+                const float o0 = BASE + CM * float(uint32_t(zp[p][s]) & 0xffu);
+                const float o1 = BASE + CM * float((uint32_t(zp[p][s]) >> 8) & 0xffu);
                 const float s0 = sc[p][s][0] * INV_CM, s1 = sc[p][s][GPT == 2 ? 1 : 0] * INV_CM;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -281,29 +296,82 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
       }
     };
 
-    // ---- prologue: first weight tiles in flight, the first chunk of the activations into LDS ----
+    // What the epilogue needs from global memory is requested here, ahead of the tile loop, so that the end of the
+    // kernel waits for no load: the destination rows of the scatter, per-channel scales, the row scales of int8
+    // activations (rows past the end of the bucket take the last row's, and are never stored).
+    int32_t out_row[MT][4];
+    float sx_row[MT][4];
+    float pcs[NS] = {1.f, 1.f};
 #pragma unroll
-    for (int p = 0; p < PF; ++p) issue_w(p, kt0 + p);
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      a_fetch(c);
-      a_store(lds + c * ROWS * A_SLOT);
+      for (int r = 0; r < 4; ++r) {
+        const int mc = min(pass0 + mt * 16 + lq * 4 + r, M_e - 1);
+        out_row[mt][r] = off_e * T + mc;
+        sx_row[mt][r] = 1.f;
+        if constexpr (A8) sx_row[mt][r] = ga.a_scale[size_t(off_e) * T + mc];
+      }
+    if constexpr (!GATEUP) {
+      if (ga.y_perm != nullptr) {          // uniform branches: one sample per row group is the common case
+        if (T == 1) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out_row[mt][r] = ga.y_perm[out_row[mt][r]];
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int mc = out_row[mt][r] - off_e * T;
+              out_row[mt][r] = ga.y_perm[off_e + mc / T] * T + (mc % T);
+            }
+        }
+      }
     }
+    if constexpr (GM == GM_PC) {
+#pragma unroll
+      for (int s = 0; s < NS; ++s) pcs[s] = __uint_as_float(buf_load32(rsrc[s], lr * 4, ex.scale_off + uint32_t(nt_ld[s]) * 64u));
+    }
+
+    // ---- prologue: the first weight tile in flight, the first chunk of the activations into LDS; then the
+    // requests the first step expects behind it, in the order a step leaves them.  The waits of the loop are
+    // counts of requests still in flight, fixed when the kernel is compiled and valid for the way in from here
+    // as well as for the way round the loop: with any other order here, every step would wait for loads that
+    // the step before has only just requested.
+    issue_w(0, kt0);
+#pragma unroll
+    for (int c = 0; c < CH; c += 2) {
+      a_fetch(0, c);
+      if (c + 1 < CH) a_fetch(1, c + 1);
+      a_store(0, lds + c * ROWS * A_SLOT);
+      if (c + 1 < CH) a_store(1, lds + (c + 1) * ROWS * A_SLOT);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    a_fetch(0, CH);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int p = 1; p < PF; ++p) issue_w(p, kt0 + p);
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
 
-    // ---- main loop over the slice's k-tiles: while tile ti is multiplied, the activations of
-    // tile ti+CH (the same position in the next chunk) travel global -> registers -> the other
-    // LDS buffer, and weight tile ti+PF is requested.  U tiles per iteration so that the ring slot
-    // and the position inside the chunk are static; the work-group meets once per chunk.
-    // Tiles past the end of a shorter slice are skipped (uniform over the wave).
+    // ---- main loop over the slice's k-tiles: step ti requests the activations of tile ti+CH+1, multiplies
+    // tile ti, requests weight tile ti+PF and stores the activations of tile ti+CH (the same position in the next
+    // chunk, requested during the step before) into the other LDS buffer.  Loads complete in the order of their
+    // requests, so a wait for one of them is a wait for everything requested before it: with the activations
+    // requested a step ahead of their store, that wait covers only weight tiles that have been multiplied
+    // already, and the tiles requested last keep their full lead.  U tiles per iteration so that the ring
+    // slot, the register set and the position inside the chunk are static; the work-group meets once per
+    // chunk.  Tiles past the end of a shorter slice are skipped (uniform over the wave).
+    static_assert(U % 2 == 0, "the register set of the staged activations alternates with the step");
     auto step = [&](int ti, int i) {                        // i = ti % U, known at compile time where it matters
       const int cur = (ti / CH) & 1;
       uint8_t* const rd = lds + cur * buf_bytes + (i % CH) * ROWS * A_SLOT;
       uint8_t* const wr = lds + (cur ^ 1) * buf_bytes + (i % CH) * ROWS * A_SLOT;
-      a_fetch(ti + CH);
+      a_fetch((i + 1) & 1, ti + CH + 1);
       if (kt0 + ti < kt1) consume(i % PF, rd);
       issue_w(i % PF, kt0 + ti + PF);
-      a_store(wr);
+      a_store(i & 1, wr);
       if ((i + 1) % CH == 0) __syncthreads();
       __builtin_amdgcn_sched_barrier(0);                    // keep the steps apart: their temporaries must not pile up
     };
@@ -358,12 +426,6 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
     }
 
     if (ks == 0 && (sv[0] || sv[1])) {
-      float pcs[NS] = {1.f, 1.f};
-      if constexpr (GM == GM_PC) {
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-          if (sv[s]) pcs[s] = reinterpret_cast<const float*>(blob[s] + ex.scale_off)[nt[s] * 16 + lr];
-      }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -374,8 +436,7 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
               if constexpr (A8) {
-                const float sx = ga.a_scale[size_t(off_e) * T + m];
-                val[s] = float(__float_as_int(tot[s][mt][r])) * sx * pcs[s];
+                val[s] = float(__float_as_int(tot[s][mt][r])) * sx_row[mt][r] * pcs[s];
               } else if constexpr (GM == GM_PC) {
                 val[s] = (pcs[s] * INV_CM) * (tot[s][mt][r] - off_sym * xs_tot[mt][r]);
               } else {
@@ -389,8 +450,7 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
                 h[brow * size_t(ga.n) + nt[0] * 16 + lr] = float_to_bf16_rne(silu_mul(val[0], val[1]));
               }
             } else {
-              size_t drow = brow;
-              if (ga.y_perm) drow = size_t(ga.y_perm[off_e + m / T]) * T + (m % T);
+              const size_t drow = size_t(out_row[mt][r]);
               if (ga.y_bf16) {
                 uint16_t* y = static_cast<uint16_t*>(ga.y) + drow * size_t(ga.n);
                 if (sv[0]) y[nt[0] * 16 + lr] = float_to_bf16_rne(val[0]);
@@ -415,19 +475,24 @@ using namespace lds_stream;
 template <bool GATEUP, int WK>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_qgemm_stream_lds(const GemmArgs ga, const StreamLdsGeom geo) {
   extern __shared__ __align__(16) uint8_t lds[];
-  const int wg = blockIdx.x;
-  const int e = geo.order[wg / geo.wg_per_expert];
-  const int wgi = wg % geo.wg_per_expert;
+  // grid: x = work-group of the expert, y = the expert's place in `order` (no division, and nothing to wait for
+  // before the expert is known)
+  const int e = geo.order[blockIdx.y];
+  const int wgi = blockIdx.x;
   const ExpertDev& ex = ga.ex[e];
+  // the bucket's place is read here, before the branch on the format: its load travels together with the loads of
+  // the expert's description instead of after them
+  const int off_e = ga.offsets[e];
+  const int M_e = (ga.offsets[e + 1] - off_e) * ga.T;
   switch (ex.fmt * 4 + ex.gm) {
-    case FMT_I8 * 4 + GM_PC:     stream_lds_task<FMT_I8, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_I8A8 * 4 + GM_PC:   stream_lds_task<FMT_I8A8, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N6 * 4 + GM_PC:     stream_lds_task<FMT_N6, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_PC:     stream_lds_task<FMT_N4, GM_PC, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_G128:   stream_lds_task<FMT_N4, GM_G128, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N4 * 4 + GM_G64:    stream_lds_task<FMT_N4, GM_G64, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N3 * 4 + GM_G128:   stream_lds_task<FMT_N3, GM_G128, GATEUP, WK>(ga, ex, e, wgi, lds); break;
-    case FMT_N3 * 4 + GM_G64:    stream_lds_task<FMT_N3, GM_G64, GATEUP, WK>(ga, ex, e, wgi, lds); break;
+    case FMT_I8 * 4 + GM_PC:     stream_lds_task<FMT_I8, GM_PC, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
+    case FMT_I8A8 * 4 + GM_PC:   stream_lds_task<FMT_I8A8, GM_PC, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
+    case FMT_N6 * 4 + GM_PC:     stream_lds_task<FMT_N6, GM_PC, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_PC:     stream_lds_task<FMT_N4, GM_PC, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_G128:   stream_lds_task<FMT_N4, GM_G128, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
+    case FMT_N4 * 4 + GM_G64:    stream_lds_task<FMT_N4, GM_G64, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
+    case FMT_N3 * 4 + GM_G128:   stream_lds_task<FMT_N3, GM_G128, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
+    case FMT_N3 * 4 + GM_G64:    stream_lds_task<FMT_N3, GM_G64, GATEUP, WK>(ga, ex, off_e, M_e, wgi, lds); break;
     default: break;
   }
 }
@@ -450,7 +515,6 @@ int32_t launch_qgemm_stream_lds(const GemmArgs& ga, bool gateup, hipStream_t st)
   for (int i = 0; i < MOQE_MAX_EXPERTS; ++i) idx[i] = i;
   std::stable_sort(idx, idx + ga.n_experts, [&](int a, int b) { return ga.ex[a].tile_bytes > ga.ex[b].tile_bytes; });
   for (int i = 0; i < MOQE_MAX_EXPERTS; ++i) geo.order[i] = idx[i];
-  const unsigned grid = unsigned(geo.wg_per_expert) * unsigned(ga.n_experts);
   const int slot_bytes = (NS * MT + MT) * 4 * 64 * 4;
   int lds_bytes = LDS_BYTES;
   if (WAVES * slot_bytes > lds_bytes) lds_bytes = WAVES * slot_bytes;
@@ -460,7 +524,7 @@ int32_t launch_qgemm_stream_lds(const GemmArgs& ga, bool gateup, hipStream_t st)
   int32_t rc = ensure_dynamic_lds(LDSK_STREAM0 + 2 + ki, reinterpret_cast<const void*>(kernels[ki]), LDS_BYTES, "grouped_qgemm");
   if (rc) return rc;
   ProfileScope ps(gateup ? MOQE_PK_GEMM_GATEUP : MOQE_PK_GEMM_PLAIN, st, true);
-  ps.launch(kernels[ki], dim3(grid), dim3(WAVES * 64), lds_bytes, ga, geo);
+  ps.launch(kernels[ki], dim3(unsigned(geo.wg_per_expert), unsigned(ga.n_experts)), dim3(WAVES * 64), lds_bytes, ga, geo);
   return check_launch("grouped_qgemm");
 }
 

@@ -69,7 +69,6 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
   const int T = ga.T;
   constexpr int wk = WK;
   constexpr int WN = WAVES / WK;                // tasks per work-group
-  if (M_e <= 0 || M_e < ga.min_rows || M_e > ga.max_rows) return;     // uniform over the work-group (one expert per work-group)
 
   const int ks = wave % wk;
   const int task = wgi * WN + wave / wk;
@@ -97,6 +96,34 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
   // empty still run the loop on clamped addresses; their results are never stored
   const int nt_ld[NS] = {sv[0] ? nt[0] : 0, sv[1] ? nt[1] : 0};
   const int kt_last = max(kt0, kt1 - 1) < KT ? max(kt0, kt1 - 1) : KT - 1;
+
+  // ---- weight ring; its first tile is requested right here, before the bucket's size is looked at and before
+  // the staging plan: nothing in the request depends on them, and the tile is the longest wait of the set-up
+  uint32_t raw[PF][NS][NR];
+  float sc[PF][NS][GPT ? GPT : 1];
+  uint16_t zp[PF][NS];      // as loaded: widened where it is used, so that nothing between request and use touches it
+
+  auto issue_w = [&](int p, int kt_want) {
+    const int kt = min(kt_want, kt_last);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const uint32_t t = uint32_t(nt_ld[s]) * uint32_t(KT) + uint32_t(kt);          // uniform; byte offsets fit 32 bits
+      load_raw<FMT>(raw[p][s], rsrc[s], t * ex.tile_bytes, lane);
+      if constexpr (GPT > 0) {          // group formats are asymmetric: scale and zero-point per group
+        if constexpr (GPT == 1) {
+          sc[p][s][0] = __uint_as_float(buf_load32(rsrc[s], lr * 4, ex.scale_off + t * 64u));
+          zp[p][s] = uint16_t(__builtin_amdgcn_raw_buffer_load_b8(rsrc[s], lr, int(ex.zero_off + t * 16u), 0));
+        } else {
+          const u32x2 v = buf_load64(rsrc[s], lr * 8, ex.scale_off + t * 128u);
+          sc[p][s][0] = __uint_as_float(v.x); sc[p][s][1] = __uint_as_float(v.y);
+          zp[p][s] = uint16_t(__builtin_amdgcn_raw_buffer_load_b16(rsrc[s], lr * 2, int(ex.zero_off + t * 32u), 0));
+        }
+      }
+    }
+  };
+
+  issue_w(0, kt0);
+  if (M_e <= 0 || M_e < ga.min_rows || M_e > ga.max_rows) return;     // uniform over the work-group (one expert per work-group)
 
   // sum_k x (c - z) = (1/CM) * (sum_k x (BASE + CM c) - (BASE + CM z) sum_k x)
   constexpr float BASE = CodeMap<FMT>::BASE, CM = CodeMap<FMT>::CM, INV_CM = 1.f / CodeMap<FMT>::CM;
@@ -151,7 +178,7 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
       if (ALL_STAGE || u < n_units) {
         const int sl = u / (ROWS * upr), cu = u % upr;
         const int sk0 = min(sl * slice_tiles, KT - 1), sk1 = min(KT, sl * slice_tiles + slice_tiles);
-        uoff[i] = uint32_t((size_t(src_row[i]) * size_t(ga.k) + size_t(sk0) * 128) * EB + cu * 16);
+        uoff[i] = (uint32_t(src_row[i]) * uint32_t(ga.k) + uint32_t(sk0) * 128u) * uint32_t(EB) + uint32_t(cu) * 16u;   // < 4 GiB
         ukend[i] = max(sk1 - sk0 - 1, 0) * 128 * EB;      // offset of the slice's last tile
       }
     }
@@ -180,29 +207,6 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
 #pragma unroll
       for (int s = 0; s < NS; ++s) tot[s][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-
-    uint32_t raw[PF][NS][NR];
-    float sc[PF][NS][GPT ? GPT : 1];
-    uint16_t zp[PF][NS];      // as loaded: widened where it is used, so that nothing between request and use touches it
-
-    auto issue_w = [&](int p, int kt_want) {
-      const int kt = min(kt_want, kt_last);
-#pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        const uint32_t t = uint32_t(nt_ld[s]) * uint32_t(KT) + uint32_t(kt);          // uniform; byte offsets fit 32 bits
-        load_raw<FMT>(raw[p][s], rsrc[s], t * ex.tile_bytes, lane);
-        if constexpr (GPT > 0) {          // group formats are asymmetric: scale and zero-point per group
-          if constexpr (GPT == 1) {
-            sc[p][s][0] = __uint_as_float(buf_load32(rsrc[s], lr * 4, ex.scale_off + t * 64u));
-            zp[p][s] = uint16_t(__builtin_amdgcn_raw_buffer_load_b8(rsrc[s], lr, int(ex.zero_off + t * 16u), 0));
-          } else {
-            const u32x2 v = buf_load64(rsrc[s], lr * 8, ex.scale_off + t * 128u);
-            sc[p][s][0] = __uint_as_float(v.x); sc[p][s][1] = __uint_as_float(v.y);
-            zp[p][s] = uint16_t(__builtin_amdgcn_raw_buffer_load_b16(rsrc[s], lr * 2, int(ex.zero_off + t * 32u), 0));
-          }
-        }
-      }
-    };
 
     // One k-tile: activation operands come from LDS (tile `tl` of the current chunk buffer).
     auto consume = [&](int p, const uint8_t* abuf) {
@@ -334,12 +338,12 @@ static __device__ __forceinline__ void stream_lds_task(const GemmArgs& ga, const
       for (int s = 0; s < NS; ++s) pcs[s] = __uint_as_float(buf_load32(rsrc[s], lr * 4, ex.scale_off + uint32_t(nt_ld[s]) * 64u));
     }
 
-    // ---- prologue: the first weight tile in flight, the first chunk of the activations into LDS; then the
+    // ---- prologue: (the first weight tile is in flight) the first chunk of the activations into LDS; then the
     // requests the first step expects behind it, in the order a step leaves them.  The waits of the loop are
     // counts of requests still in flight, fixed when the kernel is compiled and valid for the way in from here
     // as well as for the way round the loop: with any other order here, every step would wait for loads that
     // the step before has only just requested.
-    issue_w(0, kt0);
+    if (pass0 > 0) issue_w(0, kt0);
 #pragma unroll
     for (int c = 0; c < CH; c += 2) {
       a_fetch(0, c);

@@ -30,12 +30,12 @@ MFMA_INT8_PEAK_TOPS = 5000.0    # dense int8, published
 # this file are handed to the kernel launch itself and read within about 5 % of the trace (2-3 us on the decode
 # kernel); `frac_rocprof` is the roofline fraction with the profiler's own average duration.  Tied to the kernel
 # sources like the traffic figure.
-_SOURCES_AT_PROFILE = "ee1e84767e733ab505f0d3fd9759ae01e18cf8f8c81f7de06670f5c27e35e308"
+_SOURCES_AT_PROFILE = "dcf0189ef39b2755e79e71524df5645bcd9531b4e9f357a8290ce5ecd6aefd8b"
 ROCPROF_KERNEL_US = {
-    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 49.95},
-    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1749.83},
-    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 10209.22},
-    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 95.19},
+    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 50.48},
+    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1750.62},
+    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 10142.79},
+    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 95.58},
 }
 
 
@@ -45,8 +45,8 @@ ROCPROF_KERNEL_US = {
 # their hash and is ignored (traffic = null) once they have changed.
 KERNEL_SOURCES = ("qgemm_stream.hip", "qgemm_stream_lds.hip", "qgemm_tile.hip", "qgemm_device.h")       # the GEMM kernels' own sources
 MEASURED_TRAFFIC = {
-    "llama7b_mlp_decode": {"sources_sha256": "ee1e84767e733ab505f0d3fd9759ae01e18cf8f8c81f7de06670f5c27e35e308",
-                           "bytes_per_launch": 232136909},   # fetch 230.21 MB + write 1.93 MB
+    "llama7b_mlp_decode": {"sources_sha256": "dcf0189ef39b2755e79e71524df5645bcd9531b4e9f357a8290ce5ecd6aefd8b",
+                           "bytes_per_launch": 232136704},   # fetch 230.21 MB + write 1.93 MB
 }
 
 

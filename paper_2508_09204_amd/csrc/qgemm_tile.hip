@@ -93,13 +93,22 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
   uint32_t a_off[A_ITERS];
   const int a_unit = tid % A_UNITS, a_row0 = tid / A_UNITS;
   uint32_t a_taps[CONV ? A_ITERS : 1];       // convolution: bit t set = filter tap t of the row's pixel lies inside its image
+  int32_t a_srow[A_ITERS];                   // source row of each copied row in the activation matrix
+#pragma unroll
+  for (int i = 0; i < A_ITERS; ++i)
+    a_srow[i] = off_e * T + min(m0 + a_row0 + i * A_ROWS_PER_IT, M_e - 1);      // rows past the bucket repeat its last row
+  if constexpr (!A8) {
+    if (ga.a_perm != nullptr) {              // uniform; all gather indices are requested before any of them is used
+      int32_t g[A_ITERS];
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i) g[i] = ga.a_perm[off_e + (a_srow[i] - off_e * T) / T];
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i) a_srow[i] = g[i] * T + (a_srow[i] - off_e * T) % T;
+    }
+  }
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
-    const int m = min(m0 + a_row0 + i * A_ROWS_PER_IT, M_e - 1);      // rows past the bucket repeat its last row
-    size_t src;
-    if constexpr (A8) src = size_t(off_e) * T + m;
-    else if (ga.a_perm) src = size_t(ga.a_perm[off_e + m / T]) * T + (m % T);
-    else src = size_t(off_e) * T + m;
+    const size_t src = size_t(a_srow[i]);
     if constexpr (CONV && !A8) {
       a_off[i] = uint32_t(src * size_t(ga.conv_c) * 2);              // byte offset of the pixel in the NHWC image
       const int p = int(src % size_t(T));
@@ -331,13 +340,33 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
     }
   };
 
-  // ---- prologue: k-step 0 of the activations into LDS, k-step 1 in registers, two weight steps in flight
-  a_fetch(0);
-  a_store(lds);
+  // factor that turns the accumulator into the result; per-channel scales are requested here, ahead of the main
+  // loop (these formats have no group scales in flight, so the registers are there), instead of at its end.
+  // Not for the convolution, whose gather leaves no register free: it asks for them after the loop.
+  constexpr bool FIN_EARLY = GM == GM_PC && !CONV;
+  float fin[TNB];
+  auto load_fin = [&]() {
+#pragma unroll
+    for (int b = 0; b < TNB; ++b)
+      fin[b] = nok[b] ? reinterpret_cast<const float*>(blob[b] + ex.scale_off)[ncol[b]] : 1.f;
+  };
+  if constexpr (FIN_EARLY) load_fin();
+
+  // ---- prologue: k-step 0 of the activations into LDS, k-step 1 in registers, two weight steps in flight.
+  // The requests are left in the order a step of the loop leaves them (weights of the step after next, then the
+  // next step's activations), with the first step's weights already there: the loop's waits are counts of requests
+  // in flight, fixed at compile time for both ways into the loop's head, and with any other order here every
+  // second step would wait for most of the weights requested half a step before.
   issue_w(0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  a_fetch(0);
+  a_store(lds);                                     // loads complete in request order: the weights of step 0 are there too
+  __builtin_amdgcn_sched_barrier(0);
   issue_w(1, 1);
+  __builtin_amdgcn_sched_barrier(0);
   a_fetch(1);
   __syncthreads();
+  __builtin_amdgcn_sched_barrier(0);
 
   // ---- main loop, two k-steps per iteration so that ring slot and LDS buffer are static ----------
   auto step = [&](int kt, int p) {
@@ -360,15 +389,11 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
   if (kt < KT) step(kt, 0);                         // uniform over the grid
 
   // ---- epilogue -----------------------------------------------------------------------------------------
-  float fin[TNB];                                   // factor that turns the accumulator into the result
+  if constexpr (GM != GM_PC) {
 #pragma unroll
-  for (int b = 0; b < TNB; ++b) {
-    if constexpr (GM == GM_PC) {
-      const uint8_t* bl = blob[b];
-      fin[b] = nok[b] ? reinterpret_cast<const float*>(bl + ex.scale_off)[ncol[b]] : 1.f;
-    } else {
-      fin[b] = s_cur[b] * INV_CM;
-    }
+    for (int b = 0; b < TNB; ++b) fin[b] = s_cur[b] * INV_CM;
+  } else if constexpr (!FIN_EARLY) {
+    load_fin();
   }
   // every wave is past its last operand read (the loop ends with a barrier): the staging buffer is free
   int32_t* row_tab = reinterpret_cast<int32_t*>(lds);

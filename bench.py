@@ -32,10 +32,10 @@ MFMA_INT8_PEAK_TOPS = 5000.0    # dense int8, published
 # sources like the traffic figure.
 _SOURCES_AT_PROFILE = "dcf0189ef39b2755e79e71524df5645bcd9531b4e9f357a8290ce5ecd6aefd8b"
 ROCPROF_KERNEL_US = {
-    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 50.48},
-    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1750.62},
-    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 10142.79},
-    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 95.58},
+    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 50.35},
+    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1742.35},
+    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 10020.58},
+    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 94.41},
 }
 
 
@@ -46,7 +46,7 @@ ROCPROF_KERNEL_US = {
 KERNEL_SOURCES = ("qgemm_stream.hip", "qgemm_stream_lds.hip", "qgemm_tile.hip", "qgemm_device.h")       # the GEMM kernels' own sources
 MEASURED_TRAFFIC = {
     "llama7b_mlp_decode": {"sources_sha256": "dcf0189ef39b2755e79e71524df5645bcd9531b4e9f357a8290ce5ecd6aefd8b",
-                           "bytes_per_launch": 232136704},   # fetch 230.21 MB + write 1.93 MB
+                           "bytes_per_launch": 232136499},   # fetch 230.21 MB + write 1.93 MB
 }
 
 

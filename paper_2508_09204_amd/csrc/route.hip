@@ -16,8 +16,10 @@ static __device__ __forceinline__ float wave_sum(float v) {
 
 // partial[s][c][d] = sum over the tokens of chunk c of x[s][t][d].
 // Block: 256 threads = CT column-threads (8 columns each) x TR token-rows.
+// With one chunk (C == 1, `finish` set) the sum is divided by T here and written as the pooled feature: the
+// arithmetic of k_pool_finish on a single chunk (0 + sum, then the division), without its launch.
 __global__ __launch_bounds__(256) void k_pool_partial(const uint16_t* __restrict__ x, float* __restrict__ partial,
-                                                       int T, int D, int C, int CT) {
+                                                       int T, int D, int C, int CT, int finish) {
   __shared__ float red[256 * 8];
   const int s = blockIdx.z, c = blockIdx.y;
   const int TR = 256 / CT;
@@ -30,12 +32,22 @@ __global__ __launch_bounds__(256) void k_pool_partial(const uint16_t* __restrict
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
   if (col < D) {
     const uint16_t* base = x + (size_t(s) * T) * D + col;
-    for (int t = t0 + tr; t < t1; t += TR) {
-      uint4 v = *reinterpret_cast<const uint4*>(base + size_t(t) * D);
-      acc[0] += bf16_bits_to_float(v.x & 0xffffu); acc[1] += bf16_bits_to_float(v.x >> 16);
-      acc[2] += bf16_bits_to_float(v.y & 0xffffu); acc[3] += bf16_bits_to_float(v.y >> 16);
-      acc[4] += bf16_bits_to_float(v.z & 0xffffu); acc[5] += bf16_bits_to_float(v.z >> 16);
-      acc[6] += bf16_bits_to_float(v.w & 0xffffu); acc[7] += bf16_bits_to_float(v.w >> 16);
+    // eight rows' loads in flight (rows past the chunk's end are clamped, loaded and not added); the additions keep
+    // their order
+    for (int t = t0 + tr; t < t1; t += 8 * TR) {
+      uint4 v4[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v4[u] = *reinterpret_cast<const uint4*>(base + size_t(min(t + u * TR, t1 - 1)) * D);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (t + u * TR < t1) {
+          const uint4 v = v4[u];
+          acc[0] += bf16_bits_to_float(v.x & 0xffffu); acc[1] += bf16_bits_to_float(v.x >> 16);
+          acc[2] += bf16_bits_to_float(v.y & 0xffffu); acc[3] += bf16_bits_to_float(v.y >> 16);
+          acc[4] += bf16_bits_to_float(v.z & 0xffffu); acc[5] += bf16_bits_to_float(v.z >> 16);
+          acc[6] += bf16_bits_to_float(v.w & 0xffffu); acc[7] += bf16_bits_to_float(v.w >> 16);
+        }
+      }
     }
   }
 #pragma unroll
@@ -47,7 +59,7 @@ __global__ __launch_bounds__(256) void k_pool_partial(const uint16_t* __restrict
     for (int i = 0; i < 8; ++i) {
       float v = 0.f;
       for (int r = 0; r < TR; ++r) v += red[(r * CT + ct) * 8 + i];   // fixed order
-      out[i] = v;
+      out[i] = finish ? __fdiv_rn(v, float(T)) : v;
     }
   }
 }
@@ -328,7 +340,9 @@ __global__ __launch_bounds__(256) void k_pool_ragged(const uint16_t* __restrict_
   *reinterpret_cast<float4*>(dst + 4) = o1;
 }
 
-static void pool_shape(int T, int D, int* C, int* CT) {
+// Chunks of a sample's tokens (C) and column-threads per work-group (CT).  A batch that fills the chip with one
+// work-group per sample and column block, and whose samples are short, is pooled in one chunk - and then in one launch.
+static void pool_shape(int S, int T, int D, int* C, int* CT) {
   int cols8 = D / 8;
   int ct = 1;
   while (ct < cols8 && ct < 256) ct <<= 1;
@@ -336,6 +350,7 @@ static void pool_shape(int T, int D, int* C, int* CT) {
   int c = T / 64;
   if (c < 1) c = 1;
   if (c > 16) c = 16;
+  if (T <= 256 && long(S) * ((cols8 + ct - 1) / ct) >= 256) c = 1;
   *C = c;
 }
 
@@ -343,7 +358,7 @@ static int hidden_slices(int D) { return (D + HID_KC - 1) / HID_KC; }
 
 size_t route_ws_bytes(int S, int T, const moqe_router& r) {
   int C, CT;
-  pool_shape(T, r.d, &C, &CT);
+  pool_shape(S, T, r.d, &C, &CT);
   size_t b = align256(size_t(S) * C * r.d * 4);                   // partial sums of the pooling
   b += align256(size_t(S) * r.d * 4);                             // pooled features
   b += align256(size_t(hidden_slices(r.d)) * S * (r.h > 0 ? r.h : 1) * 4);   // hidden layer, one slab per k-slice
@@ -356,7 +371,7 @@ struct RouteFeat { const float* feat; int nslices; size_t stride; int Dk; };
 static int32_t route_front(const void* x, const int32_t* cu_rows, int S, int T, const moqe_router& r, void* ws, hipStream_t st,
                            RouteFeat* rf) {
   int C, CT;
-  pool_shape(T, r.d, &C, &CT);
+  pool_shape(S, T, r.d, &C, &CT);
   const int D = r.d;
   uint8_t* p = static_cast<uint8_t*>(ws);
   float* partial = reinterpret_cast<float*>(p);
@@ -373,9 +388,10 @@ static int32_t route_front(const void* x, const int32_t* cu_rows, int S, int T, 
     {
       ProfileScope ps(MOQE_PK_ROUTE, st);
       dim3 grid((D / 8 + CT - 1) / CT, C, S);
-      hipLaunchKernelGGL(k_pool_partial, grid, dim3(256), 0, st, static_cast<const uint16_t*>(x), partial, T, D, C, CT);
+      hipLaunchKernelGGL(k_pool_partial, grid, dim3(256), 0, st, static_cast<const uint16_t*>(x), C == 1 ? pooled : partial, T, D, C,
+                         CT, C == 1 ? 1 : 0);
     }
-    {
+    if (C > 1) {
       ProfileScope ps(MOQE_PK_ROUTE, st);
       size_t nel = size_t(S) * D;
       hipLaunchKernelGGL(k_pool_finish, dim3(unsigned((nel + 255) / 256)), dim3(256), 0, st, partial, pooled, S, T, D, C);
@@ -409,7 +425,7 @@ int32_t launch_route_features(const float* feat, int S, const moqe_router& r, in
   RouteFeat rf{feat, 0, 0, r.d};
   if (r.h > 0) {
     int C, CT;
-    pool_shape(1, r.d, &C, &CT);
+    pool_shape(S, 1, r.d, &C, &CT);
     float* hidden = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + align256(size_t(S) * C * r.d * 4) + align256(size_t(S) * r.d * 4));
     const int KS = hidden_slices(r.d);
     ProfileScope ps(MOQE_PK_ROUTE, st);

@@ -30,12 +30,12 @@ MFMA_INT8_PEAK_TOPS = 5000.0    # dense int8, published
 # this file are handed to the kernel launch itself and read within about 5 % of the trace (2-3 us on the decode
 # kernel); `frac_rocprof` is the roofline fraction with the profiler's own average duration.  Tied to the kernel
 # sources like the traffic figure.
-_SOURCES_AT_PROFILE = "dcf0189ef39b2755e79e71524df5645bcd9531b4e9f357a8290ce5ecd6aefd8b"
+_SOURCES_AT_PROFILE = "fcee4361dc2eceee815b53fbf9630a367ad61f4fc1f5c724897bac7c85ca4a88"
 ROCPROF_KERNEL_US = {
-    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 50.35},
-    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1742.35},
-    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 10020.58},
-    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 94.41},
+    "llama7b_mlp_decode": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 49.62},
+    "llama7b_mlp_prefill": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 1717.04},
+    "qwen_mlp_skew": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 9932.68},
+    "resnet50_conv": {"sources_sha256": _SOURCES_AT_PROFILE, "kernel_us": 93.47},
 }
 
 
@@ -45,8 +45,8 @@ ROCPROF_KERNEL_US = {
 # their hash and is ignored (traffic = null) once they have changed.
 KERNEL_SOURCES = ("qgemm_stream.hip", "qgemm_stream_lds.hip", "qgemm_tile.hip", "qgemm_device.h")       # the GEMM kernels' own sources
 MEASURED_TRAFFIC = {
-    "llama7b_mlp_decode": {"sources_sha256": "dcf0189ef39b2755e79e71524df5645bcd9531b4e9f357a8290ce5ecd6aefd8b",
-                           "bytes_per_launch": 232136499},   # fetch 230.21 MB + write 1.93 MB
+    "llama7b_mlp_decode": {"sources_sha256": "fcee4361dc2eceee815b53fbf9630a367ad61f4fc1f5c724897bac7c85ca4a88",
+                           "bytes_per_launch": 232140493},   # fetch 230.21 MB + write 1.93 MB
 }
 
 

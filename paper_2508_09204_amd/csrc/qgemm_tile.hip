@@ -94,24 +94,28 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
   const int a_unit = tid % A_UNITS, a_row0 = tid / A_UNITS;
   uint32_t a_taps[CONV ? A_ITERS : 1];       // convolution: bit t set = filter tap t of the row's pixel lies inside its image
   int32_t a_srow[A_ITERS];                   // source row of each copied row in the activation matrix
+  int32_t a_rin[A_ITERS];                    // the row's place inside its sample (0 when samples have one row)
+  const bool one_row = T == 1;               // uniform: the divisions below are some forty instructions each
 #pragma unroll
-  for (int i = 0; i < A_ITERS; ++i)
-    a_srow[i] = off_e * T + min(m0 + a_row0 + i * A_ROWS_PER_IT, M_e - 1);      // rows past the bucket repeat its last row
+  for (int i = 0; i < A_ITERS; ++i) {
+    const int m = min(m0 + a_row0 + i * A_ROWS_PER_IT, M_e - 1);      // rows past the bucket repeat its last row
+    const int smp = one_row ? m : m / T;
+    a_rin[i] = one_row ? 0 : m - smp * T;
+    a_srow[i] = off_e + smp;                 // the sample, for now
+  }
   if constexpr (!A8) {
     if (ga.a_perm != nullptr) {              // uniform; all gather indices are requested before any of them is used
-      int32_t g[A_ITERS];
 #pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) g[i] = ga.a_perm[off_e + (a_srow[i] - off_e * T) / T];
-#pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) a_srow[i] = g[i] * T + (a_srow[i] - off_e * T) % T;
+      for (int i = 0; i < A_ITERS; ++i) a_srow[i] = ga.a_perm[a_srow[i]];
     }
   }
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
-    const size_t src = size_t(a_srow[i]);
+    a_srow[i] = a_srow[i] * T + a_rin[i];
+    // each matrix is smaller than 4 GiB: 32-bit byte offsets
     if constexpr (CONV && !A8) {
-      a_off[i] = uint32_t(src * size_t(ga.conv_c) * 2);              // byte offset of the pixel in the NHWC image
-      const int p = int(src % size_t(T));
+      a_off[i] = uint32_t(a_srow[i]) * uint32_t(ga.conv_c) * 2u;     // byte offset of the pixel in the NHWC image
+      const int p = a_rin[i];                                         // the pixel inside its image
       const int py = p / ga.conv_w, px = p - py * ga.conv_w;
       uint32_t taps = 0;
 #pragma unroll
@@ -121,7 +125,7 @@ static __device__ __forceinline__ void tile_task(const GemmArgs& ga, const TileG
       }
       a_taps[i] = taps;
     } else {
-      a_off[i] = uint32_t(src * size_t(ga.k) * EB + a_unit * 16);
+      a_off[i] = uint32_t(a_srow[i]) * uint32_t(ga.k) * uint32_t(EB) + uint32_t(a_unit) * 16u;
     }
   }
   // Where each of the tile's rows goes (and, for int8 activations, its scale): worked out now by the
